@@ -1,0 +1,197 @@
+#!/usr/bin/env python3
+"""Throughput of the contraction on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 3] [--no-tune] [--no-cpu]
+
+One "step" is one call of the library on one batch of synthetic input: shape split,
+tile-config selection, operand staging, MFMA inner product and epilogue.  The default
+workload is the fp32 GEMM M=N=K=4096 (entries N(0,1)/64, seed 2); inputs are resident in
+HBM before the timed region.  Prints ONE JSON line on stdout; everything else goes to
+stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# published dense peaks of the part (TFLOP/s), by the arithmetic type of the contraction
+PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
+METRIC = "TFLOP/s and % of MI355X matrix peak, fp32 GEMM 4096^3 (1 GPU)"
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def workload_flops(c) -> int:
+    """Algorithmic flop count: 2 per multiply-add; convolution taps that fall in the zero
+    padding are not work."""
+    if c["op"] != "conv2d_nhwc":
+        return 2 * c["M"] * c["N"] * c["K"]
+
+    def valid(L, Kk, s, p):
+        Lo = (L + 2 * p - Kk) // s + 1
+        return sum(1 for o in range(Lo) for t in range(Kk) if 0 <= o * s + t - p < L)
+
+    return (2 * c["N"] * valid(c["H"], c["KH"], c["stride"], c["pad"]) *
+            valid(c["W"], c["KW"], c["stride"], c["pad"]) * c["Cin"] * c["Cout"])
+
+
+def describe(k, c) -> str:
+    if c["op"] == "conv2d_nhwc":
+        return ("cfg%d: %s conv2d NHWC N=%d H=W=%d Cin=%d Cout=%d %dx%d stride %d pad %d, seed %d"
+                % (k, c["dtype"], c["N"], c["H"], c["Cin"], c["Cout"], c["KH"], c["KW"], c["stride"], c["pad"],
+                   c["seed"]))
+    return "cfg%d: %s %s M=%d N=%d K=%d, %s entries, seed %d%s" % (
+        k, c["dtype"], c["op"], c["M"], c["N"], c["K"], c["dist"], c["seed"],
+        ", negate fused" if "negate" in c["flags"] else "")
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", type=int, default=3, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--no-tune", action="store_true", help="use the shape heuristic instead of the tuner")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--cpu-rows", type=int, default=1024, help="rows of the product the oracle is timed on")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU; --gpus %d is not supported "
+            "(the contraction shards by rows of C with no exchange, see DESIGN.md)." % args.gpus)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import synth
+    import paper_2409_03864_amd as tsg
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        return 3
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    k = args.workload
+    t0 = time.time()
+    c, a, b = synth.config_inputs(k)
+    log("inputs generated in %.1f s: %s" % (time.time() - t0, describe(k, c)))
+    dt = tsg.F32 if c["dtype"] == "f32" else tsg.BF16_F32ACC
+    flags = tsg.NEGATE if "negate" in c["flags"] else 0
+
+    def up(x):
+        x = np.ascontiguousarray(x)
+        return torch.from_numpy(x.view(np.int16) if x.dtype == np.uint16 else x).to(dev)
+
+    dA, dB = up(a), up(b)
+    if c["op"] == "conv2d_nhwc":
+        Ho = (c["H"] + 2 * c["pad"] - c["KH"]) // c["stride"] + 1
+        dC = torch.zeros((c["N"], Ho, Ho, c["Cout"]), dtype=torch.float32, device=dev)
+        geom = (c["N"], c["H"], c["W"], c["Cin"], c["Cout"], c["KH"], c["KW"], c["stride"], c["stride"],
+                c["pad"], c["pad"])
+        op = tsg.OP_CONV2D_NHWC
+        M, N, K = c["N"] * Ho * Ho, c["Cout"], c["KH"] * c["KW"] * c["Cin"]
+
+        def step():
+            tsg.conv2d_nhwc(dt, *geom, dA, dB, dC, flags)
+
+        def tune():
+            return tsg.autotune_conv2d_nhwc(dt, *geom, dA, dB, dC, flags, iters=5)
+    else:
+        M, N, K = c["M"], c["N"], c["K"]
+        trans = c["op"] == "gemm_transA"
+        op = tsg.OP_GEMM_TRANSA if trans else tsg.OP_GEMM
+        dC = torch.zeros((M, N), dtype=torch.float32, device=dev)
+        lda = M if trans else K
+        fn = tsg.gemm_transA if trans else tsg.gemm
+
+        def step():
+            fn(dt, M, N, K, dA, lda, dB, N, dC, N, flags)
+
+        def tune():
+            return tsg.autotune_gemm(dt, trans, M, N, K, dA, lda, dB, N, dC, N, flags, iters=5)
+
+    tuner_log = None
+    if not args.no_tune:
+        best, best_ms, recs = tune()
+        tuner_log = [dict(r.config.as_dict(), ms=round(r.ms, 5)) for r in recs]
+        for r in recs:
+            log("  tuner: %s -> %.4f ms (best so far %.4f)" % (r.config, r.ms, r.best_ms))
+        log("tuner picked %s at %.4f ms" % (best, best_ms))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # whole-step wall clock, and per-launch device time from events on the launch stream
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for e0, e1 in evs:
+        e0.record()
+        step()
+        e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    li = tsg.last_launch()
+    kern_ms = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+    avg_kern_ms = sum(kern_ms) / len(kern_ms)
+
+    flops = workload_flops(c)
+    ms_per_step = wall * 1e3 / args.steps
+    value = flops / (wall / args.steps) / 1e12
+    peak = PEAK_TFLOPS[c["dtype"]]
+    achieved = flops / (avg_kern_ms * 1e-3) / 1e12
+    log("step %.4f ms wall, kernel avg %.4f ms (median %.4f, min %.4f): %.2f TFLOP/s = %.1f%% of %.1f"
+        % (ms_per_step, avg_kern_ms, kern_ms[len(kern_ms) // 2], kern_ms[0], achieved, 100 * achieved / peak, peak))
+
+    cpu = None
+    if not args.no_cpu:
+        import oracle
+        if c["op"] == "conv2d_nhwc":
+            xs = a[:1]
+            t0 = time.perf_counter()
+            oracle.conv2d_nhwc(xs, b, stride=(c["stride"],) * 2, pad=(c["pad"],) * 2, with_s=False)
+            dtc = time.perf_counter() - t0
+            sflops, sample = flops // c["N"], "image 0 of %d (direct convolution)" % c["N"]
+        else:
+            rows = min(args.cpu_rows, M)
+            sub = np.ascontiguousarray(a[:, :rows] if c["op"] == "gemm_transA" else a[:rows])
+            t0 = time.perf_counter()
+            oracle.gemm(sub, b, trans_a=(c["op"] == "gemm_transA"), with_s=False)
+            dtc = time.perf_counter() - t0
+            sflops, sample = 2 * rows * N * K, "rows 0..%d of C (%d x %d x %d triple loop)" % (rows - 1, rows, N, K)
+        cpu = {"value": sflops / dtc / 1e12, "unit": "TFLOP/s", "cores": oracle.threads(), "kind": "oracle",
+               "sample": sample, "seconds": round(dtc, 3)}
+        log("cpu oracle: %s in %.2f s on %d threads = %.4f TFLOP/s" % (sample, dtc, cpu["cores"], cpu["value"]))
+
+    out = {
+        "metric": METRIC if k == 3 else "TFLOP/s and % of MI355X matrix peak, " + describe(k, c),
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": c["dtype"], "data": "synthetic",
+        "pct_of_peak": 100.0 * value / peak,
+        "config": {"workload": describe(k, c), "M": M, "N": N, "K": K, "flops_per_step": flops,
+                   "tile_config": li.config.as_dict(), "alternative": int(li.alternative),
+                   "tuned": not args.no_tune},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+                     "frac": achieved / peak, "traffic": None,
+                     "kernel_ms_avg": avg_kern_ms, "kernel_ms_min": kern_ms[0]},
+        "cpu_baseline": cpu,
+    }
+    if tuner_log is not None:
+        out["tuner_log"] = tuner_log
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

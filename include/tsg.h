@@ -1,0 +1,206 @@
+/*
+ * tsg -- tile-scheduled dense contraction for AMD CDNA4 (gfx950), C ABI.
+ *
+ * The library computes the loop nest that the paper's schedules optimise
+ * (Case Study 4, Fig. 7):
+ *
+ *        C[i][j] (+)= sum_k op(A)[i][k] * B[k][j]
+ *
+ * with the rewrites of Case Study 3 folded into addressing instead of being
+ * materialised: a transposed left operand is read in place (tsg_gemm_transA), a
+ * negate is applied in the store epilogue (TSG_NEGATE), and elements produced by
+ * zero padding are never formed, read or added (tsg_conv2d_nhwc, an implicit
+ * GEMM over M = N*Ho*Wo, N = Cout, K = KH*KW*Cin with k ordered (kh, kw, ci)).
+ * The knobs of the schedule -- tile sizes per loop, the vectorise flag and their
+ * legality constraints (Case Study 5, Fig. 9 and Fig. 10), the split of a loop
+ * into a divisible main part and a remainder (Fig. 1, Fig. 8) -- are data:
+ * tsg_tile_config and tsg_split.
+ *
+ * Conventions for every entry point
+ *  - All matrices are row-major.  Leading dimensions are in ELEMENTS.
+ *  - Pointers named A, B, C, x, w, y are DEVICE pointers owned by the caller; the
+ *    library never allocates, frees or retains them.  C / y must not overlap the
+ *    inputs.  Pointers named `out`, `off`, `log` ... are HOST pointers.
+ *  - Compute calls only enqueue work on `stream` (a hipStream_t passed as void*,
+ *    NULL = the default stream) and return; they never synchronise.
+ *  - Error model (Sec. 3, silenceable vs. definite errors; Case Study 4,
+ *    `alternatives`): TSG_E_SILENCEABLE means a precondition of the requested
+ *    schedule failed; NOTHING was enqueued and no output byte was touched, so the
+ *    caller may try another alternative.  TSG_E_INVALID and TSG_E_RUNTIME are
+ *    definite.  Without TSG_STRICT a compute call walks its own chain of
+ *    alternatives (config set by the caller -> shape heuristic -> scalar-access
+ *    fallback of the same tile) and only fails definitely.
+ *  - Extents must fit in int32 (each of M, N, K, and every tensor's element count
+ *    for convolution); larger values are TSG_E_INVALID.
+ *  - The config registry is guarded by a mutex; compute calls are re-entrant.
+ */
+#ifndef TSG_H
+#define TSG_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    TSG_OK = 0,
+    TSG_E_SILENCEABLE = 1, /* precondition failed, nothing modified (Sec. 3) */
+    TSG_E_INVALID = 2,     /* definite: null pointer, bad extent / ld / enum */
+    TSG_E_RUNTIME = 3      /* definite: HIP launch or runtime failure */
+} tsg_status;
+
+typedef enum {
+    TSG_F32 = 0,        /* fp32 operands, fp32 MFMA accumulate */
+    TSG_BF16_F32ACC = 1 /* bfloat16 operands (bit patterns), fp32 accumulate; C is fp32 */
+} tsg_dtype;
+
+typedef enum { TSG_OP_GEMM = 0, TSG_OP_GEMM_TRANSA = 1, TSG_OP_CONV2D_NHWC = 2 } tsg_op;
+
+/* flags of the compute calls */
+enum {
+    TSG_NEGATE = 1u,     /* C = -(op(A).B): the negate sunk into the epilogue (Case Study 3) */
+    TSG_ACCUMULATE = 2u, /* C += ... : the `+=` of Fig. 7; without it C is overwritten */
+    TSG_STRICT = 4u      /* use exactly the config set by tsg_tile_config_set or fail silenceably */
+};
+
+/*
+ * The tuning parameters of Fig. 9 / Fig. 10 as they exist on this hardware.
+ *   bm, bn, bk : workgroup tile of the i, j and k loops (tile1..tile3 of Fig. 10; the
+ *                batch loop is not tiled).  0 = "library default for this loop" (tiling
+ *                by 0 is a no-op, Sec. 3.4).  A tile larger than the extent is legal:
+ *                the whole loop becomes remainder.
+ *   wm, wn     : per-wavefront sub-tile (multiples of the 32x32 MFMA block).
+ *   vec        : elements per global access along the contiguous dimension, the
+ *                paper's `vect`: 1, or 4 (fp32) / 8 (bf16) = 16-byte accesses.  Legal
+ *                only if every operand's leading dimension is a multiple of vec and
+ *                its base pointer is 16-byte aligned (Fig. 10: vect = 0 unless the
+ *                innermost extent is divisible by the vector size).
+ *   raster     : 0 = tiles in row-major order, 1 = XCD-aware grouped order.
+ */
+typedef struct {
+    int32_t bm, bn, bk;
+    int32_t wm, wn;
+    int32_t vec;
+    int32_t raster;
+    int32_t reserved;
+} tsg_tile_config;
+
+/* What the most recent compute call on the calling thread enqueued. */
+typedef struct {
+    tsg_tile_config config; /* config actually used */
+    int32_t alternative;    /* 0 = caller's config, 1 = heuristic, 2 = scalar-access fallback */
+    int32_t launches;       /* kernels enqueued */
+    int32_t edge;           /* 1 if a remainder (masked) path was compiled into the launch */
+    int32_t tiles_m, tiles_n;
+    int64_t m_main, m_rest, n_main, n_rest, k_main, k_rest; /* the split (Fig. 8) */
+} tsg_launch_info;
+
+/* One evaluation of the tuner (Case Study 5, Fig. 11: runtime per evaluated point). */
+typedef struct {
+    tsg_tile_config config;
+    float ms;        /* median time of one call; < 0 if the config was illegal here */
+    float best_ms;   /* best so far, including this evaluation */
+} tsg_tune_record;
+
+/* ---- compute (device pointers, asynchronous) ---------------------------------- */
+
+/* C[M x N] = +-(A[M x K] . B[K x N]) (+ C).  Fig. 7 without the batch loop.
+ * lda >= K, ldb >= N, ldc >= N.  A, B: float (TSG_F32) or uint16 bfloat16 bits. */
+tsg_status tsg_gemm(tsg_dtype dtype, int64_t M, int64_t N, int64_t K,
+                    const void *A, int64_t lda, const void *B, int64_t ldb,
+                    float *C, int64_t ldc, uint32_t flags, void *stream);
+
+/* Same with the left operand stored transposed: A is K x M row-major (lda >= M) and
+ * op(A) = A^T is read in place (Case Study 3, transpose folded into the matmul). */
+tsg_status tsg_gemm_transA(tsg_dtype dtype, int64_t M, int64_t N, int64_t K,
+                           const void *A, int64_t lda, const void *B, int64_t ldb,
+                           float *C, int64_t ldc, uint32_t flags, void *stream);
+
+/* Batched form of Fig. 7: `batch` independent products, operand b at base + b*stride
+ * (strides in elements; stride 0 broadcasts an input). */
+tsg_status tsg_gemm_batched(tsg_dtype dtype, int32_t trans_a, int64_t batch,
+                            int64_t M, int64_t N, int64_t K,
+                            const void *A, int64_t lda, int64_t stride_a,
+                            const void *B, int64_t ldb, int64_t stride_b,
+                            float *C, int64_t ldc, int64_t stride_c,
+                            uint32_t flags, void *stream);
+
+/* y[N][Ho][Wo][Cout] = +-conv(x[N][H][W][Cin], w[KH][KW][Cin][Cout]) (+ y), zero
+ * padding (pad_h, pad_w) never materialised; Ho = (H + 2*pad_h - KH)/stride_h + 1. */
+tsg_status tsg_conv2d_nhwc(tsg_dtype dtype, int64_t N, int64_t H, int64_t W, int64_t Cin,
+                           int64_t Cout, int64_t KH, int64_t KW,
+                           int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
+                           const void *x, const void *w, float *y,
+                           uint32_t flags, void *stream);
+
+/* ---- schedule parameters (host only; no GPU needed) --------------------------- */
+
+/* Loop split of Fig. 1 / Fig. 8: main = largest multiple of d <= ub, rest = ub - main
+ * (< d), tiles = main / d.  d == 0 leaves the loop whole (main = ub, one tile).
+ * TSG_E_INVALID for ub < 0, d < 0 or null outputs. */
+tsg_status tsg_split(int64_t ub, int64_t d, int64_t *main_part, int64_t *rest, int64_t *tiles);
+
+/* Size of the instantiated search space and its idx-th point. */
+int32_t tsg_tile_config_count(tsg_op op, tsg_dtype dtype);
+tsg_status tsg_tile_config_enum(tsg_op op, tsg_dtype dtype, int32_t idx, tsg_tile_config *out);
+
+/* Legality of a config for a problem with natural leading dimensions and aligned
+ * pointers.  For convolution pass the implicit extents and Cin as `contig`
+ * (the contiguous run of the gathered operand); for GEMM contig is ignored.
+ * TSG_E_SILENCEABLE if the tile is not instantiated or `vec` violates Fig. 10's
+ * divisibility rule; TSG_E_INVALID for malformed arguments. */
+tsg_status tsg_tile_config_check(tsg_op op, tsg_dtype dtype, int64_t M, int64_t N, int64_t K,
+                                 int64_t contig, const tsg_tile_config *cfg);
+
+/* Pin the config used by later calls of (op, dtype); NULL clears the pin.
+ * Zero fields are filled from the default.  Validates instantiation first:
+ * on TSG_E_SILENCEABLE the registry is unchanged. */
+tsg_status tsg_tile_config_set(tsg_op op, tsg_dtype dtype, const tsg_tile_config *cfg);
+
+/* The config a call with these extents would try first right now. */
+tsg_status tsg_tile_config_get(tsg_op op, tsg_dtype dtype, int64_t M, int64_t N, int64_t K,
+                               tsg_tile_config *out);
+
+/* Details of the last compute call made by the calling thread. */
+tsg_status tsg_last_launch(tsg_launch_info *out);
+
+/* ---- index maps (host only, integer, compared bit-exactly) -------------------- */
+
+/* off[m*KH*KW + kh*KW + kw] = element offset of x[n][hi][wi][0] for output pixel
+ * m = (n*Ho + ho)*Wo + wo, hi = ho*stride_h + kh - pad_h, wi likewise; -1 where the
+ * tap falls in the zero padding.  `off` is a HOST array of N*Ho*Wo*KH*KW int32. */
+tsg_status tsg_conv2d_index_map(int64_t N, int64_t H, int64_t W, int64_t Cin,
+                                int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
+                                int64_t pad_h, int64_t pad_w, int32_t *off);
+
+/* off[i*K + k] = element offset of op(A)(i,k): i*lda + k, or k*lda + i if trans_a. */
+tsg_status tsg_gemm_index_map(int32_t trans_a, int64_t M, int64_t K, int64_t lda, int64_t *off);
+
+/* ---- search (Case Study 5) ----------------------------------------------------- */
+
+/* Time every legal instantiated config on the caller's buffers (`iters` calls each,
+ * after one warm-up), keep the fastest and pin it with tsg_tile_config_set.  This
+ * call SYNCHRONISES the stream and overwrites C / y.  `log` (host, may be NULL)
+ * receives up to log_cap records in evaluation order; *n_log the number written. */
+tsg_status tsg_autotune_gemm(tsg_dtype dtype, int32_t trans_a, int64_t M, int64_t N, int64_t K,
+                             const void *A, int64_t lda, const void *B, int64_t ldb,
+                             float *C, int64_t ldc, uint32_t flags, void *stream, int32_t iters,
+                             tsg_tile_config *best, float *best_ms,
+                             tsg_tune_record *log, int32_t log_cap, int32_t *n_log);
+
+tsg_status tsg_autotune_conv2d_nhwc(tsg_dtype dtype, int64_t N, int64_t H, int64_t W, int64_t Cin,
+                                    int64_t Cout, int64_t KH, int64_t KW,
+                                    int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
+                                    const void *x, const void *w, float *y,
+                                    uint32_t flags, void *stream, int32_t iters,
+                                    tsg_tile_config *best, float *best_ms,
+                                    tsg_tune_record *log, int32_t log_cap, int32_t *n_log);
+
+const char *tsg_status_string(tsg_status s);
+int32_t tsg_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TSG_H */

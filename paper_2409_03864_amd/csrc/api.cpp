@@ -1,0 +1,488 @@
+// C-ABI layer: argument validation, the loop split, the tile-config registry with its
+// legality rules, the chain of alternatives, launch planning and the tuner.
+// Host code only; the kernels live in gemm_f32.hip and gemm_bf16.hip.
+#include <algorithm>
+#include <cstring>
+#include <mutex>
+#include <vector>
+
+#include "../../include/tsg.h"
+#include "tsg_internal.h"
+
+namespace {
+
+using tsg::KArgs;
+using tsg::KernelEntry;
+
+constexpr int kNumOps = 3, kNumDtypes = 2;
+constexpr int kCUs = 256;
+
+struct Problem {
+    tsg_op op;
+    tsg_dtype dtype;
+    int64_t batch = 1;
+    int64_t M, N, K;
+    const void* A;
+    const void* B;
+    float* C;
+    int64_t lda, ldb, ldc;
+    int64_t stride_a = 0, stride_b = 0, stride_c = 0;
+    uint32_t flags;
+    // convolution geometry
+    int64_t H = 0, W = 0, Cin = 0, Ho = 0, Wo = 0, KH = 0, KW = 0, sh = 1, sw = 1, ph = 0, pw = 0;
+};
+
+std::mutex g_mu;
+bool g_pinned[kNumOps][kNumDtypes];
+tsg_tile_config g_pin[kNumOps][kNumDtypes];
+thread_local tsg_launch_info t_last;
+
+const KernelEntry* kernels(tsg_dtype dt, int* n) {
+    return dt == TSG_F32 ? tsg::f32_kernels(n) : tsg::bf16_kernels(n);
+}
+
+int elem_size(tsg_dtype dt) { return dt == TSG_F32 ? 4 : 2; }
+int vec_max(tsg_dtype dt) { return 16 / elem_size(dt); }
+
+bool valid_op(int op) { return op >= 0 && op < kNumOps; }
+bool valid_dtype(int dt) { return dt >= 0 && dt < kNumDtypes; }
+
+const KernelEntry* find_entry(tsg_dtype dt, const tsg_tile_config& c) {
+    int n = 0;
+    const KernelEntry* t = kernels(dt, &n);
+    for (int i = 0; i < n; ++i)
+        if (t[i].bm == c.bm && t[i].bn == c.bn && t[i].bk == c.bk && t[i].wm == c.wm && t[i].wn == c.wn)
+            return &t[i];
+    return nullptr;
+}
+
+tsg_tile_config config_of(const KernelEntry& e, int vec, int raster) {
+    tsg_tile_config c;
+    c.bm = e.bm; c.bn = e.bn; c.bk = e.bk; c.wm = e.wm; c.wn = e.wn;
+    c.vec = vec; c.raster = raster; c.reserved = 0;
+    return c;
+}
+
+// Shape heuristic: estimated time ~ (rounds of workgroups over the CUs) x tile area /
+// (relative efficiency of the tile); the first table entry with the lowest estimate wins.
+tsg_tile_config heuristic(tsg_dtype dt, int64_t batch, int64_t M, int64_t N, int64_t K) {
+    (void)K;
+    int n = 0;
+    const KernelEntry* t = kernels(dt, &n);
+    double best = 0;
+    int best_i = 0;
+    for (int i = 0; i < n; ++i) {
+        const double tiles = (double)((M + t[i].bm - 1) / t[i].bm) * (double)((N + t[i].bn - 1) / t[i].bn) * (double)batch;
+        const double rounds = std::max(1.0, (double)(int64_t)((tiles + kCUs - 1) / kCUs));
+        const double area = (double)t[i].bm * t[i].bn;
+        // larger wave tiles reuse each LDS fragment more often
+        const double eff = 1.0 - 8.0 / (t[i].wm + t[i].wn) - 2.0 / t[i].bk;
+        const double est = rounds * area / eff;
+        if (i == 0 || est < best * 0.999) { best = est; best_i = i; }
+    }
+    return config_of(t[best_i], vec_max(dt), 1);
+}
+
+// Fill zero fields ("tiling by 0 is a no-op": the library default stands) from `def`.
+tsg_tile_config fill_defaults(tsg_tile_config c, const tsg_tile_config& def) {
+    const bool tile_given = c.bm > 0 || c.bn > 0 || c.bk > 0 || c.wm > 0 || c.wn > 0;
+    if (c.bm <= 0) c.bm = def.bm;
+    if (c.bn <= 0) c.bn = def.bn;
+    if (c.bk <= 0) c.bk = def.bk;
+    if (!tile_given) { c.wm = def.wm; c.wn = def.wn; }
+    if (c.wm <= 0) c.wm = std::min(c.bm, 64);
+    if (c.wn <= 0) c.wn = std::min(c.bn, 64);
+    if (c.vec <= 0) c.vec = def.vec;
+    if (c.raster < 0) c.raster = def.raster;
+    c.reserved = 0;
+    return c;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Fig. 10's rule for `vect` on this hardware: wide accesses need every contiguous run to
+// start on a 16-byte boundary, i.e. leading dimensions (and Cin / Cout for the gathered
+// operand) divisible by the vector size and aligned bases.
+bool vec_legal(const Problem& p, int vec) {
+    if (vec == 1) return true;
+    if (vec != vec_max(p.dtype)) return false;
+    if (!aligned16(p.A) || !aligned16(p.B)) return false;
+    if (p.op == TSG_OP_CONV2D_NHWC) return p.Cin % vec == 0 && p.ldb % vec == 0;
+    if (p.lda % vec || p.ldb % vec) return false;
+    if (p.batch > 1 && (p.stride_a % vec || p.stride_b % vec)) return false;
+    return true;
+}
+
+struct Plan {
+    const KernelEntry* entry;
+    tsg_tile_config cfg;
+    int variant;
+    KArgs args;
+    tsg_launch_info info;
+};
+
+// One alternative: SILENCEABLE if its preconditions fail (nothing is touched).
+tsg_status make_plan(const Problem& p, const tsg_tile_config& cfg, int alternative, Plan* out) {
+    const KernelEntry* e = find_entry(p.dtype, cfg);
+    if (!e) return TSG_E_SILENCEABLE;
+    if (!vec_legal(p, cfg.vec)) return TSG_E_SILENCEABLE;
+    if (cfg.raster != 0 && cfg.raster != 1) return TSG_E_SILENCEABLE;
+
+    int64_t m_main, m_rest, n_main, n_rest, k_main, k_rest, t;
+    tsg_split(p.M, e->bm, &m_main, &m_rest, &t);
+    tsg_split(p.N, e->bn, &n_main, &n_rest, &t);
+    tsg_split(p.K, e->bk, &k_main, &k_rest, &t);
+    const int64_t tiles_m = (p.M + e->bm - 1) / e->bm, tiles_n = (p.N + e->bn - 1) / e->bn;
+    if (tiles_m * tiles_n > 0x7fffffff / 2 || p.batch > 65535) return TSG_E_SILENCEABLE;
+
+    const bool edge = m_rest || n_rest || k_rest;
+    out->entry = e;
+    out->cfg = cfg;
+    out->variant = cfg.vec == 1 ? 2 : (edge ? 1 : 0);
+
+    KArgs& a = out->args;
+    std::memset(&a, 0, sizeof a);
+    a.A = p.A; a.B = p.B; a.C = p.C;
+    a.lda = p.lda; a.ldb = p.ldb; a.ldc = p.ldc;
+    a.stride_a = p.stride_a; a.stride_b = p.stride_b; a.stride_c = p.stride_c;
+    a.M = (int)p.M; a.N = (int)p.N; a.K = (int)p.K;
+    a.tiles_m = (int)tiles_m; a.tiles_n = (int)tiles_n;
+    a.m_main = (int)m_main; a.n_main = (int)n_main; a.k_full = (int)(k_main / e->bk);
+    a.flags = p.flags & (TSG_NEGATE | TSG_ACCUMULATE);
+    a.raster = cfg.raster;
+    a.H = (int)p.H; a.W = (int)p.W; a.Cin = (int)p.Cin; a.Ho = (int)p.Ho; a.Wo = (int)p.Wo;
+    a.KW = (int)p.KW; a.sh = (int)p.sh; a.sw = (int)p.sw; a.ph = (int)p.ph; a.pw = (int)p.pw;
+
+    tsg_launch_info& li = out->info;
+    li.config = cfg;
+    li.alternative = alternative;
+    li.launches = 1;
+    li.edge = out->variant != 0;
+    li.tiles_m = (int)tiles_m; li.tiles_n = (int)tiles_n;
+    li.m_main = m_main; li.m_rest = m_rest; li.n_main = n_main; li.n_rest = n_rest;
+    li.k_main = k_main; li.k_rest = k_rest;
+    return TSG_OK;
+}
+
+tsg_status enqueue(const Problem& p, const Plan& pl, hipStream_t s) {
+    const int amode = p.op == TSG_OP_GEMM ? tsg::A_ROW : p.op == TSG_OP_GEMM_TRANSA ? tsg::A_COL : tsg::A_CONV;
+    const hipError_t e = pl.entry->launch(amode, pl.variant, pl.args, (int)p.batch, s);
+    if (e != hipSuccess) return TSG_E_RUNTIME;
+    t_last = pl.info;
+    return TSG_OK;
+}
+
+// The chain of alternatives (Case Study 4: try, and on a silenceable failure fall through
+// to the next region): caller's pinned config -> shape heuristic -> the heuristic's tile
+// with scalar accesses, which has no precondition beyond a valid problem.
+tsg_status run(const Problem& p, hipStream_t s) {
+    bool pinned;
+    tsg_tile_config pin;
+    {
+        std::lock_guard<std::mutex> g(g_mu);
+        pinned = g_pinned[p.op][p.dtype];
+        pin = g_pin[p.op][p.dtype];
+    }
+    const tsg_tile_config heur = heuristic(p.dtype, p.batch, p.M, p.N, p.K);
+    Plan pl;
+    if (pinned) {
+        if (make_plan(p, pin, 0, &pl) == TSG_OK) return enqueue(p, pl, s);
+        if (p.flags & TSG_STRICT) return TSG_E_SILENCEABLE;
+    }
+    if (make_plan(p, heur, 1, &pl) == TSG_OK) return enqueue(p, pl, s);
+    if (p.flags & TSG_STRICT) return TSG_E_SILENCEABLE;
+    tsg_tile_config scalar = heur;
+    scalar.vec = 1;
+    if (make_plan(p, scalar, 2, &pl) == TSG_OK) return enqueue(p, pl, s);
+    return TSG_E_SILENCEABLE;
+}
+
+bool fits_i32(int64_t v) { return v >= 0 && v <= 0x7fffffff; }
+
+tsg_status check_gemm(int dtype, int64_t batch, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
+                      const void* B, int64_t ldb, const float* C, int64_t ldc, bool trans_a, uint32_t flags) {
+    if (!valid_dtype(dtype)) return TSG_E_INVALID;
+    if (!A || !B || !C) return TSG_E_INVALID;
+    if (M <= 0 || N <= 0 || K <= 0 || batch <= 0) return TSG_E_INVALID;
+    if (!fits_i32(M) || !fits_i32(N) || !fits_i32(K)) return TSG_E_INVALID;
+    if (lda < (trans_a ? M : K) || ldb < N || ldc < N) return TSG_E_INVALID;
+    if (flags & ~(uint32_t)(TSG_NEGATE | TSG_ACCUMULATE | TSG_STRICT)) return TSG_E_INVALID;
+    return TSG_OK;
+}
+
+tsg_status conv_problem(int dtype, int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout, int64_t KH,
+                        int64_t KW, int64_t sh, int64_t sw, int64_t ph, int64_t pw, const void* x, const void* w,
+                        float* y, uint32_t flags, Problem* p) {
+    if (!valid_dtype(dtype) || !x || !w || !y) return TSG_E_INVALID;
+    if (N <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || KH <= 0 || KW <= 0) return TSG_E_INVALID;
+    if (sh <= 0 || sw <= 0 || ph < 0 || pw < 0) return TSG_E_INVALID;
+    if (H + 2 * ph < KH || W + 2 * pw < KW) return TSG_E_INVALID;
+    if (flags & ~(uint32_t)(TSG_NEGATE | TSG_ACCUMULATE | TSG_STRICT)) return TSG_E_INVALID;
+    const int64_t Ho = (H + 2 * ph - KH) / sh + 1, Wo = (W + 2 * pw - KW) / sw + 1;
+    const int64_t lim = 0x7fffffff;
+    if (N > lim / H || N * H > lim / W || N * H * W > lim / Cin) return TSG_E_INVALID;
+    if (N > lim / Ho || N * Ho > lim / Wo || N * Ho * Wo > lim / Cout) return TSG_E_INVALID;
+    if (KH > lim / KW || KH * KW > lim / Cin || KH * KW * Cin > lim / Cout) return TSG_E_INVALID;
+    if (ph > (1 << 20) || pw > (1 << 20) || sh > (1 << 20) || sw > (1 << 20)) return TSG_E_INVALID;
+    p->op = TSG_OP_CONV2D_NHWC;
+    p->dtype = (tsg_dtype)dtype;
+    p->M = N * Ho * Wo; p->N = Cout; p->K = KH * KW * Cin;
+    p->A = x; p->B = w; p->C = y;
+    p->lda = 0; p->ldb = Cout; p->ldc = Cout;
+    p->flags = flags;
+    p->H = H; p->W = W; p->Cin = Cin; p->Ho = Ho; p->Wo = Wo; p->KH = KH; p->KW = KW;
+    p->sh = sh; p->sw = sw; p->ph = ph; p->pw = pw;
+    return TSG_OK;
+}
+
+// Enumerated search space: every instantiated tile x {wide, scalar} access x raster order.
+int space_size(tsg_dtype dt) {
+    int n = 0;
+    kernels(dt, &n);
+    return 3 * n;
+}
+
+tsg_tile_config space_point(tsg_dtype dt, int idx) {
+    int n = 0;
+    const KernelEntry* t = kernels(dt, &n);
+    const KernelEntry& e = t[idx / 3];
+    switch (idx % 3) {
+        case 0: return config_of(e, vec_max(dt), 1);
+        case 1: return config_of(e, vec_max(dt), 0);
+        default: return config_of(e, 1, 1);
+    }
+}
+
+tsg_status autotune(Problem p, hipStream_t s, int iters, tsg_tile_config* best, float* best_ms,
+                    tsg_tune_record* log, int32_t log_cap, int32_t* n_log) {
+    if (iters <= 0 || iters > 256) return TSG_E_INVALID;
+    if (log_cap < 0 || (log_cap > 0 && !log)) return TSG_E_INVALID;
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return TSG_E_RUNTIME;
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return TSG_E_RUNTIME; }
+    p.flags &= ~(uint32_t)TSG_STRICT;
+    float bms = -1.f;
+    tsg_tile_config bcfg{};
+    int written = 0;
+    tsg_status st = TSG_OK;
+    std::vector<float> ms(iters);
+    const int n = space_size(p.dtype);
+    for (int i = 0; i < n && st == TSG_OK; ++i) {
+        const tsg_tile_config c = space_point(p.dtype, i);
+        Plan pl;
+        float med = -1.f;
+        if (make_plan(p, c, 0, &pl) == TSG_OK) {
+            st = enqueue(p, pl, s);   // warm-up
+            for (int it = 0; it < iters && st == TSG_OK; ++it) {
+                if (hipEventRecord(e0, s) != hipSuccess) { st = TSG_E_RUNTIME; break; }
+                st = enqueue(p, pl, s);
+                if (st != TSG_OK) break;
+                if (hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+                    hipEventElapsedTime(&ms[it], e0, e1) != hipSuccess) { st = TSG_E_RUNTIME; break; }
+            }
+            if (st != TSG_OK) break;
+            std::sort(ms.begin(), ms.end());
+            med = ms[iters / 2];
+            if (bms < 0 || med < bms) { bms = med; bcfg = c; }
+        }
+        if (written < log_cap) {
+            log[written].config = c;
+            log[written].ms = med;
+            log[written].best_ms = bms;
+            ++written;
+        }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (n_log) *n_log = written;
+    if (st != TSG_OK) return st;
+    if (bms < 0) return TSG_E_SILENCEABLE;
+    if (best) *best = bcfg;
+    if (best_ms) *best_ms = bms;
+    return tsg_tile_config_set(p.op, p.dtype, &bcfg);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* tsg_status_string(tsg_status s) {
+    switch (s) {
+        case TSG_OK: return "ok";
+        case TSG_E_SILENCEABLE: return "silenceable: precondition of the requested schedule failed, nothing modified";
+        case TSG_E_INVALID: return "definite: invalid argument";
+        case TSG_E_RUNTIME: return "definite: HIP runtime failure";
+    }
+    return "unknown status";
+}
+
+int32_t tsg_version(void) { return 1; }
+
+tsg_status tsg_split(int64_t ub, int64_t d, int64_t* main_part, int64_t* rest, int64_t* tiles) {
+    if (ub < 0 || d < 0 || !main_part || !rest || !tiles) return TSG_E_INVALID;
+    const int64_t t = d == 0 ? 1 : ub / d;
+    *tiles = t;
+    *main_part = d == 0 ? ub : t * d;
+    *rest = ub - *main_part;
+    return TSG_OK;
+}
+
+tsg_status tsg_gemm_batched(tsg_dtype dtype, int32_t trans_a, int64_t batch, int64_t M, int64_t N, int64_t K,
+                            const void* A, int64_t lda, int64_t stride_a, const void* B, int64_t ldb,
+                            int64_t stride_b, float* C, int64_t ldc, int64_t stride_c, uint32_t flags,
+                            void* stream) {
+    const tsg_status v = check_gemm(dtype, batch, M, N, K, A, lda, B, ldb, C, ldc, trans_a != 0, flags);
+    if (v != TSG_OK) return v;
+    if (stride_a < 0 || stride_b < 0 || stride_c < 0) return TSG_E_INVALID;
+    if (batch > 1 && stride_c < (M - 1) * ldc + N) return TSG_E_INVALID;   // outputs must not overlap
+    Problem p;
+    p.op = trans_a ? TSG_OP_GEMM_TRANSA : TSG_OP_GEMM;
+    p.dtype = dtype;
+    p.batch = batch;
+    p.M = M; p.N = N; p.K = K;
+    p.A = A; p.B = B; p.C = C;
+    p.lda = lda; p.ldb = ldb; p.ldc = ldc;
+    p.stride_a = stride_a; p.stride_b = stride_b; p.stride_c = stride_c;
+    p.flags = flags;
+    return run(p, (hipStream_t)stream);
+}
+
+tsg_status tsg_gemm(tsg_dtype dtype, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B,
+                    int64_t ldb, float* C, int64_t ldc, uint32_t flags, void* stream) {
+    return tsg_gemm_batched(dtype, 0, 1, M, N, K, A, lda, 0, B, ldb, 0, C, ldc, 0, flags, stream);
+}
+
+tsg_status tsg_gemm_transA(tsg_dtype dtype, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
+                           const void* B, int64_t ldb, float* C, int64_t ldc, uint32_t flags, void* stream) {
+    return tsg_gemm_batched(dtype, 1, 1, M, N, K, A, lda, 0, B, ldb, 0, C, ldc, 0, flags, stream);
+}
+
+tsg_status tsg_conv2d_nhwc(tsg_dtype dtype, int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                           int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w, int64_t pad_h,
+                           int64_t pad_w, const void* x, const void* w, float* y, uint32_t flags, void* stream) {
+    Problem p;
+    const tsg_status v = conv_problem(dtype, N, H, W, Cin, Cout, KH, KW, stride_h, stride_w, pad_h, pad_w, x, w, y,
+                                      flags, &p);
+    if (v != TSG_OK) return v;
+    return run(p, (hipStream_t)stream);
+}
+
+int32_t tsg_tile_config_count(tsg_op op, tsg_dtype dtype) {
+    if (!valid_op(op) || !valid_dtype(dtype)) return 0;
+    return space_size(dtype);
+}
+
+tsg_status tsg_tile_config_enum(tsg_op op, tsg_dtype dtype, int32_t idx, tsg_tile_config* out) {
+    if (!valid_op(op) || !valid_dtype(dtype) || !out) return TSG_E_INVALID;
+    if (idx < 0 || idx >= space_size(dtype)) return TSG_E_INVALID;
+    *out = space_point(dtype, idx);
+    return TSG_OK;
+}
+
+tsg_status tsg_tile_config_check(tsg_op op, tsg_dtype dtype, int64_t M, int64_t N, int64_t K, int64_t contig,
+                                 const tsg_tile_config* cfg) {
+    if (!valid_op(op) || !valid_dtype(dtype) || !cfg) return TSG_E_INVALID;
+    if (M <= 0 || N <= 0 || K <= 0) return TSG_E_INVALID;
+    if (cfg->bm < 0 || cfg->bn < 0 || cfg->bk < 0 || cfg->wm < 0 || cfg->wn < 0 || cfg->vec < 0) return TSG_E_INVALID;
+    const tsg_tile_config c = fill_defaults(*cfg, heuristic(dtype, 1, M, N, K));
+    if (!find_entry(dtype, c)) return TSG_E_SILENCEABLE;
+    if (c.raster != 0 && c.raster != 1) return TSG_E_SILENCEABLE;
+    if (c.vec == 1) return TSG_OK;
+    if (c.vec != vec_max(dtype)) return TSG_E_SILENCEABLE;
+    // natural leading dimensions: A rows have K (or M when transposed, or Cin-long runs
+    // when gathered) elements, B rows have N
+    const int64_t a_run = op == TSG_OP_GEMM ? K : op == TSG_OP_GEMM_TRANSA ? M : contig;
+    if (op == TSG_OP_CONV2D_NHWC && contig <= 0) return TSG_E_INVALID;
+    if (a_run % c.vec || N % c.vec) return TSG_E_SILENCEABLE;
+    return TSG_OK;
+}
+
+tsg_status tsg_tile_config_set(tsg_op op, tsg_dtype dtype, const tsg_tile_config* cfg) {
+    if (!valid_op(op) || !valid_dtype(dtype)) return TSG_E_INVALID;
+    std::lock_guard<std::mutex> g(g_mu);
+    if (!cfg) { g_pinned[op][dtype] = false; return TSG_OK; }
+    if (cfg->bm < 0 || cfg->bn < 0 || cfg->bk < 0 || cfg->wm < 0 || cfg->wn < 0 || cfg->vec < 0) return TSG_E_INVALID;
+    int n = 0;
+    const KernelEntry* t = kernels(dtype, &n);
+    const tsg_tile_config c = fill_defaults(*cfg, config_of(t[0], vec_max(dtype), 1));
+    if (!find_entry(dtype, c)) return TSG_E_SILENCEABLE;
+    if (c.vec != 1 && c.vec != vec_max(dtype)) return TSG_E_SILENCEABLE;
+    if (c.raster != 0 && c.raster != 1) return TSG_E_SILENCEABLE;
+    g_pin[op][dtype] = c;
+    g_pinned[op][dtype] = true;
+    return TSG_OK;
+}
+
+tsg_status tsg_tile_config_get(tsg_op op, tsg_dtype dtype, int64_t M, int64_t N, int64_t K, tsg_tile_config* out) {
+    if (!valid_op(op) || !valid_dtype(dtype) || !out) return TSG_E_INVALID;
+    if (M <= 0 || N <= 0 || K <= 0) return TSG_E_INVALID;
+    std::lock_guard<std::mutex> g(g_mu);
+    *out = g_pinned[op][dtype] ? g_pin[op][dtype] : heuristic(dtype, 1, M, N, K);
+    return TSG_OK;
+}
+
+tsg_status tsg_last_launch(tsg_launch_info* out) {
+    if (!out) return TSG_E_INVALID;
+    *out = t_last;
+    return TSG_OK;
+}
+
+tsg_status tsg_conv2d_index_map(int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t KH, int64_t KW,
+                                int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w, int32_t* off) {
+    if (!off || N <= 0 || H <= 0 || W <= 0 || Cin <= 0 || KH <= 0 || KW <= 0) return TSG_E_INVALID;
+    if (stride_h <= 0 || stride_w <= 0 || pad_h < 0 || pad_w < 0) return TSG_E_INVALID;
+    if (H + 2 * pad_h < KH || W + 2 * pad_w < KW) return TSG_E_INVALID;
+    const int64_t lim = 0x7fffffff;
+    if (N > lim / H || N * H > lim / W || N * H * W > lim / Cin) return TSG_E_INVALID;
+    const int64_t Ho = (H + 2 * pad_h - KH) / stride_h + 1, Wo = (W + 2 * pad_w - KW) / stride_w + 1;
+    const int64_t taps = KH * KW, M = N * Ho * Wo;
+    // Same decode as the kernel's gather: m -> (n, ho, wo), tap -> (kh, kw).
+    for (int64_t m = 0; m < M; ++m) {
+        const int64_t wo = m % Wo, t = m / Wo, ho = t % Ho, n = t / Ho;
+        const int64_t hi0 = ho * stride_h - pad_h, wi0 = wo * stride_w - pad_w;
+        for (int64_t tap = 0; tap < taps; ++tap) {
+            const int64_t kh = tap / KW, kw = tap - kh * KW;
+            const int64_t hi = hi0 + kh, wi = wi0 + kw;
+            const bool inside = hi >= 0 && hi < H && wi >= 0 && wi < W;
+            off[m * taps + tap] = inside ? (int32_t)(((n * H + hi) * W + wi) * Cin) : -1;
+        }
+    }
+    return TSG_OK;
+}
+
+tsg_status tsg_gemm_index_map(int32_t trans_a, int64_t M, int64_t K, int64_t lda, int64_t* off) {
+    if (!off || M <= 0 || K <= 0 || lda < (trans_a ? M : K)) return TSG_E_INVALID;
+    for (int64_t i = 0; i < M; ++i)
+        for (int64_t k = 0; k < K; ++k) off[i * K + k] = trans_a ? k * lda + i : i * lda + k;
+    return TSG_OK;
+}
+
+tsg_status tsg_autotune_gemm(tsg_dtype dtype, int32_t trans_a, int64_t M, int64_t N, int64_t K, const void* A,
+                             int64_t lda, const void* B, int64_t ldb, float* C, int64_t ldc, uint32_t flags,
+                             void* stream, int32_t iters, tsg_tile_config* best, float* best_ms,
+                             tsg_tune_record* log, int32_t log_cap, int32_t* n_log) {
+    const tsg_status v = check_gemm(dtype, 1, M, N, K, A, lda, B, ldb, C, ldc, trans_a != 0, flags);
+    if (v != TSG_OK) return v;
+    Problem p;
+    p.op = trans_a ? TSG_OP_GEMM_TRANSA : TSG_OP_GEMM;
+    p.dtype = dtype;
+    p.M = M; p.N = N; p.K = K;
+    p.A = A; p.B = B; p.C = C;
+    p.lda = lda; p.ldb = ldb; p.ldc = ldc;
+    p.flags = flags;
+    return autotune(p, (hipStream_t)stream, iters, best, best_ms, log, log_cap, n_log);
+}
+
+tsg_status tsg_autotune_conv2d_nhwc(tsg_dtype dtype, int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                                    int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w, int64_t pad_h,
+                                    int64_t pad_w, const void* x, const void* w, float* y, uint32_t flags,
+                                    void* stream, int32_t iters, tsg_tile_config* best, float* best_ms,
+                                    tsg_tune_record* log, int32_t log_cap, int32_t* n_log) {
+    Problem p;
+    const tsg_status v = conv_problem(dtype, N, H, W, Cin, Cout, KH, KW, stride_h, stride_w, pad_h, pad_w, x, w, y,
+                                      flags, &p);
+    if (v != TSG_OK) return v;
+    return autotune(p, (hipStream_t)stream, iters, best, best_ms, log, log_cap, n_log);
+}
+
+}  // extern "C"

@@ -1,0 +1,299 @@
+// bfloat16-operand contraction kernels for gfx950: C(fp32) = +-op(A).B (+C) with
+// v_mfma_f32_32x32x16_bf16 (fp32 accumulate).  Same tiling, split and address generators
+// as the fp32 kernels; operands are staged in LDS with k contiguous per row so that a
+// lane's eight consecutive k values are one 16-byte read.  An operand that is NOT
+// k-contiguous in memory (B, and op(A) when the left operand is stored transposed) is
+// transposed on its way into LDS.
+#include "tsg_internal.h"
+
+namespace tsg {
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned short u16;
+typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
+
+constexpr unsigned FLAG_NEGATE = 1u, FLAG_ACCUMULATE = 2u;
+constexpr int kXcds = 8, kGroupM = 8;
+
+template <int BM_, int BN_, int BK_, int WM_, int WN_, int MINW_>
+struct Tile {
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, MINW = MINW_;
+    static constexpr int WAVES_M = BM / WM, WAVES_N = BN / WN;
+    static constexpr int NT = 64 * WAVES_M * WAVES_N;
+    static constexpr int MI = WM / 32, NI = WN / 32;
+    static constexpr int LD = BK + 8;   // LDS row pitch in elements (144 B at BK = 64)
+    static constexpr int A_SIZE = BM * LD, B_SIZE = BN * LD, STAGE = A_SIZE + B_SIZE;
+    static constexpr int BYTES = 2 * STAGE * 2;
+    static_assert(BM % WM == 0 && BN % WN == 0 && WM % 32 == 0 && WN % 32 == 0 && BK % 16 == 0, "tile");
+};
+
+__device__ __forceinline__ void tile_coords(const KArgs& p, int bid, int& tm, int& tn) {
+    if (p.raster) {
+        const int T = p.tiles_m * p.tiles_n;
+        const int xcd = bid % kXcds, loc = bid / kXcds;
+        const int q = T / kXcds, r = T % kXcds;
+        const int id = (xcd < r) ? xcd * (q + 1) + loc : r * (q + 1) + (xcd - r) * q + loc;
+        const int gsize = kGroupM * p.tiles_n;
+        const int g = id / gsize, in_g = id - g * gsize;
+        const int first_m = g * kGroupM;
+        const int gm = min(p.tiles_m - first_m, kGroupM);
+        tm = first_m + in_g % gm;
+        tn = in_g / gm;
+        return;
+    }
+    tm = bid / p.tiles_n;
+    tn = bid - tm * p.tiles_n;
+}
+
+template <class T, int AMODE, int VEC, bool EDGE>
+__global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_kernel(const KArgs p) {
+    constexpr int BM = T::BM, BN = T::BN, BK = T::BK, NT = T::NT, MI = T::MI, NI = T::NI, LD = T::LD;
+    extern __shared__ __attribute__((aligned(16))) u16 smem16[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm0 = (wave / T::WAVES_N) * T::WM, wn0 = (wave % T::WAVES_N) * T::WN;
+    const int li = lane & 31, lh = lane >> 5;
+
+    int tm, tn;
+    tile_coords(p, blockIdx.x, tm, tn);
+    const int m0 = tm * BM, n0 = tn * BN;
+    const u16* __restrict__ A = (const u16*)p.A + (long long)blockIdx.y * p.stride_a;
+    const u16* __restrict__ B = (const u16*)p.B + (long long)blockIdx.y * p.stride_b;
+    float* __restrict__ C = p.C + (long long)blockIdx.y * p.stride_c;
+
+    const bool interior = !EDGE || (m0 + BM <= p.m_main && n0 + BN <= p.n_main);
+    const int nk = (p.K + BK - 1) / BK;
+
+    // 8-element (16-byte) chunks along the contiguous dimension of each stored operand.
+    // kmaj == true: the stored rows run along k (A_ROW, A_CONV); false: along i or j.
+    constexpr bool A_KMAJ = (AMODE != A_COL);
+    constexpr int A_CPR = A_KMAJ ? BK / 8 : BM / 8;
+    constexpr int A_ROWS = A_KMAJ ? BM : BK;
+    constexpr int A_RPP = NT / A_CPR, PA = A_ROWS / A_RPP;
+    constexpr int B_CPR = BN / 8, B_RPP = NT / B_CPR, PB = BK / B_RPP;
+    static_assert(NT % A_CPR == 0 && A_ROWS % A_RPP == 0 && PA >= 1, "A staging shape");
+    static_assert(NT % B_CPR == 0 && BK % B_RPP == 0 && PB >= 1, "B staging shape");
+    const int a_r = tid / A_CPR, a_c = (tid % A_CPR) * 8;
+    const int b_r = tid / B_CPR, b_c = (tid % B_CPR) * 8;
+
+    int cv_base[PA], cv_hi0[PA], cv_wi0[PA];
+    if constexpr (AMODE == A_CONV) {
+#pragma unroll
+        for (int q = 0; q < PA; ++q) {
+            const int m = m0 + a_r + q * A_RPP;
+            if (m < p.M) {
+                const int wo = m % p.Wo, t = m / p.Wo;
+                const int ho = t % p.Ho, n = t / p.Ho;
+                cv_base[q] = n * p.H;
+                cv_hi0[q] = ho * p.sh - p.ph;
+                cv_wi0[q] = wo * p.sw - p.pw;
+            } else {
+                cv_base[q] = 0;
+                cv_hi0[q] = -(1 << 28);
+                cv_wi0[q] = 0;
+            }
+        }
+    }
+
+    u16x8 ra[PA], rb[PB];
+
+    auto a_elem = [&](int q, int row_or_k, int e) -> u16 {
+        if constexpr (AMODE == A_ROW) {
+            const int m = m0 + row_or_k, k = e;
+            return (m < p.M && k < p.K) ? A[(long long)m * p.lda + k] : (u16)0;
+        } else if constexpr (AMODE == A_COL) {
+            const int k = row_or_k, m = e;
+            return (k < p.K && m < p.M) ? A[(long long)k * p.lda + m] : (u16)0;
+        } else {
+            const int k = e;
+            if (k >= p.K) return 0;
+            const int tap = k / p.Cin, ci = k - tap * p.Cin;
+            const int kh = tap / p.KW, kw = tap - kh * p.KW;
+            const int hi = cv_hi0[q] + kh, wi = cv_wi0[q] + kw;
+            if (hi < 0 || hi >= p.H || wi < 0 || wi >= p.W) return 0;
+            return A[((long long)(cv_base[q] + hi) * p.W + wi) * p.Cin + ci];
+        }
+    };
+
+    auto load_tiles = [&](int kt, bool fast) {
+        const int k0 = kt * BK;
+#pragma unroll
+        for (int q = 0; q < PA; ++q) {
+            const int r = a_r + q * A_RPP;
+            if constexpr (AMODE == A_ROW) {
+                const int k = k0 + a_c;
+                if (VEC == 8 && (fast || (m0 + r < p.M && k + 8 <= p.K))) {
+                    ra[q] = *(const u16x8*)(A + (long long)(m0 + r) * p.lda + k);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) ra[q][e] = a_elem(q, r, k + e);
+                }
+            } else if constexpr (AMODE == A_COL) {
+                const int k = k0 + r, m = m0 + a_c;
+                if (VEC == 8 && (fast || (k < p.K && m + 8 <= p.M))) {
+                    ra[q] = *(const u16x8*)(A + (long long)k * p.lda + m);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) ra[q][e] = a_elem(q, k, m + e);
+                }
+            } else {
+                const int k = k0 + a_c;
+                if constexpr (VEC == 8) {
+                    u16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+                    if (fast || k < p.K) {
+                        const int tap = k / p.Cin, ci = k - tap * p.Cin;
+                        const int kh = tap / p.KW, kw = tap - kh * p.KW;
+                        const int hi = cv_hi0[q] + kh, wi = cv_wi0[q] + kw;
+                        if (hi >= 0 && hi < p.H && wi >= 0 && wi < p.W)
+                            v = *(const u16x8*)(A + ((long long)(cv_base[q] + hi) * p.W + wi) * p.Cin + ci);
+                    }
+                    ra[q] = v;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) ra[q][e] = a_elem(q, r, k + e);
+                }
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < PB; ++q) {
+            const int k = k0 + b_r + q * B_RPP, n = n0 + b_c;
+            if (VEC == 8 && (fast || (k < p.K && n + 8 <= p.N))) {
+                rb[q] = *(const u16x8*)(B + (long long)k * p.ldb + n);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    rb[q][e] = (k < p.K && n + e < p.N) ? B[(long long)k * p.ldb + n + e] : (u16)0;
+            }
+        }
+    };
+
+    auto store_tiles = [&](int stage) {
+        u16* As = smem16 + stage * T::STAGE;
+        u16* Bs = As + T::A_SIZE;
+#pragma unroll
+        for (int q = 0; q < PA; ++q) {
+            const int r = a_r + q * A_RPP;
+            if constexpr (A_KMAJ) {
+                *(u16x8*)(As + r * LD + a_c) = ra[q];
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) As[(a_c + e) * LD + r] = ra[q][e];   // transpose: row = i, col = k
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < PB; ++q) {
+            const int r = b_r + q * B_RPP;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) Bs[(b_c + e) * LD + r] = rb[q][e];       // transpose: row = j, col = k
+        }
+    };
+
+    f32x16 acc[MI][NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    auto compute = [&](int stage) {
+        const u16* As = smem16 + stage * T::STAGE;
+        const u16* Bs = As + T::A_SIZE;
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 16) {
+            bf16x8 af[MI], bf[NI];
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+                af[i] = *(const bf16x8*)(As + (wm0 + i * 32 + li) * LD + kk + 8 * lh);
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+                bf[j] = *(const bf16x8*)(Bs + (wn0 + j * 32 + li) * LD + kk + 8 * lh);
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NI; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+        }
+    };
+
+    load_tiles(0, EDGE ? (interior && 0 < p.k_full) : true);
+    store_tiles(0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        const bool more = kt + 1 < nk;
+        if (more) load_tiles(kt + 1, EDGE ? (interior && kt + 1 < p.k_full) : true);
+        compute(cur);
+        if (more) store_tiles(cur ^ 1);
+        __syncthreads();
+    }
+
+    const bool neg = p.flags & FLAG_NEGATE, accum = p.flags & FLAG_ACCUMULATE;
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            const int col = n0 + wn0 + j * 32 + li;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = m0 + wm0 + i * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+                if (interior || (row < p.M && col < p.N)) {
+                    float* c = C + (long long)row * p.ldc + col;
+                    float v = acc[i][j][r];
+                    if (neg) v = -v;
+                    if (accum) v += *c;
+                    *c = v;
+                }
+            }
+        }
+}
+
+template <class T, int AMODE>
+hipError_t launch_mode(int variant, const KArgs& a, int batch, hipStream_t s) {
+    const dim3 grid(a.tiles_m * a.tiles_n, batch, 1), block(T::NT, 1, 1);
+    void (*fn)(const KArgs) = nullptr;
+    switch (variant) {
+        case 0: fn = gemm_bf16_kernel<T, AMODE, 8, false>; break;
+        case 1: fn = gemm_bf16_kernel<T, AMODE, 8, true>; break;
+        default: fn = gemm_bf16_kernel<T, AMODE, 1, true>; break;
+    }
+    static bool attr_done[3] = {false, false, false};
+    if (T::BYTES > 48 * 1024 && !attr_done[variant]) {
+        hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, T::BYTES);
+        if (e != hipSuccess) return e;
+        attr_done[variant] = true;
+    }
+    hipLaunchKernelGGL(fn, grid, block, T::BYTES, s, a);
+    return hipGetLastError();
+}
+
+template <class T>
+hipError_t launch_tile(int amode, int variant, const KArgs& a, int batch, hipStream_t s) {
+    switch (amode) {
+        case A_ROW: return launch_mode<T, A_ROW>(variant, a, batch, s);
+        case A_COL: return launch_mode<T, A_COL>(variant, a, batch, s);
+        default: return launch_mode<T, A_CONV>(variant, a, batch, s);
+    }
+}
+
+template <class T>
+constexpr KernelEntry entry() {
+    return KernelEntry{T::BM, T::BN, T::BK, T::WM, T::WN, T::NT, 8, &launch_tile<T>};
+}
+
+const KernelEntry kTable[] = {
+    entry<Tile<256, 256, 64, 128, 128, 1>>(),
+    entry<Tile<128, 128, 64, 64, 64, 2>>(),
+    entry<Tile<64, 64, 64, 32, 32, 2>>(),
+};
+
+}  // namespace
+
+const KernelEntry* bf16_kernels(int* count) {
+    *count = (int)(sizeof(kTable) / sizeof(kTable[0]));
+    return kTable;
+}
+
+}  // namespace tsg

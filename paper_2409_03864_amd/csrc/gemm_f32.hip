@@ -1,0 +1,340 @@
+// fp32 contraction kernels for gfx950: C = +-op(A).B (+C), fp32 MFMA accumulate.
+//
+// One workgroup computes a BM x BN tile of C (the i/j tiling of Case Study 4, Fig. 8);
+// the k loop advances in BK steps with the operand tiles of step t+1 fetched from
+// global memory into registers while step t is consumed from LDS (two LDS stages,
+// one barrier per step).  Each wavefront owns a WM x WN sub-tile built from 32x32
+// MFMA blocks: the fixed-size inner matmul that the paper hands to a microkernel
+// library is here the v_mfma_f32_32x32x2_f32 sequence.
+//
+// The rewrites of Case Study 3 live in the address generators only:
+//   A_ROW  : op(A)(i,k) = A[i*lda + k]
+//   A_COL  : op(A)(i,k) = A[k*lda + i]        transposed operand, read in place
+//   A_CONV : op(A)(m,k) = x[n][ho*sh+kh-ph][wo*sw+kw-pw][ci], k = (kh*KW+kw)*Cin+ci,
+//            and 0 WITHOUT a memory access where the coordinate is in the padding
+// The main/remainder split of Fig. 8 is taken per tile: tiles inside
+// [0,m_main) x [0,n_main) and k steps below k_full run the unmasked loaders, the
+// remainder runs masked ones (zero fill), chosen by a wavefront-uniform branch.
+#include "tsg_internal.h"
+
+namespace tsg {
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr unsigned FLAG_NEGATE = 1u, FLAG_ACCUMULATE = 2u;
+constexpr int kXcds = 8;      // workgroup ids are dealt round-robin over this many L2 domains
+constexpr int kGroupM = 8;    // tile rows per raster group
+
+template <int BM_, int BN_, int BK_, int WM_, int WN_, int MINW_>
+struct Tile {
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, MINW = MINW_;
+    static constexpr int WAVES_M = BM / WM, WAVES_N = BN / WN;
+    static constexpr int NT = 64 * WAVES_M * WAVES_N;
+    static constexpr int MI = WM / 32, NI = WN / 32;
+    static_assert(BM % WM == 0 && BN % WN == 0 && WM % 32 == 0 && WN % 32 == 0 && BK % 8 == 0, "tile");
+};
+
+template <class T, int AMODE>
+struct Lds {
+    // k-contiguous A rows are padded by 4 floats so that the 16-byte fragment reads of
+    // 16 consecutive rows fall in distinct banks; i/j-contiguous tiles are padded by 8 so
+    // the two half-waves (k and k+4) read different bank halves.
+    static constexpr int A_LD = (AMODE == A_COL) ? T::BM + 8 : T::BK + 4;
+    static constexpr int A_ROWS = (AMODE == A_COL) ? T::BK : T::BM;
+    static constexpr int B_LD = T::BN + 8;
+    static constexpr int A_SIZE = A_ROWS * A_LD, B_SIZE = T::BK * B_LD;
+    static constexpr int STAGE = A_SIZE + B_SIZE;
+    static constexpr int BYTES = 2 * STAGE * (int)sizeof(float);
+};
+
+__device__ __forceinline__ void tile_coords(const KArgs& p, int bid, int& tm, int& tn) {
+    int id = bid;
+    if (p.raster) {
+        // Give each XCD a contiguous range of tile ids, then walk the range in groups of
+        // kGroupM tile rows so that concurrently resident tiles share A and B panels in
+        // that XCD's L2.
+        const int T = p.tiles_m * p.tiles_n;
+        const int xcd = bid % kXcds, loc = bid / kXcds;
+        const int q = T / kXcds, r = T % kXcds;
+        id = (xcd < r) ? xcd * (q + 1) + loc : r * (q + 1) + (xcd - r) * q + loc;
+        const int gsize = kGroupM * p.tiles_n;
+        const int g = id / gsize, in_g = id - g * gsize;
+        const int first_m = g * kGroupM;
+        const int gm = min(p.tiles_m - first_m, kGroupM);
+        tm = first_m + in_g % gm;
+        tn = in_g / gm;
+        return;
+    }
+    tm = id / p.tiles_n;
+    tn = id - tm * p.tiles_n;
+}
+
+template <class T, int AMODE, int VEC, bool EDGE>
+__global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_kernel(const KArgs p) {
+    constexpr int BM = T::BM, BN = T::BN, BK = T::BK, NT = T::NT, MI = T::MI, NI = T::NI;
+    using L = Lds<T, AMODE>;
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm0 = (wave / T::WAVES_N) * T::WM, wn0 = (wave % T::WAVES_N) * T::WN;
+    const int li = lane & 31, lh = lane >> 5;
+
+    int tm, tn;
+    tile_coords(p, blockIdx.x, tm, tn);
+    const int m0 = tm * BM, n0 = tn * BN;
+    const float* __restrict__ A = (const float*)p.A + (long long)blockIdx.y * p.stride_a;
+    const float* __restrict__ B = (const float*)p.B + (long long)blockIdx.y * p.stride_b;
+    float* __restrict__ C = p.C + (long long)blockIdx.y * p.stride_c;
+
+    // Remainder tiles (Fig. 8's %rest) take the masked loaders for every k step.
+    const bool interior = !EDGE || (m0 + BM <= p.m_main && n0 + BN <= p.n_main);
+    const int nk = (p.K + BK - 1) / BK;
+
+    // ---- per-thread global->LDS assignment: 4-element chunks along the contiguous dim
+    constexpr int A_CPR = (AMODE == A_COL) ? BM / 4 : BK / 4;   // chunks per stored row
+    constexpr int A_RPP = NT / A_CPR;                            // rows per pass
+    constexpr int A_ROWS = L::A_ROWS;
+    constexpr int PA = A_ROWS / A_RPP;
+    constexpr int B_CPR = BN / 4, B_RPP = NT / B_CPR, PB = BK / B_RPP;
+    static_assert(NT % A_CPR == 0 && A_ROWS % A_RPP == 0 && PA >= 1, "A staging shape");
+    static_assert(NT % B_CPR == 0 && BK % B_RPP == 0 && PB >= 1, "B staging shape");
+    const int a_r = tid / A_CPR, a_c = (tid % A_CPR) * 4;
+    const int b_r = tid / B_CPR, b_c = (tid % B_CPR) * 4;
+
+    // convolution: decode this thread's output pixels once
+    int cv_base[PA], cv_hi0[PA], cv_wi0[PA];
+    if constexpr (AMODE == A_CONV) {
+#pragma unroll
+        for (int q = 0; q < PA; ++q) {
+            const int m = m0 + a_r + q * A_RPP;
+            if (m < p.M) {
+                const int wo = m % p.Wo, t = m / p.Wo;
+                const int ho = t % p.Ho, n = t / p.Ho;
+                cv_base[q] = n * p.H;
+                cv_hi0[q] = ho * p.sh - p.ph;
+                cv_wi0[q] = wo * p.sw - p.pw;
+            } else {
+                cv_base[q] = 0;
+                cv_hi0[q] = -(1 << 28);   // every tap reads as padding
+                cv_wi0[q] = 0;
+            }
+        }
+    }
+
+    f32x4 ra[PA], rb[PB];
+
+    // One element of op(A) for the scalar path (row/col relative to the problem).
+    auto a_elem = [&](int q, int row_or_k, int e) -> float {
+        if constexpr (AMODE == A_ROW) {
+            const int m = m0 + row_or_k, k = e;
+            return (m < p.M && k < p.K) ? A[(long long)m * p.lda + k] : 0.f;
+        } else if constexpr (AMODE == A_COL) {
+            const int k = row_or_k, m = e;
+            return (k < p.K && m < p.M) ? A[(long long)k * p.lda + m] : 0.f;
+        } else {
+            const int k = e;
+            if (k >= p.K) return 0.f;
+            const int tap = k / p.Cin, ci = k - tap * p.Cin;
+            const int kh = tap / p.KW, kw = tap - kh * p.KW;
+            const int hi = cv_hi0[q] + kh, wi = cv_wi0[q] + kw;
+            if (hi < 0 || hi >= p.H || wi < 0 || wi >= p.W) return 0.f;
+            return A[((long long)(cv_base[q] + hi) * p.W + wi) * p.Cin + ci];
+        }
+    };
+
+    auto load_tiles = [&](int kt, bool fast) {
+        const int k0 = kt * BK;
+        // ---------------- A
+#pragma unroll
+        for (int q = 0; q < PA; ++q) {
+            const int r = a_r + q * A_RPP;
+            if constexpr (AMODE == A_ROW) {
+                const int k = k0 + a_c;
+                if (VEC == 4 && (fast || (m0 + r < p.M && k + 4 <= p.K))) {
+                    ra[q] = *(const f32x4*)(A + (long long)(m0 + r) * p.lda + k);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) ra[q][e] = a_elem(q, r, k + e);
+                }
+            } else if constexpr (AMODE == A_COL) {
+                const int k = k0 + r, m = m0 + a_c;
+                if (VEC == 4 && (fast || (k < p.K && m + 4 <= p.M))) {
+                    ra[q] = *(const f32x4*)(A + (long long)k * p.lda + m);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) ra[q][e] = a_elem(q, k, m + e);
+                }
+            } else {
+                const int k = k0 + a_c;
+                if constexpr (VEC == 4) {
+                    // Cin % 4 == 0: the chunk lies inside one tap
+                    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+                    if (fast || k < p.K) {
+                        const int tap = k / p.Cin, ci = k - tap * p.Cin;
+                        const int kh = tap / p.KW, kw = tap - kh * p.KW;
+                        const int hi = cv_hi0[q] + kh, wi = cv_wi0[q] + kw;
+                        if (hi >= 0 && hi < p.H && wi >= 0 && wi < p.W)
+                            v = *(const f32x4*)(A + ((long long)(cv_base[q] + hi) * p.W + wi) * p.Cin + ci);
+                    }
+                    ra[q] = v;
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) ra[q][e] = a_elem(q, r, k + e);
+                }
+            }
+        }
+        // ---------------- B (K x N, j contiguous)
+#pragma unroll
+        for (int q = 0; q < PB; ++q) {
+            const int k = k0 + b_r + q * B_RPP, n = n0 + b_c;
+            if (VEC == 4 && (fast || (k < p.K && n + 4 <= p.N))) {
+                rb[q] = *(const f32x4*)(B + (long long)k * p.ldb + n);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    rb[q][e] = (k < p.K && n + e < p.N) ? B[(long long)k * p.ldb + n + e] : 0.f;
+            }
+        }
+    };
+
+    auto store_tiles = [&](int stage) {
+        float* As = smem + stage * L::STAGE;
+        float* Bs = As + L::A_SIZE;
+#pragma unroll
+        for (int q = 0; q < PA; ++q)
+            *(f32x4*)(As + (a_r + q * A_RPP) * L::A_LD + a_c) = ra[q];
+#pragma unroll
+        for (int q = 0; q < PB; ++q)
+            *(f32x4*)(Bs + (b_r + q * B_RPP) * L::B_LD + b_c) = rb[q];
+    };
+
+    f32x16 acc[MI][NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // The k values of an 8-wide group are consumed in the order (t, t+4), t = 0..3: lanes
+    // 0-31 feed k = t and lanes 32-63 feed k = t+4 of MFMA number t.  Any order is legal as
+    // long as both operands use it, and this one lets a k-contiguous A row be fetched with
+    // a single 16-byte LDS read.
+    auto compute = [&](int stage) {
+        const float* As = smem + stage * L::STAGE;
+        const float* Bs = As + L::A_SIZE;
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 8) {
+            f32x4 af[MI], bf[NI];
+#pragma unroll
+            for (int i = 0; i < MI; ++i) {
+                if constexpr (AMODE == A_COL) {
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+                        af[i][t] = As[(kk + 4 * lh + t) * L::A_LD + wm0 + i * 32 + li];
+                } else {
+                    af[i] = *(const f32x4*)(As + (wm0 + i * 32 + li) * L::A_LD + kk + 4 * lh);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+                    bf[j][t] = Bs[(kk + 4 * lh + t) * L::B_LD + wn0 + j * 32 + li];
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int j = 0; j < NI; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i][t], bf[j][t], acc[i][j], 0, 0, 0);
+        }
+    };
+
+    // ---- main loop: global loads of step t+1 are in flight while step t is multiplied
+    load_tiles(0, EDGE ? (interior && 0 < p.k_full) : true);
+    store_tiles(0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        const bool more = kt + 1 < nk;
+        if (more) load_tiles(kt + 1, EDGE ? (interior && kt + 1 < p.k_full) : true);
+        compute(cur);
+        if (more) store_tiles(cur ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: sign, optional accumulate, masked at the remainder
+    const bool neg = p.flags & FLAG_NEGATE, accum = p.flags & FLAG_ACCUMULATE;
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            const int col = n0 + wn0 + j * 32 + li;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = m0 + wm0 + i * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+                if (interior || (row < p.M && col < p.N)) {
+                    float* c = C + (long long)row * p.ldc + col;
+                    float v = acc[i][j][r];
+                    if (neg) v = -v;
+                    if (accum) v += *c;
+                    *c = v;
+                }
+            }
+        }
+}
+
+template <class T, int AMODE>
+hipError_t launch_mode(int variant, const KArgs& a, int batch, hipStream_t s) {
+    using L = Lds<T, AMODE>;
+    const dim3 grid(a.tiles_m * a.tiles_n, batch, 1), block(T::NT, 1, 1);
+    void (*fn)(const KArgs) = nullptr;
+    switch (variant) {
+        case 0: fn = gemm_f32_kernel<T, AMODE, 4, false>; break;
+        case 1: fn = gemm_f32_kernel<T, AMODE, 4, true>; break;
+        default: fn = gemm_f32_kernel<T, AMODE, 1, true>; break;
+    }
+    static bool attr_done[3] = {false, false, false};
+    if (L::BYTES > 48 * 1024 && !attr_done[variant]) {
+        hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, L::BYTES);
+        if (e != hipSuccess) return e;
+        attr_done[variant] = true;
+    }
+    hipLaunchKernelGGL(fn, grid, block, L::BYTES, s, a);
+    return hipGetLastError();
+}
+
+template <class T>
+hipError_t launch_tile(int amode, int variant, const KArgs& a, int batch, hipStream_t s) {
+    switch (amode) {
+        case A_ROW: return launch_mode<T, A_ROW>(variant, a, batch, s);
+        case A_COL: return launch_mode<T, A_COL>(variant, a, batch, s);
+        default: return launch_mode<T, A_CONV>(variant, a, batch, s);
+    }
+}
+
+template <class T>
+constexpr KernelEntry entry() {
+    return KernelEntry{T::BM, T::BN, T::BK, T::WM, T::WN, T::NT, 4, &launch_tile<T>};
+}
+
+const KernelEntry kTable[] = {
+    entry<Tile<128, 128, 32, 64, 64, 2>>(),   // default for large shapes
+    entry<Tile<128, 128, 16, 64, 64, 2>>(),
+    entry<Tile<256, 128, 16, 64, 64, 2>>(),
+    entry<Tile<128, 64, 32, 64, 32, 2>>(),
+    entry<Tile<64, 64, 32, 32, 32, 2>>(),     // default for small shapes
+    entry<Tile<64, 64, 16, 32, 32, 2>>(),
+};
+
+}  // namespace
+
+const KernelEntry* f32_kernels(int* count) {
+    *count = (int)(sizeof(kTable) / sizeof(kTable[0]));
+    return kTable;
+}
+
+}  // namespace tsg

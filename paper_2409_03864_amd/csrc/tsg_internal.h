@@ -1,0 +1,45 @@
+// Internal glue between the C-ABI layer (api.cpp) and the kernel translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tsg {
+
+// How op(A)(i,k) is addressed.
+enum AMode : int {
+    A_ROW = 0,   // A stored M x K, k contiguous
+    A_COL = 1,   // A stored K x M, i contiguous (transposed left operand read in place)
+    A_CONV = 2   // A is the implicit im2col matrix of an NHWC tensor, never materialised
+};
+
+// Kernel arguments, passed by value.
+struct KArgs {
+    const void* A;
+    const void* B;
+    float* C;
+    long long lda, ldb, ldc;
+    long long stride_a, stride_b, stride_c;   // batch strides (elements)
+    int M, N, K;
+    int tiles_m, tiles_n;
+    int m_main, n_main;      // extents of the divisible (unmasked) part of i and j
+    int k_full;              // number of complete BK steps (the rest of k is masked)
+    unsigned flags;
+    int raster;
+    // convolution geometry (A_CONV only)
+    int H, W, Cin, Ho, Wo, KW, sh, sw, ph, pw;
+};
+
+// One instantiated tile shape and its launchers.
+struct KernelEntry {
+    int bm, bn, bk, wm, wn;
+    int threads;
+    int vec;   // elements per 16-byte access for this dtype
+    // variant: 0 = vec, no remainder path; 1 = vec with remainder path; 2 = scalar
+    // accesses with remainder path
+    hipError_t (*launch)(int amode, int variant, const KArgs& a, int batch, hipStream_t s);
+};
+
+const KernelEntry* f32_kernels(int* count);
+const KernelEntry* bf16_kernels(int* count);
+
+}  // namespace tsg

@@ -1,0 +1,370 @@
+"""Parity of the HIP library against the CPU oracle, element by element, through the C
+ABI.  Tolerances (fp32 1e-4, bf16-in/fp32-accumulate 2e-2) are applied to both the
+normwise error max|d|/max|ref| and the componentwise error max |d_ij| / (|A|.|B|)_ij;
+integer-valued inputs (every fp32 summation order exact) must match bit for bit."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import oracle
+import synth
+import paper_2409_03864_amd as tsg
+
+TOL = {tsg.F32: 1e-4, tsg.BF16_F32ACC: 2e-2}
+DEV = "cuda:0"
+
+
+def dev(a):
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).to(DEV)
+    return torch.from_numpy(a).to(DEV)
+
+
+def run_gemm(dtype, A, B, *, trans_a=False, flags=0, C0=None, lda=None, ldb=None, ldc=None):
+    K, N = B.shape
+    M = A.shape[1] if trans_a else A.shape[0]
+    acols = A.shape[1]
+    lda, ldb, ldc = lda or acols, ldb or N, ldc or N
+    Ah = np.zeros((A.shape[0], lda), A.dtype); Ah[:, :acols] = A
+    Bh = np.zeros((K, ldb), B.dtype); Bh[:, :N] = B
+    Ch = np.full((M, ldc), np.float32(-77.0))
+    if C0 is not None:
+        Ch[:, :N] = C0
+    dA, dB, dC = dev(Ah), dev(Bh), dev(Ch)
+    fn = tsg.gemm_transA if trans_a else tsg.gemm
+    fn(dtype, M, N, K, dA, lda, dB, ldb, dC, ldc, flags)
+    torch.cuda.synchronize()
+    out = dC.cpu().numpy()
+    if ldc > N:
+        assert np.all(out[:, N:] == np.float32(-77.0)), "padding columns of C were written"
+    return out[:, :N]
+
+
+def check(C, A, B, dtype, *, trans_a=False, flags=0, C0=None, exact=False):
+    R, S = oracle.gemm(A, B, trans_a=trans_a)
+    ref = oracle.epilogue(R, flags & 3, C0)
+    if C0 is not None and flags & tsg.ACCUMULATE:
+        S = S + np.abs(C0)
+    if exact:
+        assert np.array_equal(C.astype(np.float64), ref)
+    else:
+        nw, cw = oracle.errors(C, ref, S)
+        assert nw <= TOL[dtype] and cw <= TOL[dtype], (nw, cw)
+
+
+def inputs(M, N, K, seed, dist, trans_a, dtype):
+    return synth.gemm_inputs(M, N, K, seed=seed, dist=dist, trans_a=trans_a, bf16=(dtype == tsg.BF16_F32ACC))
+
+
+@pytest.fixture(autouse=True)
+def _clear_pins():
+    yield
+    for op in (tsg.OP_GEMM, tsg.OP_GEMM_TRANSA, tsg.OP_CONV2D_NHWC):
+        for dt in (tsg.F32, tsg.BF16_F32ACC):
+            tsg.tile_config_set(op, dt, None)
+
+
+# shapes spanning several tiles with ragged tails in every dimension, plus degenerate ones
+SHAPES = [(1, 1, 1), (4, 4, 4), (5, 3, 2), (64, 64, 64), (65, 63, 33), (196, 256, 129), (130, 260, 72),
+          (257, 129, 40), (300, 70, 2305 // 5), (32, 512, 8), (512, 32, 100)]
+
+
+@pytest.mark.parametrize("dtype", [tsg.F32, tsg.BF16_F32ACC])
+@pytest.mark.parametrize("trans_a", [False, True])
+@pytest.mark.parametrize("M,N,K", SHAPES)
+def test_gemm_integer_inputs_bit_exact(dtype, trans_a, M, N, K):
+    A, B = inputs(M, N, K, 100 + M + N + K, "ints", trans_a, dtype)
+    C = run_gemm(dtype, A, B, trans_a=trans_a)
+    check(C, A, B, dtype, trans_a=trans_a, exact=True)
+
+
+@pytest.mark.parametrize("dtype", [tsg.F32, tsg.BF16_F32ACC])
+@pytest.mark.parametrize("trans_a", [False, True])
+@pytest.mark.parametrize("M,N,K", [(65, 63, 33), (196, 256, 461), (384, 256, 256), (256, 384, 512)])
+def test_gemm_random_within_tolerance(dtype, trans_a, M, N, K):
+    A, B = inputs(M, N, K, 7, "uniform", trans_a, dtype)
+    C = run_gemm(dtype, A, B, trans_a=trans_a)
+    check(C, A, B, dtype, trans_a=trans_a)
+
+
+@pytest.mark.parametrize("dtype", [tsg.F32, tsg.BF16_F32ACC])
+@pytest.mark.parametrize("op", [tsg.OP_GEMM, tsg.OP_GEMM_TRANSA])
+def test_every_instantiated_config_bit_exact(dtype, op):
+    """Each point of the search space, on a shape with remainders (edge variant) and on a
+    divisible shape (no-remainder variant), pinned with TSG_STRICT so no fallback hides it."""
+    trans = op == tsg.OP_GEMM_TRANSA
+    for (M, N, K) in [(512, 512, 256), (300, 200, 136), (259, 131, 77)]:
+        A, B = inputs(M, N, K, 11, "ints", trans, dtype)
+        R = oracle.gemm(A, B, trans_a=trans, with_s=False)
+        for i in range(tsg.tile_config_count(op, dtype)):
+            c = tsg.tile_config_enum(op, dtype, i)
+            if tsg.tile_config_check(op, dtype, M, N, K, c) != tsg.OK:
+                continue
+            tsg.tile_config_set(op, dtype, c)
+            C = run_gemm(dtype, A, B, trans_a=trans, flags=tsg.STRICT)
+            li = tsg.last_launch()
+            assert li.config.as_dict() == c.as_dict() and li.alternative == 0
+            assert (li.m_main, li.m_rest) == oracle.split(M, c.bm)[:2]
+            assert (li.k_main, li.k_rest) == oracle.split(K, c.bk)[:2]
+            assert np.array_equal(C.astype(np.float64), R), (M, N, K, c)
+
+
+@pytest.mark.parametrize("dtype", [tsg.F32, tsg.BF16_F32ACC])
+def test_flags_negate_is_a_sign_flip_and_accumulate_adds(dtype):
+    M, N, K = 130, 97, 200
+    A, B = inputs(M, N, K, 5, "uniform", False, dtype)
+    C = run_gemm(dtype, A, B)
+    Cn = run_gemm(dtype, A, B, flags=tsg.NEGATE)
+    assert np.array_equal(Cn.view(np.uint32), C.view(np.uint32) ^ np.uint32(0x80000000))
+    Z = np.zeros((M, N), np.float32)
+    Ca = run_gemm(dtype, A, B, flags=tsg.ACCUMULATE, C0=Z)
+    assert np.array_equal(Ca, C)                     # `+=` on a zero-initialised C
+    C0 = synth.uniform_pm1(9, 2, M * N).reshape(M, N)
+    for fl in (tsg.ACCUMULATE, tsg.ACCUMULATE | tsg.NEGATE):
+        Cb = run_gemm(dtype, A, B, flags=fl, C0=C0)
+        check(Cb, A, B, dtype, flags=fl, C0=C0)
+
+
+@pytest.mark.parametrize("dtype", [tsg.F32, tsg.BF16_F32ACC])
+def test_leading_dimensions_and_scalar_access_fallback(dtype):
+    """ld larger than the row; then an ld that breaks the 16-byte rule so the chain of
+    alternatives must end in the scalar-access variant (alternative 2)."""
+    M, N, K = 70, 52, 90
+    vmax = 4 if dtype == tsg.F32 else 8
+    for trans in (False, True):
+        A, B = inputs(M, N, K, 21, "ints", trans, dtype)
+        acols = A.shape[1]
+        C = run_gemm(dtype, A, B, trans_a=trans, lda=acols + 2 * vmax, ldb=N + vmax, ldc=N + 3)
+        assert tsg.last_launch().config.vec == vmax
+        check(C, A, B, dtype, trans_a=trans, exact=True)
+        C = run_gemm(dtype, A, B, trans_a=trans, lda=acols + 1, ldb=N + 1, ldc=N + 5)
+        li = tsg.last_launch()
+        assert li.alternative == 2 and li.config.vec == 1
+        check(C, A, B, dtype, trans_a=trans, exact=True)
+
+
+def test_strict_silenceable_failure_leaves_output_untouched():
+    dt, op = tsg.F32, tsg.OP_GEMM
+    c = tsg.tile_config_enum(op, dt, 0)
+    tsg.tile_config_set(op, dt, c)
+    M = N = K = 64
+    A, B = inputs(M, N, K, 3, "ints", False, dt)
+    Ah = np.zeros((M, K + 1), np.float32); Ah[:, :K] = A
+    dA, dB = dev(Ah), dev(B)
+    sentinel = synth.uniform_pm1(1, 5, M * N).reshape(M, N)
+    dC = dev(sentinel)
+    with pytest.raises(tsg.SilenceableError):
+        tsg.gemm(dt, M, N, K, dA, K + 1, dB, N, dC, N, tsg.STRICT)
+    torch.cuda.synchronize()
+    assert np.array_equal(dC.cpu().numpy().view(np.uint32), sentinel.view(np.uint32))
+    # without STRICT the chain of alternatives completes the call
+    tsg.gemm(dt, M, N, K, dA, K + 1, dB, N, dC, N, 0)
+    torch.cuda.synchronize()
+    assert tsg.last_launch().alternative == 2
+    assert np.array_equal(dC.cpu().numpy().astype(np.float64), oracle.gemm(A, B, with_s=False))
+
+
+def test_one_hot_and_identity_on_device():
+    M, N, K = 150, 140, 130
+    B = synth.uniform_pm1(2, 1, K * N).reshape(K, N)
+    A = np.zeros((M, K), np.float32); A[101, 77] = 1
+    C = run_gemm(tsg.F32, A, B)
+    exp = np.zeros((M, N), np.float32); exp[101] = B[77]
+    assert np.array_equal(C, exp)
+    At = np.zeros((K, M), np.float32); At[77, 101] = 1
+    assert np.array_equal(run_gemm(tsg.F32, At, B, trans_a=True), exp)
+    Bsq = synth.uniform_pm1(2, 3, 130 * 130).reshape(130, 130)
+    assert np.array_equal(run_gemm(tsg.F32, np.eye(130, dtype=np.float32), Bsq), Bsq)
+
+
+@pytest.mark.parametrize("dtype", [tsg.F32, tsg.BF16_F32ACC])
+def test_batched_paper_loop_nest(dtype):
+    """Case Study 4, Fig. 7: batch 6, 196 x 256 x 2305 (remainders in i and k)."""
+    P = synth.PAPER_BATCH_MATMUL
+    Bt, M, N, K = P["B"], P["M"], P["N"], P["K"]
+    bf = dtype == tsg.BF16_F32ACC
+    for dist, exact in (("ints", True), ("normal", False)):
+        As, Bs = [], []
+        for b in range(Bt):
+            a, bb = synth.gemm_inputs(M, N, K, seed=40 + b, dist=dist, bf16=bf)
+            As.append(a); Bs.append(bb)
+        A, B = np.stack(As), np.stack(Bs)
+        dA, dB = dev(A), dev(B)
+        dC = torch.zeros((Bt, M, N), dtype=torch.float32, device=DEV)
+        tsg.gemm_batched(dtype, False, Bt, M, N, K, dA, K, M * K, dB, N, K * N, dC, N, M * N, tsg.ACCUMULATE)
+        torch.cuda.synchronize()
+        li = tsg.last_launch()
+        assert li.m_main + li.m_rest == 196 and li.k_rest == K - li.k_main and li.k_rest > 0
+        C = dC.cpu().numpy()
+        for b in range(Bt):
+            check(C[b], A[b], B[b], dtype, exact=exact)
+
+
+# ------------------------------------------------------------------ convolution
+
+def run_conv(dtype, x, w, stride, pad, flags=0, y0=None):
+    N, H, W, Cin = x.shape
+    KH, KW, _, Cout = w.shape
+    Ho, Wo = oracle.conv_out_dim(H, KH, stride[0], pad[0]), oracle.conv_out_dim(W, KW, stride[1], pad[1])
+    dx, dw = dev(x), dev(w)
+    dy = dev(y0) if y0 is not None else torch.full((N, Ho, Wo, Cout), -55.0, dtype=torch.float32, device=DEV)
+    tsg.conv2d_nhwc(dtype, N, H, W, Cin, Cout, KH, KW, stride[0], stride[1], pad[0], pad[1], dx, dw, dy, flags)
+    torch.cuda.synchronize()
+    return dy.cpu().numpy()
+
+
+CONV_GEOMS = [
+    # N, H, W, Cin, Cout, KH, KW, stride, pad
+    (1, 3, 3, 2, 2, 3, 3, (1, 1), (1, 1)),
+    (2, 9, 7, 4, 6, 3, 3, (1, 1), (1, 1)),
+    (2, 12, 10, 8, 20, 3, 3, (2, 2), (1, 1)),
+    (1, 14, 14, 64, 64, 3, 3, (1, 1), (1, 1)),
+    (2, 11, 13, 5, 7, 3, 2, (1, 2), (2, 0)),       # Cin, Cout not multiples of 4: scalar path
+    (3, 8, 8, 16, 32, 1, 1, (1, 1), (0, 0)),
+    (1, 20, 20, 12, 40, 5, 5, (1, 1), (2, 2)),
+    (2, 16, 16, 32, 70, 3, 3, (1, 1), (0, 0)),
+]
+
+
+@pytest.mark.parametrize("geom", CONV_GEOMS)
+def test_conv_integer_inputs_bit_exact(geom):
+    N, H, W, Cin, Cout, KH, KW, st, pd = geom
+    x, w = synth.conv_inputs(N, H, W, Cin, Cout, KH, KW, seed=77, dist="ints")
+    y = run_conv(tsg.F32, x, w, st, pd)
+    R = oracle.conv2d_nhwc(x, w, stride=st, pad=pd, with_s=False)
+    assert y.shape == R.shape
+    assert np.array_equal(y.astype(np.float64), R)
+
+
+@pytest.mark.parametrize("geom", CONV_GEOMS[1:5])
+def test_conv_random_and_flags(geom):
+    N, H, W, Cin, Cout, KH, KW, st, pd = geom
+    x, w = synth.conv_inputs(N, H, W, Cin, Cout, KH, KW, seed=78)
+    R, S = oracle.conv2d_nhwc(x, w, stride=st, pad=pd)
+    y = run_conv(tsg.F32, x, w, st, pd)
+    nw, cw = oracle.errors(y, R, S)
+    assert nw <= 1e-4 and cw <= 1e-4
+    yn = run_conv(tsg.F32, x, w, st, pd, flags=tsg.NEGATE)
+    assert np.array_equal(yn.view(np.uint32), y.view(np.uint32) ^ np.uint32(0x80000000))
+    y0 = synth.uniform_pm1(3, 9, R.size).reshape(R.shape)
+    ya = run_conv(tsg.F32, x, w, st, pd, flags=tsg.ACCUMULATE, y0=y0)
+    nw, cw = oracle.errors(ya, oracle.epilogue(R, oracle.ACCUMULATE, y0), S + np.abs(y0))
+    assert nw <= 1e-4 and cw <= 1e-4
+
+
+def test_conv_every_config_and_zero_pad_identity():
+    """All instantiated configs on one geometry; and conv(x, pad 1) == conv(padded x, pad 0)
+    bitwise for the same config (padding taps contribute exact zeros in any order)."""
+    N, H, W, Cin, Cout = 2, 10, 9, 16, 24
+    x, w = synth.conv_inputs(N, H, W, Cin, Cout, 3, 3, seed=79, dist="ints")
+    R = oracle.conv2d_nhwc(x, w, pad=(1, 1), with_s=False)
+    xp = np.zeros((N, H + 2, W + 2, Cin), np.float32); xp[:, 1:-1, 1:-1] = x
+    op, dt = tsg.OP_CONV2D_NHWC, tsg.F32
+    for i in range(tsg.tile_config_count(op, dt)):
+        c = tsg.tile_config_enum(op, dt, i)
+        tsg.tile_config_set(op, dt, c)
+        y = run_conv(dt, x, w, (1, 1), (1, 1), flags=tsg.STRICT)
+        assert tsg.last_launch().config.as_dict() == c.as_dict()
+        assert np.array_equal(y.astype(np.float64), R), c
+        yp = run_conv(dt, xp, w, (1, 1), (0, 0), flags=tsg.STRICT)
+        assert np.array_equal(yp, y)
+
+
+def test_conv_all_ones_counts_valid_taps_on_device():
+    x = np.ones((2, 12, 12, 64), np.float32)
+    w = np.ones((3, 3, 64, 64), np.float32)
+    y = run_conv(tsg.F32, x, w, (1, 1), (1, 1))
+    assert np.all(y[:, 0, 0] == 256) and np.all(y[:, 0, 1:-1] == 384) and np.all(y[:, 1:-1, 1:-1] == 576)
+
+
+# ------------------------------------------------------------------ the five workloads
+
+def test_config1_gemm_256():
+    c, A, B = synth.config_inputs(1)
+    C = run_gemm(tsg.F32, A, B)
+    check(C, A, B, tsg.F32)
+    Ca = run_gemm(tsg.F32, A, B, flags=tsg.ACCUMULATE, C0=np.zeros((256, 256), np.float32))
+    assert np.array_equal(C, Ca)
+
+
+def test_config2_gemm_transA_1024():
+    c, A, B = synth.config_inputs(2)
+    C = run_gemm(tsg.F32, A, B, trans_a=True)
+    check(C, A, B, tsg.F32, trans_a=True)
+    # the folded transpose equals the materialised one, bit for bit (same kernel arithmetic
+    # order is not guaranteed across operand layouts, so compare through the oracle bound)
+    C2 = run_gemm(tsg.F32, np.ascontiguousarray(A.T), B)
+    check(C2, A, B, tsg.F32, trans_a=True)
+
+
+def _sampled_rows_cols(C, A, B, dtype, flags, nsamp=48, seed=1234):
+    """Oracle on a pseudo-random set of full rows and full columns of the product."""
+    M, N = C.shape
+    rows = np.sort(synth.raw_bits(seed, 0, nsamp) % np.uint64(M)).astype(np.int64)
+    cols = np.sort(synth.raw_bits(seed, 1, nsamp) % np.uint64(N)).astype(np.int64)
+    rows[0], rows[-1], cols[0], cols[-1] = 0, M - 1, 0, N - 1
+    sgn = -1.0 if flags & tsg.NEGATE else 1.0
+    R, S = oracle.gemm(np.ascontiguousarray(A[rows]), B)
+    nw, cw = oracle.errors(C[rows], sgn * R, S)
+    assert nw <= TOL[dtype] and cw <= TOL[dtype], ("rows", nw, cw)
+    R, S = oracle.gemm(A, np.ascontiguousarray(B[:, cols]))
+    nw, cw = oracle.errors(C[:, cols], sgn * R, S)
+    assert nw <= TOL[dtype] and cw <= TOL[dtype], ("cols", nw, cw)
+
+
+def test_config3_gemm_4096_sampled_and_all_ones_full():
+    c, A, B = synth.config_inputs(3)
+    C = run_gemm(tsg.F32, A, B)
+    li = tsg.last_launch()
+    assert li.edge == 0 and li.alternative == 1
+    _sampled_rows_cols(C, A, B, tsg.F32, 0)
+    ones = np.ones((4096, 4096), np.float32)
+    assert np.all(run_gemm(tsg.F32, ones, ones) == 4096.0)
+    Ai, Bi = synth.gemm_inputs(4096, 4096, 4096, seed=2, dist="ints")
+    Ci = run_gemm(tsg.F32, Ai, Bi)
+    ref = Ai.astype(np.float64) @ Bi.astype(np.float64)       # exact: small integers
+    rows = [0, 1, 2047, 4095]
+    assert np.array_equal(oracle.gemm(np.ascontiguousarray(Ai[rows]), Bi, with_s=False), ref[rows])
+    assert np.array_equal(Ci.astype(np.float64), ref)
+
+
+def test_config4_conv_resnet_layer():
+    c, x, w = synth.config_inputs(4)
+    y = run_conv(tsg.F32, x, w, (1, 1), (1, 1))
+    li = tsg.last_launch()
+    assert li.tiles_m * li.config.bm >= 25088 and li.k_main == 576
+    R, S = oracle.conv2d_nhwc(x, w, pad=(1, 1))
+    nw, cw = oracle.errors(y, R, S)
+    assert nw <= 1e-4 and cw <= 1e-4, (nw, cw)
+
+
+def test_config5_bf16_gemm_8192_negated_sampled_and_all_ones_full():
+    c, A, B = synth.config_inputs(5)
+    C = run_gemm(tsg.BF16_F32ACC, A, B, flags=tsg.NEGATE)
+    _sampled_rows_cols(C, A, B, tsg.BF16_F32ACC, tsg.NEGATE, nsamp=32)
+    del C
+    ones = np.full((8192, 8192), 0x3F80, np.uint16)
+    assert np.all(run_gemm(tsg.BF16_F32ACC, ones, ones, flags=tsg.NEGATE) == -8192.0)
+
+
+# ------------------------------------------------------------------ search
+
+def test_autotune_pins_the_fastest_legal_config():
+    M, N, K = 512, 384, 256
+    A, B = inputs(M, N, K, 8, "ints", False, tsg.F32)
+    dA, dB = dev(A), dev(B)
+    dC = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+    best, ms, log = tsg.autotune_gemm(tsg.F32, False, M, N, K, dA, K, dB, N, dC, N, iters=3)
+    assert len(log) == tsg.tile_config_count(tsg.OP_GEMM, tsg.F32)
+    timed = [r for r in log if r.ms >= 0]
+    assert timed and abs(min(r.ms for r in timed) - ms) < 1e-6
+    bests = [r.best_ms for r in log if r.best_ms >= 0]
+    assert all(a >= b for a, b in zip(bests, bests[1:]))          # best-so-far curve (Fig. 11)
+    assert tsg.tile_config_get(tsg.OP_GEMM, tsg.F32, M, N, K).as_dict() == best.as_dict()
+    tsg.gemm(tsg.F32, M, N, K, dA, K, dB, N, dC, N, tsg.STRICT)
+    torch.cuda.synchronize()
+    assert np.array_equal(dC.cpu().numpy().astype(np.float64), oracle.gemm(A, B, with_s=False))

@@ -1,0 +1,191 @@
+"""Host-side behaviour of the C-ABI library (no GPU): exported symbols, the loop
+split, tile-config legality, index maps and the error model."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2409_03864_amd as tsg
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "tsg.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(tsg_[a-zA-Z0-9_]+)\s*\(", hdr))
+    assert len(declared) >= 17
+    lib = ctypes.CDLL(tsg.LIB_PATH)
+    for name in sorted(declared):
+        assert hasattr(lib, name), name
+    assert declared == set(tsg.EXPORTS)
+    assert tsg.version() >= 1
+
+
+def test_split_matches_paper_and_oracle(golden_dir):
+    for line in open(os.path.join(golden_dir, "paper_split_examples.txt")):
+        line = line.split("#")[0].split()
+        if line:
+            ub, d, main, rest, tiles = map(int, line)
+            assert tsg.split(ub, d) == (main, rest, tiles)
+    for ub in (0, 1, 31, 32, 33, 196, 2305, 4096, 25088):
+        for d in (0, 1, 8, 32, 64, 128, 256):
+            assert tsg.split(ub, d) == oracle.split(ub, d)
+    with pytest.raises(tsg.TsgError):
+        tsg.split(-1, 8)
+    with pytest.raises(tsg.TsgError):
+        tsg.split(8, -1)
+
+
+def test_search_space_enumeration():
+    for op in (tsg.OP_GEMM, tsg.OP_GEMM_TRANSA, tsg.OP_CONV2D_NHWC):
+        for dt, vmax in ((tsg.F32, 4), (tsg.BF16_F32ACC, 8)):
+            n = tsg.tile_config_count(op, dt)
+            assert n >= 6
+            seen = set()
+            for i in range(n):
+                c = tsg.tile_config_enum(op, dt, i)
+                assert c.bm % c.wm == 0 and c.bn % c.wn == 0 and c.wm % 32 == 0 and c.wn % 32 == 0
+                assert c.vec in (1, vmax) and c.raster in (0, 1)
+                key = tuple(c.as_dict().values())
+                assert key not in seen
+                seen.add(key)
+                assert tsg.tile_config_check(op, dt, 4096, 4096, 4096, c, contig=64) == tsg.OK
+            with pytest.raises(tsg.TsgError):
+                tsg.tile_config_enum(op, dt, n)
+    assert tsg.tile_config_count(7, 0) == 0
+
+
+def test_vect_constraint_matches_fig10_rule():
+    """vec > 1 is legal exactly when the contiguous extents are multiples of the vector
+    size: the library's check must agree with the oracle's statement of Fig. 10."""
+    c = tsg.tile_config_enum(tsg.OP_GEMM, tsg.F32, 0)
+    assert c.vec == 4
+    for K in (2304, 2305, 2306, 2308, 64):
+        for N in (256, 255, 64, 66):
+            legal = oracle.vect_legal(K, 0, 4, 1) and oracle.vect_legal(N, 0, 4, 1)
+            st = tsg.tile_config_check(tsg.OP_GEMM, tsg.F32, 196, N, K, c)
+            assert st == (tsg.OK if legal else tsg.E_SILENCEABLE), (K, N)
+    # transposed left operand: its contiguous extent is M
+    assert tsg.tile_config_check(tsg.OP_GEMM_TRANSA, tsg.F32, 196, 256, 2305, c) == tsg.OK
+    assert tsg.tile_config_check(tsg.OP_GEMM_TRANSA, tsg.F32, 197, 256, 2304, c) == tsg.E_SILENCEABLE
+    # gathered operand: runs of Cin
+    assert tsg.tile_config_check(tsg.OP_CONV2D_NHWC, tsg.F32, 25088, 64, 576, c, contig=64) == tsg.OK
+    assert tsg.tile_config_check(tsg.OP_CONV2D_NHWC, tsg.F32, 25088, 64, 27, c, contig=3) == tsg.E_SILENCEABLE
+    # vec = 1 has no precondition
+    c.vec = 1
+    assert tsg.tile_config_check(tsg.OP_GEMM, tsg.F32, 196, 255, 2305, c) == tsg.OK
+    # a vector size the hardware path does not have
+    c.vec = 2
+    assert tsg.tile_config_check(tsg.OP_GEMM, tsg.F32, 196, 256, 2304, c) == tsg.E_SILENCEABLE
+
+
+def test_tile_zero_means_default_and_oversized_tile_is_legal():
+    """Sec. 3.4: tiling by 0 is a no-op (library default stands); a tile larger than the
+    extent is legal (the whole loop is remainder)."""
+    z = tsg.TileConfig()
+    assert tsg.tile_config_check(tsg.OP_GEMM, tsg.F32, 512, 512, 512, z) == tsg.OK
+    big = tsg.tile_config_enum(tsg.OP_GEMM, tsg.F32, 0)
+    assert big.bm >= 128
+    assert tsg.tile_config_check(tsg.OP_GEMM, tsg.F32, 5, 8, 12, big) == tsg.OK
+    assert oracle.normalise_tile(5, big.bm) == 5          # the oracle's reading of the same rule
+    # not instantiated -> silenceable, like a microkernel library lacking a size
+    odd = tsg.TileConfig(bm=96, bn=96, bk=32, wm=32, wn=32, vec=4, raster=0)
+    assert tsg.tile_config_check(tsg.OP_GEMM, tsg.F32, 512, 512, 512, odd) == tsg.E_SILENCEABLE
+    neg = tsg.TileConfig(bm=-1)
+    assert tsg.tile_config_check(tsg.OP_GEMM, tsg.F32, 512, 512, 512, neg) == tsg.E_INVALID
+
+
+def test_config_set_get_roundtrip_and_rollback():
+    op, dt = tsg.OP_GEMM, tsg.F32
+    tsg.tile_config_set(op, dt, None)
+    h = tsg.tile_config_get(op, dt, 4096, 4096, 4096)
+    assert (h.bm, h.bn) == (128, 128) and h.vec == 4
+    hs = tsg.tile_config_get(op, dt, 256, 256, 256)
+    assert hs.bm * hs.bn < h.bm * h.bn           # small problems get small tiles
+    c = tsg.tile_config_enum(op, dt, tsg.tile_config_count(op, dt) - 1)
+    tsg.tile_config_set(op, dt, c)
+    g = tsg.tile_config_get(op, dt, 4096, 4096, 4096)
+    assert g.as_dict() == c.as_dict()
+    # a failing set leaves the registry unchanged
+    with pytest.raises(tsg.SilenceableError):
+        tsg.tile_config_set(op, dt, tsg.TileConfig(bm=96, bn=96, bk=32, wm=32, wn=32, vec=4))
+    assert tsg.tile_config_get(op, dt, 4096, 4096, 4096).as_dict() == c.as_dict()
+    # other (op, dtype) slots are independent
+    assert tsg.tile_config_get(tsg.OP_GEMM_TRANSA, dt, 4096, 4096, 4096).as_dict() == h.as_dict()
+    tsg.tile_config_set(op, dt, None)
+    assert tsg.tile_config_get(op, dt, 4096, 4096, 4096).as_dict() == h.as_dict()
+
+
+@pytest.mark.parametrize("geom", [
+    (2, 4, 5, 3, 3, 2, 2, 1, 1, 1),
+    (1, 7, 7, 4, 3, 3, 1, 1, 0, 0),
+    (3, 9, 6, 2, 1, 1, 2, 2, 0, 0),
+    (1, 5, 5, 1, 5, 5, 1, 1, 2, 2),
+    (8, 56, 56, 64, 3, 3, 1, 1, 1, 1),
+])
+def test_conv_index_map_bit_exact(geom):
+    N, H, W, Cin, KH, KW, sh, sw, ph, pw = geom
+    ref = oracle.conv2d_index_map(N, H, W, Cin, KH, KW, (sh, sw), (ph, pw))
+    off = np.full(ref.shape, 12345, np.int32)
+    tsg.conv2d_index_map(N, H, W, Cin, KH, KW, sh, sw, ph, pw, off)
+    assert off.dtype == ref.dtype and np.array_equal(off, ref)
+
+
+def test_gemm_index_map_bit_exact():
+    for trans in (False, True):
+        ref = oracle.gemm_index_map(37, 53, 61, trans)
+        off = np.zeros((37, 53), np.int64)
+        tsg.gemm_index_map(trans, 37, 53, 61, off)
+        assert np.array_equal(off, ref)
+    with pytest.raises(tsg.TsgError):
+        tsg.gemm_index_map(True, 37, 53, 30, np.zeros((37, 53), np.int64))
+
+
+FAKE = 0x7F0000001000     # never dereferenced: every call below fails before a launch
+
+
+def test_invalid_arguments_are_definite_errors():
+    ok = dict(dtype=tsg.F32, M=8, N=8, K=8, A=FAKE, lda=8, B=FAKE, ldb=8, C=FAKE, ldc=8, flags=0, stream=0)
+    bad = [dict(A=None), dict(B=None), dict(C=None), dict(M=0), dict(N=-1), dict(K=0), dict(lda=7), dict(ldb=7),
+           dict(ldc=7), dict(flags=64), dict(dtype=9), dict(M=1 << 31)]
+    for b in bad:
+        kw = dict(ok, **b)
+        with pytest.raises(tsg.TsgError) as e:
+            tsg.gemm(**kw)
+        assert e.value.status == tsg.E_INVALID, b
+    with pytest.raises(tsg.TsgError) as e:
+        tsg.gemm_transA(tsg.F32, 16, 8, 4, FAKE, 8, FAKE, 8, FAKE, 8, 0, 0)      # lda < M
+    assert e.value.status == tsg.E_INVALID
+    with pytest.raises(tsg.TsgError) as e:
+        tsg.conv2d_nhwc(tsg.F32, 1, 2, 2, 4, 4, 3, 3, 1, 1, 0, 0, FAKE, FAKE, FAKE, 0, 0)   # kernel > image
+    assert e.value.status == tsg.E_INVALID
+    with pytest.raises(tsg.TsgError) as e:
+        tsg.gemm_batched(tsg.F32, 0, 2, 8, 8, 8, FAKE, 8, 64, FAKE, 8, 64, FAKE, 8, 32, 0, 0)  # C overlap
+    assert e.value.status == tsg.E_INVALID
+
+
+def test_strict_call_with_failed_precondition_is_silenceable_and_enqueues_nothing():
+    """The pinned config wants 16-byte accesses; lda = 9 breaks the divisibility rule.
+    With TSG_STRICT there is no further alternative: silenceable, nothing launched (the
+    pointers are fake, so a launch attempt would have been a runtime error instead)."""
+    op, dt = tsg.OP_GEMM, tsg.F32
+    c = tsg.tile_config_enum(op, dt, 0)
+    assert c.vec == 4
+    tsg.tile_config_set(op, dt, c)
+    try:
+        with pytest.raises(tsg.SilenceableError):
+            tsg.gemm(dt, 8, 8, 8, FAKE, 9, FAKE, 8, FAKE, 8, tsg.STRICT, 0)
+        with pytest.raises(tsg.SilenceableError):
+            tsg.gemm(dt, 8, 8, 8, FAKE + 4, 8, FAKE, 8, FAKE, 8, tsg.STRICT, 0)   # misaligned base
+    finally:
+        tsg.tile_config_set(op, dt, None)
+
+
+def test_status_strings():
+    assert "ok" in tsg.status_string(tsg.OK)
+    assert "silenceable" in tsg.status_string(tsg.E_SILENCEABLE)
+    assert "definite" in tsg.status_string(tsg.E_INVALID) and "definite" in tsg.status_string(tsg.E_RUNTIME)
