@@ -138,10 +138,11 @@ def test_leading_dimensions_and_scalar_access_fallback(dtype):
     for trans in (False, True):
         A, B = inputs(M, N, K, 21, "ints", trans, dtype)
         acols = A.shape[1]
-        C = run_gemm(dtype, A, B, trans_a=trans, lda=acols + 2 * vmax, ldb=N + vmax, ldc=N + 3)
+        up = lambda v: -(-v // vmax) * vmax
+        C = run_gemm(dtype, A, B, trans_a=trans, lda=up(acols) + 2 * vmax, ldb=up(N) + vmax, ldc=N + 3)
         assert tsg.last_launch().config.vec == vmax
         check(C, A, B, dtype, trans_a=trans, exact=True)
-        C = run_gemm(dtype, A, B, trans_a=trans, lda=acols + 1, ldb=N + 1, ldc=N + 5)
+        C = run_gemm(dtype, A, B, trans_a=trans, lda=up(acols) + 1, ldb=up(N) + 1, ldc=N + 5)
         li = tsg.last_launch()
         assert li.alternative == 2 and li.config.vec == 1
         check(C, A, B, dtype, trans_a=trans, exact=True)
