@@ -61,7 +61,10 @@ def main() -> int:
     ap.add_argument("--workload", type=int, default=3, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--no-tune", action="store_true", help="use the shape heuristic instead of the tuner")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
-    ap.add_argument("--cpu-rows", type=int, default=1024, help="rows of the product the oracle is timed on")
+    ap.add_argument("--cpu-rows", type=int, default=4096, help="rows of the product the oracle is timed on")
+    ap.add_argument("--pin", default="", help="bm,bn,bk,wm,wn,vec,raster: pin this tile config instead of tuning")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
+                    help="also run one plain device copy of this many MiB (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU; --gpus %d is not supported "
@@ -119,7 +122,21 @@ def main() -> int:
         def tune():
             return tsg.autotune_gemm(dt, trans, M, N, K, dA, lda, dB, N, dC, N, flags, iters=5)
 
+    if args.copy_calibration:
+        n = args.copy_calibration * (1 << 20) // 4
+        src = torch.ones(n, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)            # reads n*4 bytes, writes n*4 bytes
+        torch.cuda.synchronize()
+        log("copy calibration: one device copy of %d MiB (reads and writes that many bytes)" % args.copy_calibration)
+        del src, dst
+
     tuner_log = None
+    if args.pin:
+        v = [int(t) for t in args.pin.split(",")]
+        tsg.tile_config_set(op, dt, tsg.TileConfig(bm=v[0], bn=v[1], bk=v[2], wm=v[3], wn=v[4], vec=v[5], raster=v[6]))
+        args.no_tune = True
     if not args.no_tune:
         best, best_ms, recs = tune()
         tuner_log = [dict(r.config.as_dict(), ms=round(r.ms, 5)) for r in recs]
