@@ -63,24 +63,40 @@ tsg_tile_config config_of(const KernelEntry& e, int vec, int raster) {
     return c;
 }
 
-// Shape heuristic: estimated time ~ (rounds of workgroups over the CUs) x tile area /
-// (relative efficiency of the tile); the first table entry with the lowest estimate wins.
+// Shape heuristic: a small analytical model of one CU.  A workgroup step costs its MFMA
+// cycles on the SIMD it shares with the other resident workgroups, but never less than
+// the global-memory latency its single prefetch has to cover; the kernel costs
+// (rounds of workgroups) x (steps x step cost + one latency).  The table entry with the
+// lowest estimate wins; the tuner (tsg_autotune_*) replaces the guess by measurement.
 tsg_tile_config heuristic(tsg_dtype dt, int64_t batch, int64_t M, int64_t N, int64_t K) {
-    (void)K;
     int n = 0;
     const KernelEntry* t = kernels(dt, &n);
+    const double kLatency = 1400.0;      // cycles from issuing a tile's loads to LDS-ready
+    const double kLds = 160.0 * 1024;
     double best = 0;
     int best_i = 0;
     for (int i = 0; i < n; ++i) {
-        const double tiles = (double)((M + t[i].bm - 1) / t[i].bm) * (double)((N + t[i].bn - 1) / t[i].bn) * (double)batch;
-        const double rounds = std::max(1.0, (double)(int64_t)((tiles + kCUs - 1) / kCUs));
-        const double area = (double)t[i].bm * t[i].bn;
-        // larger wave tiles reuse each LDS fragment more often
-        const double eff = 1.0 - 8.0 / (t[i].wm + t[i].wn) - 2.0 / t[i].bk;
-        const double est = rounds * area / eff;
+        const KernelEntry& e = t[i];
+        const double tiles = (double)((M + e.bm - 1) / e.bm) * (double)((N + e.bn - 1) / e.bn) * (double)batch;
+        const double blocks = (e.wm / 32) * (e.wn / 32);
+        const double wg_wps = e.threads / 256.0;                        // waves per SIMD of one workgroup
+        const double wps_cap = (double)(int)(512.0 / (blocks * 16.0 + 64.0));   // register-file limit
+        const double resident = std::max(1.0, std::min((double)(int)(kLds / e.lds_bytes),
+                                                       (double)(int)(wps_cap / wg_wps)));
+        const double rounds = (double)(int64_t)((tiles + kCUs * resident - 1) / (kCUs * resident));
+        const double conc = std::min(resident, (double)(int64_t)((tiles + kCUs - 1) / kCUs));
+        const double steps = (double)((K + e.bk - 1) / e.bk);
+        // cycles one wave spends in MFMA per step: fp32 32x32x2 = 64 cycles, bf16 32x32x16 = 32
+        const double wave_mfma = dt == TSG_F32 ? blocks * e.bk * 32.0 : blocks * e.bk * 2.0;
+        const double wg_mfma = wave_mfma * wg_wps;
+        // fewer waves per SIMD hide less of the barrier and LDS latency; small wave tiles
+        // re-read LDS more often per MFMA (factors fitted to measured 4096^3 runs)
+        const double ineff = (1.0 + 0.4 / (conc * wg_wps)) * (1.0 + 16.0 / (e.wm + e.wn));
+        const double step_cost = std::max(conc * wg_mfma * ineff, kLatency + 0.2 * wg_mfma);
+        const double est = rounds * (steps * step_cost + kLatency + 600.0);
         if (i == 0 || est < best * 0.999) { best = est; best_i = i; }
     }
-    return config_of(t[best_i], vec_max(dt), 1);
+    return config_of(t[best_i], vec_max(dt), dt == TSG_F32 ? 0 : 1);
 }
 
 // Fill zero fields ("tiling by 0 is a no-op": the library default stands) from `def`.

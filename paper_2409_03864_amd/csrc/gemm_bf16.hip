@@ -1,9 +1,14 @@
 // bfloat16-operand contraction kernels for gfx950: C(fp32) = +-op(A).B (+C) with
 // v_mfma_f32_32x32x16_bf16 (fp32 accumulate).  Same tiling, split and address generators
-// as the fp32 kernels; operands are staged in LDS with k contiguous per row so that a
-// lane's eight consecutive k values are one 16-byte read.  An operand that is NOT
-// k-contiguous in memory (B, and op(A) when the left operand is stored transposed) is
-// transposed on its way into LDS.
+// as the fp32 kernels.  The MFMA wants, per lane, eight consecutive k values of one row
+// of op(A) (one column of B).  A k-contiguous operand (A_ROW, A_CONV) is staged as
+// [row][k] and fetched with one 16-byte LDS read.  An operand that is contiguous along
+// i or j instead (B, and op(A) when the left operand is stored transposed) is staged
+// exactly as it lies in memory, [k][j], and fetched with the transposing LDS read
+// ds_read_b64_tr_b16: within a 16-lane group, lane l receives element (l % 4) of the four
+// 8-byte rows addressed by lanes l/4, l/4 + 4, l/4 + 8, l/4 + 12.  Pointing lane s of a
+// group at row k0 + s/4, columns j0 + 4*(s%4) .. +3 therefore hands lane l the four
+// values B[k0 .. k0+3][j0 + l]: no transposition in registers or on the store side.
 #include "tsg_internal.h"
 
 namespace tsg {
@@ -13,6 +18,8 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned short u16;
 typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) bf16x4* lds_bf16x4_ptr;
 
 constexpr unsigned FLAG_NEGATE = 1u, FLAG_ACCUMULATE = 2u;
 constexpr int kXcds = 8, kGroupM = 8;
@@ -23,9 +30,11 @@ struct Tile {
     static constexpr int WAVES_M = BM / WM, WAVES_N = BN / WN;
     static constexpr int NT = 64 * WAVES_M * WAVES_N;
     static constexpr int MI = WM / 32, NI = WN / 32;
-    static constexpr int LD = BK + 8;   // LDS row pitch in elements (144 B at BK = 64)
-    static constexpr int A_SIZE = BM * LD, B_SIZE = BN * LD, STAGE = A_SIZE + B_SIZE;
-    static constexpr int BYTES = 2 * STAGE * 2;
+    // LDS pitches in elements.  [row][k] tiles: +8 (16 B) makes the 16-byte reads of 16
+    // consecutive rows hit distinct banks.  [k][j] tiles: +32 (64 B) puts the four rows of
+    // one transposing read in four different 64-byte bank ranges.
+    static constexpr int LDK = BK + 8;
+    static constexpr int LDA_T = BM + 32, LDB = BN + 32;
     static_assert(BM % WM == 0 && BN % WN == 0 && WM % 32 == 0 && WN % 32 == 0 && BK % 16 == 0, "tile");
 };
 
@@ -49,7 +58,10 @@ __device__ __forceinline__ void tile_coords(const KArgs& p, int bid, int& tm, in
 
 template <class T, int AMODE, int VEC, bool EDGE>
 __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_kernel(const KArgs p) {
-    constexpr int BM = T::BM, BN = T::BN, BK = T::BK, NT = T::NT, MI = T::MI, NI = T::NI, LD = T::LD;
+    constexpr int BM = T::BM, BN = T::BN, BK = T::BK, NT = T::NT, MI = T::MI, NI = T::NI;
+    constexpr bool A_KMAJ = (AMODE != A_COL);
+    constexpr int LDA = A_KMAJ ? T::LDK : T::LDA_T, LDB = T::LDB;
+    constexpr int A_SIZE = A_KMAJ ? BM * LDA : BK * LDA, B_SIZE = BK * LDB, STAGE = A_SIZE + B_SIZE;
     extern __shared__ __attribute__((aligned(16))) u16 smem16[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -68,7 +80,6 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_kernel(const KArgs p
 
     // 8-element (16-byte) chunks along the contiguous dimension of each stored operand.
     // kmaj == true: the stored rows run along k (A_ROW, A_CONV); false: along i or j.
-    constexpr bool A_KMAJ = (AMODE != A_COL);
     constexpr int A_CPR = A_KMAJ ? BK / 8 : BM / 8;
     constexpr int A_ROWS = A_KMAJ ? BM : BK;
     constexpr int A_RPP = NT / A_CPR, PA = A_ROWS / A_RPP;
@@ -170,24 +181,25 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_kernel(const KArgs p
     };
 
     auto store_tiles = [&](int stage) {
-        u16* As = smem16 + stage * T::STAGE;
-        u16* Bs = As + T::A_SIZE;
+        u16* As = smem16 + stage * STAGE;
+        u16* Bs = As + A_SIZE;
 #pragma unroll
-        for (int q = 0; q < PA; ++q) {
-            const int r = a_r + q * A_RPP;
-            if constexpr (A_KMAJ) {
-                *(u16x8*)(As + r * LD + a_c) = ra[q];
-            } else {
+        for (int q = 0; q < PA; ++q)
+            *(u16x8*)(As + (a_r + q * A_RPP) * LDA + a_c) = ra[q];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) As[(a_c + e) * LD + r] = ra[q][e];   // transpose: row = i, col = k
-            }
-        }
-#pragma unroll
-        for (int q = 0; q < PB; ++q) {
-            const int r = b_r + q * B_RPP;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) Bs[(b_c + e) * LD + r] = rb[q][e];       // transpose: row = j, col = k
-        }
+        for (int q = 0; q < PB; ++q)
+            *(u16x8*)(Bs + (b_r + q * B_RPP) * LDB + b_c) = rb[q];
+    };
+
+    // lane -> source row / column of the transposing read (see the header comment)
+    const int tr_row = 8 * lh + ((lane & 15) >> 2);          // k offset inside a 16-wide k step
+    const int tr_col = (lane & 16) + 4 * (lane & 3);         // i or j offset inside a 32-wide block
+
+    auto read_tr = [&](const u16* tile, int ld, int k, int col) -> bf16x8 {
+        const u16* p0 = tile + (k + tr_row) * ld + col + tr_col;
+        const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p0));
+        const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p0 + 4 * ld));
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     };
 
     f32x16 acc[MI][NI];
@@ -198,23 +210,38 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_kernel(const KArgs p
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    auto compute = [&](int stage) {
-        const u16* As = smem16 + stage * T::STAGE;
-        const u16* Bs = As + T::A_SIZE;
+    auto load_frags = [&](const u16* As, const u16* Bs, int kk, bf16x8 (&af)[MI], bf16x8 (&bf)[NI]) {
 #pragma unroll
-        for (int kk = 0; kk < BK; kk += 16) {
-            bf16x8 af[MI], bf[NI];
+        for (int i = 0; i < MI; ++i) {
+            if constexpr (A_KMAJ)
+                af[i] = *(const bf16x8*)(As + (wm0 + i * 32 + li) * LDA + kk + 8 * lh);
+            else
+                af[i] = read_tr(As, LDA, kk, wm0 + i * 32);
+        }
 #pragma unroll
-            for (int i = 0; i < MI; ++i)
-                af[i] = *(const bf16x8*)(As + (wm0 + i * 32 + li) * LD + kk + 8 * lh);
+        for (int j = 0; j < NI; ++j) bf[j] = read_tr(Bs, LDB, kk, wn0 + j * 32);
+    };
+
+    // Fragments of k step g+1 are fetched from LDS while the MFMAs of step g run; the next
+    // tile (already in registers) is written to the other LDS stage half way through.  The
+    // scheduling barriers keep the compiler from sinking the reads back to their first use.
+    auto compute = [&](int stage, bool store_next) {
+        const u16* As = smem16 + stage * STAGE;
+        const u16* Bs = As + A_SIZE;
+        constexpr int G = BK / 16;
+        bf16x8 af[2][MI], bf[2][NI];
+        load_frags(As, Bs, 0, af[0], bf[0]);
 #pragma unroll
-            for (int j = 0; j < NI; ++j)
-                bf[j] = *(const bf16x8*)(Bs + (wn0 + j * 32 + li) * LD + kk + 8 * lh);
+        for (int g = 0; g < G; ++g) {
+            if (g + 1 < G) load_frags(As, Bs, (g + 1) * 16, af[(g + 1) & 1], bf[(g + 1) & 1]);
+            if (g == G / 2 && store_next) store_tiles(stage ^ 1);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int i = 0; i < MI; ++i)
 #pragma unroll
                 for (int j = 0; j < NI; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[g & 1][i], bf[g & 1][j], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
@@ -225,8 +252,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_kernel(const KArgs p
         const int cur = kt & 1;
         const bool more = kt + 1 < nk;
         if (more) load_tiles(kt + 1, EDGE ? (interior && kt + 1 < p.k_full) : true);
-        compute(cur);
-        if (more) store_tiles(cur ^ 1);
+        compute(cur, more);
         __syncthreads();
     }
 
@@ -253,6 +279,8 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_kernel(const KArgs p
 template <class T, int AMODE>
 hipError_t launch_mode(int variant, const KArgs& a, int batch, hipStream_t s) {
     const dim3 grid(a.tiles_m * a.tiles_n, batch, 1), block(T::NT, 1, 1);
+    constexpr int A_SIZE = (AMODE != A_COL) ? T::BM * T::LDK : T::BK * T::LDA_T;
+    constexpr int BYTES = 2 * (A_SIZE + T::BK * T::LDB) * 2;
     void (*fn)(const KArgs) = nullptr;
     switch (variant) {
         case 0: fn = gemm_bf16_kernel<T, AMODE, 8, false>; break;
@@ -260,12 +288,12 @@ hipError_t launch_mode(int variant, const KArgs& a, int batch, hipStream_t s) {
         default: fn = gemm_bf16_kernel<T, AMODE, 1, true>; break;
     }
     static bool attr_done[3] = {false, false, false};
-    if (T::BYTES > 48 * 1024 && !attr_done[variant]) {
-        hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, T::BYTES);
+    if (BYTES > 48 * 1024 && !attr_done[variant]) {
+        hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, BYTES);
         if (e != hipSuccess) return e;
         attr_done[variant] = true;
     }
-    hipLaunchKernelGGL(fn, grid, block, T::BYTES, s, a);
+    hipLaunchKernelGGL(fn, grid, block, BYTES, s, a);
     return hipGetLastError();
 }
 
@@ -280,12 +308,16 @@ hipError_t launch_tile(int amode, int variant, const KArgs& a, int batch, hipStr
 
 template <class T>
 constexpr KernelEntry entry() {
-    return KernelEntry{T::BM, T::BN, T::BK, T::WM, T::WN, T::NT, 8, &launch_tile<T>};
+    return KernelEntry{T::BM, T::BN, T::BK, T::WM, T::WN, T::NT, 8, 4 * (T::BM * T::LDK + T::BK * T::LDB),
+                       &launch_tile<T>};
 }
 
 const KernelEntry kTable[] = {
-    entry<Tile<256, 256, 64, 128, 128, 1>>(),
+    entry<Tile<256, 256, 64, 128, 64, 2>>(),    // 8 waves, two per SIMD
+    entry<Tile<256, 256, 64, 128, 128, 1>>(),   // 4 waves, one per SIMD, 256 accumulator registers
+    entry<Tile<256, 128, 64, 64, 64, 2>>(),
     entry<Tile<128, 128, 64, 64, 64, 2>>(),
+    entry<Tile<128, 128, 32, 64, 64, 2>>(),
     entry<Tile<64, 64, 64, 32, 32, 2>>(),
 };
 

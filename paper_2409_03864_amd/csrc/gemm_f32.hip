@@ -222,34 +222,47 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_kernel(const KArgs p)
     // 0-31 feed k = t and lanes 32-63 feed k = t+4 of MFMA number t.  Any order is legal as
     // long as both operands use it, and this one lets a k-contiguous A row be fetched with
     // a single 16-byte LDS read.
-    auto compute = [&](int stage) {
-        const float* As = smem + stage * L::STAGE;
-        const float* Bs = As + L::A_SIZE;
+    auto load_frags = [&](const float* As, const float* Bs, int kk, f32x4 (&af)[MI], f32x4 (&bf)[NI]) {
 #pragma unroll
-        for (int kk = 0; kk < BK; kk += 8) {
-            f32x4 af[MI], bf[NI];
-#pragma unroll
-            for (int i = 0; i < MI; ++i) {
-                if constexpr (AMODE == A_COL) {
-#pragma unroll
-                    for (int t = 0; t < 4; ++t)
-                        af[i][t] = As[(kk + 4 * lh + t) * L::A_LD + wm0 + i * 32 + li];
-                } else {
-                    af[i] = *(const f32x4*)(As + (wm0 + i * 32 + li) * L::A_LD + kk + 4 * lh);
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < NI; ++j)
+        for (int i = 0; i < MI; ++i) {
+            if constexpr (AMODE == A_COL) {
 #pragma unroll
                 for (int t = 0; t < 4; ++t)
-                    bf[j][t] = Bs[(kk + 4 * lh + t) * L::B_LD + wn0 + j * 32 + li];
+                    af[i][t] = As[(kk + 4 * lh + t) * L::A_LD + wm0 + i * 32 + li];
+            } else {
+                af[i] = *(const f32x4*)(As + (wm0 + i * 32 + li) * L::A_LD + kk + 4 * lh);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                bf[j][t] = Bs[(kk + 4 * lh + t) * L::B_LD + wn0 + j * 32 + li];
+    };
+
+    // Fragments of k group g+1 are fetched from LDS while the MFMAs of group g run; the
+    // next tile (already in registers) is written to the other LDS stage half way through,
+    // so that neither LDS latency is exposed at the barrier.  The scheduling barriers keep
+    // the compiler from sinking the reads back to their first use.
+    auto compute = [&](int stage, bool store_next) {
+        const float* As = smem + stage * L::STAGE;
+        const float* Bs = As + L::A_SIZE;
+        constexpr int G = BK / 8;
+        f32x4 af[2][MI], bf[2][NI];
+        load_frags(As, Bs, 0, af[0], bf[0]);
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            if (g + 1 < G) load_frags(As, Bs, (g + 1) * 8, af[(g + 1) & 1], bf[(g + 1) & 1]);
+            if (g == G / 2 && store_next) store_tiles(stage ^ 1);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int t = 0; t < 4; ++t)
 #pragma unroll
                 for (int i = 0; i < MI; ++i)
 #pragma unroll
                     for (int j = 0; j < NI; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i][t], bf[j][t], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[g & 1][i][t], bf[g & 1][j][t], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
@@ -261,8 +274,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_kernel(const KArgs p)
         const int cur = kt & 1;
         const bool more = kt + 1 < nk;
         if (more) load_tiles(kt + 1, EDGE ? (interior && kt + 1 < p.k_full) : true);
-        compute(cur);
-        if (more) store_tiles(cur ^ 1);
+        compute(cur, more);
         __syncthreads();
     }
 
@@ -318,16 +330,24 @@ hipError_t launch_tile(int amode, int variant, const KArgs& a, int batch, hipStr
 
 template <class T>
 constexpr KernelEntry entry() {
-    return KernelEntry{T::BM, T::BN, T::BK, T::WM, T::WN, T::NT, 4, &launch_tile<T>};
+    return KernelEntry{T::BM, T::BN, T::BK, T::WM, T::WN, T::NT, 4, Lds<T, A_ROW>::BYTES, &launch_tile<T>};
 }
 
 const KernelEntry kTable[] = {
-    entry<Tile<128, 128, 32, 64, 64, 2>>(),   // default for large shapes
+    entry<Tile<128, 128, 32, 64, 64, 2>>(),
     entry<Tile<128, 128, 16, 64, 64, 2>>(),
     entry<Tile<256, 128, 16, 64, 64, 2>>(),
+    entry<Tile<256, 128, 32, 64, 64, 2>>(),
+    entry<Tile<256, 128, 16, 128, 64, 2>>(),
+    entry<Tile<256, 256, 16, 128, 64, 2>>(),
     entry<Tile<128, 64, 32, 64, 32, 2>>(),
-    entry<Tile<64, 64, 32, 32, 32, 2>>(),     // default for small shapes
+    entry<Tile<128, 64, 64, 64, 32, 2>>(),
+    entry<Tile<64, 64, 32, 32, 32, 2>>(),
     entry<Tile<64, 64, 16, 32, 32, 2>>(),
+    // long k steps for small problems: few workgroups per CU, so each one must keep many
+    // bytes in flight to cover the global-memory latency
+    entry<Tile<64, 64, 64, 32, 32, 2>>(),
+    entry<Tile<64, 64, 128, 32, 32, 1>>(),
 };
 
 }  // namespace

@@ -33,7 +33,8 @@ struct KArgs {
 struct KernelEntry {
     int bm, bn, bk, wm, wn;
     int threads;
-    int vec;   // elements per 16-byte access for this dtype
+    int vec;         // elements per 16-byte access for this dtype
+    int lds_bytes;   // LDS per workgroup (both stages, k-contiguous A layout)
     // variant: 0 = vec, no remainder path; 1 = vec with remainder path; 2 = scalar
     // accesses with remainder path
     hipError_t (*launch)(int amode, int variant, const KArgs& a, int batch, hipStream_t s);
