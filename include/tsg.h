@@ -77,13 +77,17 @@ enum {
  *                its base pointer is 16-byte aligned (Fig. 10: vect = 0 unless the
  *                innermost extent is divisible by the vector size).
  *   raster     : 0 = tiles in row-major order, 1 = XCD-aware grouped order.
+ *   sched      : form of the inner loop: 0 = fragments read where they are used, order
+ *                left to the compiler; 1 = explicit software pipeline (fragments one k
+ *                group ahead, next tile parked in LDS mid-step).  -1 = library default.
+ *                Only (tile, sched) pairs that are instantiated are legal.
  */
 typedef struct {
     int32_t bm, bn, bk;
     int32_t wm, wn;
     int32_t vec;
     int32_t raster;
-    int32_t reserved;
+    int32_t sched;
 } tsg_tile_config;
 
 /* What the most recent compute call on the calling thread enqueued. */
@@ -99,7 +103,7 @@ typedef struct {
 /* One evaluation of the tuner (Case Study 5, Fig. 11: runtime per evaluated point). */
 typedef struct {
     tsg_tile_config config;
-    float ms;        /* median time of one call; < 0 if the config was illegal here */
+    float ms;        /* mean time of one call (best of three batches); < 0 if illegal here */
     float best_ms;   /* best so far, including this evaluation */
 } tsg_tune_record;
 
@@ -179,8 +183,8 @@ tsg_status tsg_gemm_index_map(int32_t trans_a, int64_t M, int64_t K, int64_t lda
 
 /* ---- search (Case Study 5) ----------------------------------------------------- */
 
-/* Time every legal instantiated config on the caller's buffers (`iters` calls each,
- * after one warm-up), keep the fastest and pin it with tsg_tile_config_set.  This
+/* Time every legal instantiated config on the caller's buffers (three batches of `iters`
+ * back-to-back calls each, after one warm-up), keep the fastest and pin it with tsg_tile_config_set.  This
  * call SYNCHRONISES the stream and overwrites C / y.  `log` (host, may be NULL)
  * receives up to log_cap records in evaluation order; *n_log the number written. */
 tsg_status tsg_autotune_gemm(tsg_dtype dtype, int32_t trans_a, int64_t M, int64_t N, int64_t K,

@@ -21,10 +21,10 @@ NEGATE, ACCUMULATE, STRICT = 1, 2, 4
 
 
 class TileConfig(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int32) for n in ("bm", "bn", "bk", "wm", "wn", "vec", "raster", "reserved")]
+    _fields_ = [(n, ctypes.c_int32) for n in ("bm", "bn", "bk", "wm", "wn", "vec", "raster", "sched")]
 
     def as_dict(self):
-        return {n: int(getattr(self, n)) for n, _ in self._fields_ if n != "reserved"}
+        return {n: int(getattr(self, n)) for n, _ in self._fields_}
 
     def __repr__(self):
         return "TileConfig(%s)" % ", ".join("%s=%d" % kv for kv in self.as_dict().items())

@@ -16,10 +16,12 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtsg.so")
-SOURCES = ["api.cpp", "gemm_f32.hip", "gemm_bf16.hip"]
-HEADERS = [os.path.join(CSRC, "tsg_internal.h"), os.path.join(HERE, "..", "include", "tsg.h")]
+SOURCES = ["api.cpp", "gemm_f32_row.hip", "gemm_f32_col.hip", "gemm_f32_conv.hip",
+           "gemm_bf16_row.hip", "gemm_bf16_col.hip", "gemm_bf16_conv.hip"]
+HEADERS = [os.path.join(CSRC, h) for h in ("tsg_internal.h", "gemm_f32_kernel.h", "gemm_bf16_kernel.h")] + \
+          [os.path.join(HERE, "..", "include", "tsg.h")]
 
-# packed-fp32 instruction selection is switched off: see the build notes in the design doc
+# packed-fp32 instruction selection is switched off for all device code
 HIPCC_FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-fno-gpu-rdc",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
                "-Wno-unused-command-line-argument"]

@@ -1,10 +1,9 @@
 // C-ABI layer: argument validation, the loop split, the tile-config registry with its
 // legality rules, the chain of alternatives, launch planning and the tuner.
-// Host code only; the kernels live in gemm_f32.hip and gemm_bf16.hip.
+// Host code only; the kernels live in gemm_f32_*.hip and gemm_bf16_*.hip.
 #include <algorithm>
 #include <cstring>
 #include <mutex>
-#include <vector>
 
 #include "../../include/tsg.h"
 #include "tsg_internal.h"
@@ -51,7 +50,8 @@ const KernelEntry* find_entry(tsg_dtype dt, const tsg_tile_config& c) {
     int n = 0;
     const KernelEntry* t = kernels(dt, &n);
     for (int i = 0; i < n; ++i)
-        if (t[i].bm == c.bm && t[i].bn == c.bn && t[i].bk == c.bk && t[i].wm == c.wm && t[i].wn == c.wn)
+        if (t[i].bm == c.bm && t[i].bn == c.bn && t[i].bk == c.bk && t[i].wm == c.wm && t[i].wn == c.wn &&
+            t[i].sched == c.sched)
             return &t[i];
     return nullptr;
 }
@@ -59,7 +59,7 @@ const KernelEntry* find_entry(tsg_dtype dt, const tsg_tile_config& c) {
 tsg_tile_config config_of(const KernelEntry& e, int vec, int raster) {
     tsg_tile_config c;
     c.bm = e.bm; c.bn = e.bn; c.bk = e.bk; c.wm = e.wm; c.wn = e.wn;
-    c.vec = vec; c.raster = raster; c.reserved = 0;
+    c.vec = vec; c.raster = raster; c.sched = e.sched;
     return c;
 }
 
@@ -105,12 +105,12 @@ tsg_tile_config fill_defaults(tsg_tile_config c, const tsg_tile_config& def) {
     if (c.bm <= 0) c.bm = def.bm;
     if (c.bn <= 0) c.bn = def.bn;
     if (c.bk <= 0) c.bk = def.bk;
-    if (!tile_given) { c.wm = def.wm; c.wn = def.wn; }
+    if (!tile_given) { c.wm = def.wm; c.wn = def.wn; c.sched = def.sched; }
     if (c.wm <= 0) c.wm = std::min(c.bm, 64);
     if (c.wn <= 0) c.wn = std::min(c.bn, 64);
     if (c.vec <= 0) c.vec = def.vec;
     if (c.raster < 0) c.raster = def.raster;
-    c.reserved = 0;
+    if (c.sched < 0) c.sched = def.sched;
     return c;
 }
 
@@ -182,7 +182,9 @@ tsg_status make_plan(const Problem& p, const tsg_tile_config& cfg, int alternati
 
 tsg_status enqueue(const Problem& p, const Plan& pl, hipStream_t s) {
     const int amode = p.op == TSG_OP_GEMM ? tsg::A_ROW : p.op == TSG_OP_GEMM_TRANSA ? tsg::A_COL : tsg::A_CONV;
-    const hipError_t e = pl.entry->launch(amode, pl.variant, pl.args, (int)p.batch, s);
+    int n = 0;
+    const int tile = (int)(pl.entry - kernels(p.dtype, &n));
+    const hipError_t e = pl.entry->launch(tile, amode, pl.variant, pl.args, (int)p.batch, s);
     if (e != hipSuccess) return TSG_E_RUNTIME;
     t_last = pl.info;
     return TSG_OK;
@@ -281,7 +283,6 @@ tsg_status autotune(Problem p, hipStream_t s, int iters, tsg_tile_config* best, 
     tsg_tile_config bcfg{};
     int written = 0;
     tsg_status st = TSG_OK;
-    std::vector<float> ms(iters);
     const int n = space_size(p.dtype);
     for (int i = 0; i < n && st == TSG_OK; ++i) {
         const tsg_tile_config c = space_point(p.dtype, i);
@@ -289,16 +290,18 @@ tsg_status autotune(Problem p, hipStream_t s, int iters, tsg_tile_config* best, 
         float med = -1.f;
         if (make_plan(p, c, 0, &pl) == TSG_OK) {
             st = enqueue(p, pl, s);   // warm-up
-            for (int it = 0; it < iters && st == TSG_OK; ++it) {
+            // best of three batches of `iters` back-to-back calls, mean time per call
+            for (int round = 0; round < 3 && st == TSG_OK; ++round) {
                 if (hipEventRecord(e0, s) != hipSuccess) { st = TSG_E_RUNTIME; break; }
-                st = enqueue(p, pl, s);
+                for (int it = 0; it < iters && st == TSG_OK; ++it) st = enqueue(p, pl, s);
                 if (st != TSG_OK) break;
+                float t = 0.f;
                 if (hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
-                    hipEventElapsedTime(&ms[it], e0, e1) != hipSuccess) { st = TSG_E_RUNTIME; break; }
+                    hipEventElapsedTime(&t, e0, e1) != hipSuccess) { st = TSG_E_RUNTIME; break; }
+                t /= (float)iters;
+                if (med < 0 || t < med) med = t;
             }
             if (st != TSG_OK) break;
-            std::sort(ms.begin(), ms.end());
-            med = ms[iters / 2];
             if (bms < 0 || med < bms) { bms = med; bcfg = c; }
         }
         if (written < log_cap) {

@@ -9,6 +9,7 @@
 // 8-byte rows addressed by lanes l/4, l/4 + 4, l/4 + 8, l/4 + 12.  Pointing lane s of a
 // group at row k0 + s/4, columns j0 + 4*(s%4) .. +3 therefore hands lane l the four
 // values B[k0 .. k0+3][j0 + l]: no transposition in registers or on the store side.
+#pragma once
 #include "tsg_internal.h"
 
 namespace tsg {
@@ -24,9 +25,11 @@ typedef __attribute__((address_space(3))) bf16x4* lds_bf16x4_ptr;
 constexpr unsigned FLAG_NEGATE = 1u, FLAG_ACCUMULATE = 2u;
 constexpr int kXcds = 8, kGroupM = 8;
 
-template <int BM_, int BN_, int BK_, int WM_, int WN_, int MINW_>
+// SCHED: 0 = instruction order inside a k step left to the compiler, 1 = fragments of
+// k step g+1 read while the MFMAs of step g run, next tile written to LDS mid-step.
+template <int BM_, int BN_, int BK_, int WM_, int WN_, int MINW_, int SCHED_>
 struct Tile {
-    static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, MINW = MINW_;
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, MINW = MINW_, SCHED = SCHED_;
     static constexpr int WAVES_M = BM / WM, WAVES_N = BN / WN;
     static constexpr int NT = 64 * WAVES_M * WAVES_N;
     static constexpr int MI = WM / 32, NI = WN / 32;
@@ -225,7 +228,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_kernel(const KArgs p
     // Fragments of k step g+1 are fetched from LDS while the MFMAs of step g run; the next
     // tile (already in registers) is written to the other LDS stage half way through.  The
     // scheduling barriers keep the compiler from sinking the reads back to their first use.
-    auto compute = [&](int stage, bool store_next) {
+    auto compute = [&](int stage, int kt) {
         const u16* As = smem16 + stage * STAGE;
         const u16* Bs = As + A_SIZE;
         constexpr int G = BK / 16;
@@ -234,7 +237,12 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_kernel(const KArgs p
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             if (g + 1 < G) load_frags(As, Bs, (g + 1) * 16, af[(g + 1) & 1], bf[(g + 1) & 1]);
-            if (g == G / 2 && store_next) store_tiles(stage ^ 1);
+            if (g == G / 2) {
+                // tile kt+1 has had a whole step to arrive: park it in the other stage, then
+                // reuse the same registers for the loads of tile kt+2
+                if (kt + 1 < nk) store_tiles(stage ^ 1);
+                if (kt + 2 < nk) load_tiles(kt + 2, EDGE ? (interior && kt + 2 < p.k_full) : true);
+            }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int i = 0; i < MI; ++i)
@@ -245,14 +253,35 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_kernel(const KArgs p
         }
     };
 
+    // SCHED 0: the plain form of the same step
+    auto compute_plain = [&](int stage) {
+        const u16* As = smem16 + stage * STAGE;
+        const u16* Bs = As + A_SIZE;
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 16) {
+            bf16x8 af[MI], bf[NI];
+            load_frags(As, Bs, kk, af, bf);
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NI; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+        }
+    };
+
+    // tile t+1 sits in registers and tile t+2 is in flight while step t is multiplied
     load_tiles(0, EDGE ? (interior && 0 < p.k_full) : true);
     store_tiles(0);
+    if (nk > 1) load_tiles(1, EDGE ? (interior && 1 < p.k_full) : true);
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
-        const bool more = kt + 1 < nk;
-        if (more) load_tiles(kt + 1, EDGE ? (interior && kt + 1 < p.k_full) : true);
-        compute(cur, more);
+        if constexpr (T::SCHED == 1) {
+            compute(kt & 1, kt);
+        } else {
+            compute_plain(kt & 1);
+            if (kt + 1 < nk) store_tiles((kt & 1) ^ 1);
+            if (kt + 2 < nk) load_tiles(kt + 2, EDGE ? (interior && kt + 2 < p.k_full) : true);
+        }
         __syncthreads();
     }
 
@@ -297,35 +326,34 @@ hipError_t launch_mode(int variant, const KArgs& a, int batch, hipStream_t s) {
     return hipGetLastError();
 }
 
-template <class T>
-hipError_t launch_tile(int amode, int variant, const KArgs& a, int batch, hipStream_t s) {
-    switch (amode) {
-        case A_ROW: return launch_mode<T, A_ROW>(variant, a, batch, s);
-        case A_COL: return launch_mode<T, A_COL>(variant, a, batch, s);
-        default: return launch_mode<T, A_CONV>(variant, a, batch, s);
-    }
-}
-
-template <class T>
-constexpr KernelEntry entry() {
-    return KernelEntry{T::BM, T::BN, T::BK, T::WM, T::WN, T::NT, 8, 4 * (T::BM * T::LDK + T::BK * T::LDB),
-                       &launch_tile<T>};
-}
-
-const KernelEntry kTable[] = {
-    entry<Tile<256, 256, 64, 128, 64, 2>>(),    // 8 waves, two per SIMD
-    entry<Tile<256, 256, 64, 128, 128, 1>>(),   // 4 waves, one per SIMD, 256 accumulator registers
-    entry<Tile<256, 128, 64, 64, 64, 2>>(),
-    entry<Tile<128, 128, 64, 64, 64, 2>>(),
-    entry<Tile<128, 128, 32, 64, 64, 2>>(),
-    entry<Tile<64, 64, 64, 32, 32, 2>>(),
-};
-
 }  // namespace
-
-const KernelEntry* bf16_kernels(int* count) {
-    *count = (int)(sizeof(kTable) / sizeof(kTable[0]));
-    return kTable;
-}
-
 }  // namespace tsg
+
+// The instantiated tile shapes: X(BM, BN, BK, WM, WN, min waves per SIMD, SCHED).
+#define TSG_BF16_TILES(X)           \
+    X(256, 256, 64, 128, 64, 2, 1)  \
+    X(256, 256, 64, 128, 64, 2, 0)  \
+    X(256, 256, 64, 64, 128, 2, 1)  \
+    X(256, 256, 64, 128, 128, 1, 1) \
+    X(256, 256, 32, 128, 64, 2, 1)  \
+    X(256, 128, 64, 64, 64, 2, 1)   \
+    X(128, 128, 64, 64, 64, 2, 1)   \
+    X(128, 128, 32, 64, 64, 2, 1)   \
+    X(128, 128, 32, 64, 64, 2, 0)   \
+    X(64, 64, 64, 32, 32, 2, 1)     \
+    X(64, 64, 64, 32, 32, 2, 0)
+
+#define TSG_BF16_DEFINE_MODE(FN, AMODE)                                                             \
+    namespace tsg {                                                                                 \
+    hipError_t FN(int tile, int variant, const KArgs& a, int batch, hipStream_t s) {                \
+        int idx = 0;                                                                                \
+        TSG_BF16_TILES(TSG_BF16_CASE_##AMODE)                                                       \
+        return hipErrorInvalidValue;                                                                \
+    }                                                                                               \
+    }
+#define TSG_BF16_CASE_A_ROW(bm, bn, bk, wm, wn, mw, sc) \
+    if (tile == idx++) return launch_mode<Tile<bm, bn, bk, wm, wn, mw, sc>, A_ROW>(variant, a, batch, s);
+#define TSG_BF16_CASE_A_COL(bm, bn, bk, wm, wn, mw, sc) \
+    if (tile == idx++) return launch_mode<Tile<bm, bn, bk, wm, wn, mw, sc>, A_COL>(variant, a, batch, s);
+#define TSG_BF16_CASE_A_CONV(bm, bn, bk, wm, wn, mw, sc) \
+    if (tile == idx++) return launch_mode<Tile<bm, bn, bk, wm, wn, mw, sc>, A_CONV>(variant, a, batch, s);

@@ -15,6 +15,7 @@
 // The main/remainder split of Fig. 8 is taken per tile: tiles inside
 // [0,m_main) x [0,n_main) and k steps below k_full run the unmasked loaders, the
 // remainder runs masked ones (zero fill), chosen by a wavefront-uniform branch.
+#pragma once
 #include "tsg_internal.h"
 
 namespace tsg {
@@ -27,9 +28,14 @@ constexpr unsigned FLAG_NEGATE = 1u, FLAG_ACCUMULATE = 2u;
 constexpr int kXcds = 8;      // workgroup ids are dealt round-robin over this many L2 domains
 constexpr int kGroupM = 8;    // tile rows per raster group
 
-template <int BM_, int BN_, int BK_, int WM_, int WN_, int MINW_>
+// SCHED selects the shape of the inner loop, a tunable like the tile sizes:
+//   0  fragments are read from LDS group by group where they are used; the instruction
+//      order inside a k step is left to the compiler
+//   1  fragments of k group g+1 are read while the MFMAs of group g run and the next tile
+//      is written to LDS half way through the step, both pinned by scheduling barriers
+template <int BM_, int BN_, int BK_, int WM_, int WN_, int MINW_, int SCHED_>
 struct Tile {
-    static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, MINW = MINW_;
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, MINW = MINW_, SCHED = SCHED_;
     static constexpr int WAVES_M = BM / WM, WAVES_N = BN / WN;
     static constexpr int NT = 64 * WAVES_M * WAVES_N;
     static constexpr int MI = WM / 32, NI = WN / 32;
@@ -244,7 +250,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_kernel(const KArgs p)
     // next tile (already in registers) is written to the other LDS stage half way through,
     // so that neither LDS latency is exposed at the barrier.  The scheduling barriers keep
     // the compiler from sinking the reads back to their first use.
-    auto compute = [&](int stage, bool store_next) {
+    auto compute = [&](int stage, int kt) {
         const float* As = smem + stage * L::STAGE;
         const float* Bs = As + L::A_SIZE;
         constexpr int G = BK / 8;
@@ -253,7 +259,12 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_kernel(const KArgs p)
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             if (g + 1 < G) load_frags(As, Bs, (g + 1) * 8, af[(g + 1) & 1], bf[(g + 1) & 1]);
-            if (g == G / 2 && store_next) store_tiles(stage ^ 1);
+            if (g == G / 2) {
+                // tile kt+1 has had a whole step to arrive: park it in the other stage, then
+                // reuse the same registers for the loads of tile kt+2
+                if (kt + 1 < nk) store_tiles(stage ^ 1);
+                if (kt + 2 < nk) load_tiles(kt + 2, EDGE ? (interior && kt + 2 < p.k_full) : true);
+            }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int t = 0; t < 4; ++t)
@@ -266,15 +277,37 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_kernel(const KArgs p)
         }
     };
 
-    // ---- main loop: global loads of step t+1 are in flight while step t is multiplied
+    // SCHED 0: the plain form of the same step
+    auto compute_plain = [&](int stage) {
+        const float* As = smem + stage * L::STAGE;
+        const float* Bs = As + L::A_SIZE;
+#pragma unroll
+        for (int kk = 0; kk < BK; kk += 8) {
+            f32x4 af[MI], bf[NI];
+            load_frags(As, Bs, kk, af, bf);
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int j = 0; j < NI; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[i][t], bf[j][t], acc[i][j], 0, 0, 0);
+        }
+    };
+
+    // ---- main loop: tile t+1 sits in registers and tile t+2 is in flight while step t is multiplied
     load_tiles(0, EDGE ? (interior && 0 < p.k_full) : true);
     store_tiles(0);
+    if (nk > 1) load_tiles(1, EDGE ? (interior && 1 < p.k_full) : true);
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
-        const bool more = kt + 1 < nk;
-        if (more) load_tiles(kt + 1, EDGE ? (interior && kt + 1 < p.k_full) : true);
-        compute(cur, more);
+        if constexpr (T::SCHED == 1) {
+            compute(kt & 1, kt);
+        } else {
+            compute_plain(kt & 1);
+            if (kt + 1 < nk) store_tiles((kt & 1) ^ 1);
+            if (kt + 2 < nk) load_tiles(kt + 2, EDGE ? (interior && kt + 2 < p.k_full) : true);
+        }
         __syncthreads();
     }
 
@@ -319,42 +352,43 @@ hipError_t launch_mode(int variant, const KArgs& a, int batch, hipStream_t s) {
     return hipGetLastError();
 }
 
-template <class T>
-hipError_t launch_tile(int amode, int variant, const KArgs& a, int batch, hipStream_t s) {
-    switch (amode) {
-        case A_ROW: return launch_mode<T, A_ROW>(variant, a, batch, s);
-        case A_COL: return launch_mode<T, A_COL>(variant, a, batch, s);
-        default: return launch_mode<T, A_CONV>(variant, a, batch, s);
-    }
-}
-
-template <class T>
-constexpr KernelEntry entry() {
-    return KernelEntry{T::BM, T::BN, T::BK, T::WM, T::WN, T::NT, 4, Lds<T, A_ROW>::BYTES, &launch_tile<T>};
-}
-
-const KernelEntry kTable[] = {
-    entry<Tile<128, 128, 32, 64, 64, 2>>(),
-    entry<Tile<128, 128, 16, 64, 64, 2>>(),
-    entry<Tile<256, 128, 16, 64, 64, 2>>(),
-    entry<Tile<256, 128, 32, 64, 64, 2>>(),
-    entry<Tile<256, 128, 16, 128, 64, 2>>(),
-    entry<Tile<256, 256, 16, 128, 64, 2>>(),
-    entry<Tile<128, 64, 32, 64, 32, 2>>(),
-    entry<Tile<128, 64, 64, 64, 32, 2>>(),
-    entry<Tile<64, 64, 32, 32, 32, 2>>(),
-    entry<Tile<64, 64, 16, 32, 32, 2>>(),
-    // long k steps for small problems: few workgroups per CU, so each one must keep many
-    // bytes in flight to cover the global-memory latency
-    entry<Tile<64, 64, 64, 32, 32, 2>>(),
-    entry<Tile<64, 64, 128, 32, 32, 1>>(),
-};
-
 }  // namespace
-
-const KernelEntry* f32_kernels(int* count) {
-    *count = (int)(sizeof(kTable) / sizeof(kTable[0]));
-    return kTable;
-}
-
 }  // namespace tsg
+
+// The instantiated tile shapes: X(BM, BN, BK, WM, WN, min waves per SIMD, SCHED).
+#define TSG_F32_TILES(X)          \
+    X(128, 128, 32, 64, 64, 2, 0) \
+    X(128, 128, 16, 64, 64, 2, 0) \
+    X(128, 128, 16, 64, 64, 2, 1) \
+    X(256, 128, 16, 64, 64, 2, 0) \
+    X(256, 128, 16, 64, 64, 2, 1) \
+    X(256, 128, 32, 64, 64, 2, 0) \
+    X(256, 128, 32, 64, 64, 2, 1) \
+    X(256, 128, 16, 128, 64, 2, 0) \
+    X(256, 128, 16, 128, 64, 2, 1) \
+    X(256, 256, 16, 128, 64, 2, 0) \
+    X(256, 256, 16, 128, 64, 2, 1) \
+    X(128, 64, 32, 64, 32, 2, 0)  \
+    X(128, 64, 64, 64, 32, 2, 1)  \
+    X(64, 64, 32, 32, 32, 2, 0)   \
+    X(64, 64, 32, 32, 32, 2, 1)   \
+    X(64, 64, 16, 32, 32, 2, 0)   \
+    X(64, 64, 64, 32, 32, 2, 0)   \
+    X(64, 64, 64, 32, 32, 2, 1)   \
+    X(64, 64, 128, 32, 32, 1, 1)
+
+// Each address mode is compiled in its own translation unit.
+#define TSG_F32_DEFINE_MODE(FN, AMODE)                                                              \
+    namespace tsg {                                                                                 \
+    hipError_t FN(int tile, int variant, const KArgs& a, int batch, hipStream_t s) {                \
+        int idx = 0;                                                                                \
+        TSG_F32_TILES(TSG_F32_CASE_##AMODE)                                                         \
+        return hipErrorInvalidValue;                                                                \
+    }                                                                                               \
+    }
+#define TSG_F32_CASE_A_ROW(bm, bn, bk, wm, wn, mw, sc) \
+    if (tile == idx++) return launch_mode<Tile<bm, bn, bk, wm, wn, mw, sc>, A_ROW>(variant, a, batch, s);
+#define TSG_F32_CASE_A_COL(bm, bn, bk, wm, wn, mw, sc) \
+    if (tile == idx++) return launch_mode<Tile<bm, bn, bk, wm, wn, mw, sc>, A_COL>(variant, a, batch, s);
+#define TSG_F32_CASE_A_CONV(bm, bn, bk, wm, wn, mw, sc) \
+    if (tile == idx++) return launch_mode<Tile<bm, bn, bk, wm, wn, mw, sc>, A_CONV>(variant, a, batch, s);

@@ -1,0 +1,28 @@
+// fp32 kernels, op(A)(i,k) = A[i*lda + k], and the table of instantiated tiles.
+#include "gemm_f32_kernel.h"
+
+TSG_F32_DEFINE_MODE(launch_f32_row, A_ROW)
+
+namespace tsg {
+hipError_t launch_f32_col(int tile, int variant, const KArgs& a, int batch, hipStream_t s);
+hipError_t launch_f32_conv(int tile, int variant, const KArgs& a, int batch, hipStream_t s);
+
+namespace {
+hipError_t launch_any(int tile, int amode, int variant, const KArgs& a, int batch, hipStream_t s) {
+    switch (amode) {
+        case A_ROW: return launch_f32_row(tile, variant, a, batch, s);
+        case A_COL: return launch_f32_col(tile, variant, a, batch, s);
+        default: return launch_f32_conv(tile, variant, a, batch, s);
+    }
+}
+#define TSG_F32_ENTRY(bm, bn, bk, wm, wn, mw, sc)                                                     \
+    KernelEntry{bm, bn, bk, wm, wn, sc, Tile<bm, bn, bk, wm, wn, mw, sc>::NT, 4,                       \
+                Lds<Tile<bm, bn, bk, wm, wn, mw, sc>, A_ROW>::BYTES, &launch_any},
+const KernelEntry kTable[] = {TSG_F32_TILES(TSG_F32_ENTRY)};
+}  // namespace
+
+const KernelEntry* f32_kernels(int* count) {
+    *count = (int)(sizeof(kTable) / sizeof(kTable[0]));
+    return kTable;
+}
+}  // namespace tsg

@@ -29,15 +29,16 @@ struct KArgs {
     int H, W, Cin, Ho, Wo, KW, sh, sw, ph, pw;
 };
 
-// One instantiated tile shape and its launchers.
+// One instantiated tile shape.  `launch` takes the entry's index in its table.
 struct KernelEntry {
     int bm, bn, bk, wm, wn;
+    int sched;       // inner-loop form, see the kernel headers
     int threads;
     int vec;         // elements per 16-byte access for this dtype
     int lds_bytes;   // LDS per workgroup (both stages, k-contiguous A layout)
     // variant: 0 = vec, no remainder path; 1 = vec with remainder path; 2 = scalar
     // accesses with remainder path
-    hipError_t (*launch)(int amode, int variant, const KArgs& a, int batch, hipStream_t s);
+    hipError_t (*launch)(int tile, int amode, int variant, const KArgs& a, int batch, hipStream_t s);
 };
 
 const KernelEntry* f32_kernels(int* count);

@@ -49,7 +49,7 @@ def test_search_space_enumeration():
             for i in range(n):
                 c = tsg.tile_config_enum(op, dt, i)
                 assert c.bm % c.wm == 0 and c.bn % c.wn == 0 and c.wm % 32 == 0 and c.wn % 32 == 0
-                assert c.vec in (1, vmax) and c.raster in (0, 1)
+                assert c.vec in (1, vmax) and c.raster in (0, 1) and c.sched in (0, 1)
                 key = tuple(c.as_dict().values())
                 assert key not in seen
                 seen.add(key)
@@ -93,7 +93,7 @@ def test_tile_zero_means_default_and_oversized_tile_is_legal():
     assert tsg.tile_config_check(tsg.OP_GEMM, tsg.F32, 5, 8, 12, big) == tsg.OK
     assert oracle.normalise_tile(5, big.bm) == 5          # the oracle's reading of the same rule
     # not instantiated -> silenceable, like a microkernel library lacking a size
-    odd = tsg.TileConfig(bm=96, bn=96, bk=32, wm=32, wn=32, vec=4, raster=0)
+    odd = tsg.TileConfig(bm=96, bn=96, bk=32, wm=32, wn=32, vec=4, raster=0, sched=0)
     assert tsg.tile_config_check(tsg.OP_GEMM, tsg.F32, 512, 512, 512, odd) == tsg.E_SILENCEABLE
     neg = tsg.TileConfig(bm=-1)
     assert tsg.tile_config_check(tsg.OP_GEMM, tsg.F32, 512, 512, 512, neg) == tsg.E_INVALID
