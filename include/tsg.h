@@ -79,7 +79,8 @@ enum {
  *   raster     : 0 = tiles in row-major order, 1 = XCD-aware grouped order.
  *   sched      : form of the inner loop: 0 = fragments read where they are used, order
  *                left to the compiler; 1 = explicit software pipeline (fragments one k
- *                group ahead, next tile parked in LDS mid-step).  -1 = library default.
+ *                group ahead, next tile parked in LDS mid-step); 2 = the same pipeline
+ *                one MFMA ahead.  -1 = library default.
  *                Only (tile, sched) pairs that are instantiated are legal.
  */
 typedef struct {

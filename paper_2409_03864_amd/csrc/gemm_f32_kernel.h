@@ -33,6 +33,9 @@ constexpr int kGroupM = 8;    // tile rows per raster group
 //      order inside a k step is left to the compiler
 //   1  fragments of k group g+1 are read while the MFMAs of group g run and the next tile
 //      is written to LDS half way through the step, both pinned by scheduling barriers
+//   2  as 1 but one MFMA k pair ahead instead of one group of four: every wave always has
+//      the operands of its next MFMAs in registers, so waves that the issue arbiter has
+//      put in lock step never wait for LDS together
 template <int BM_, int BN_, int BK_, int WM_, int WN_, int MINW_, int SCHED_>
 struct Tile {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, MINW = MINW_, SCHED = SCHED_;
@@ -277,6 +280,50 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_kernel(const KArgs p)
         }
     };
 
+    // SCHED 2: operands are fetched one k pair (= one MFMA per block) ahead.
+    auto compute_fine = [&](int stage, int kt) {
+        const float* As = smem + stage * L::STAGE;
+        const float* Bs = As + L::A_SIZE;
+        constexpr int G = BK / 8, S = 4 * G;
+        f32x4 ag[2][MI];   // k-contiguous A: one 16-byte read per group of four k pairs
+        float av[2][MI];   // i-contiguous A: one value per k pair
+        float bv[2][NI];
+        auto fetch = [&](int s1) {
+            const int g1 = s1 >> 2, t1 = s1 & 3;
+            const int krow = g1 * 8 + 4 * lh + t1;
+            if constexpr (AMODE == A_COL) {
+#pragma unroll
+                for (int i = 0; i < MI; ++i) av[s1 & 1][i] = As[krow * L::A_LD + wm0 + i * 32 + li];
+            } else {
+                if (t1 == 0) {
+#pragma unroll
+                    for (int i = 0; i < MI; ++i)
+                        ag[g1 & 1][i] = *(const f32x4*)(As + (wm0 + i * 32 + li) * L::A_LD + g1 * 8 + 4 * lh);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < NI; ++j) bv[s1 & 1][j] = Bs[krow * L::B_LD + wn0 + j * 32 + li];
+        };
+        fetch(0);
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            if (s + 1 < S) fetch(s + 1);
+            if (s == S / 2) {
+                if (kt + 1 < nk) store_tiles(stage ^ 1);
+                if (kt + 2 < nk) load_tiles(kt + 2, EDGE ? (interior && kt + 2 < p.k_full) : true);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NI; ++j) {
+                    const float a = (AMODE == A_COL) ? av[s & 1][i] : ag[(s >> 2) & 1][i][s & 3];
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, bv[s & 1][j], acc[i][j], 0, 0, 0);
+                }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
     // SCHED 0: the plain form of the same step
     auto compute_plain = [&](int stage) {
         const float* As = smem + stage * L::STAGE;
@@ -301,7 +348,9 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_kernel(const KArgs p)
     if (nk > 1) load_tiles(1, EDGE ? (interior && 1 < p.k_full) : true);
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
-        if constexpr (T::SCHED == 1) {
+        if constexpr (T::SCHED == 2) {
+            compute_fine(kt & 1, kt);
+        } else if constexpr (T::SCHED == 1) {
             compute(kt & 1, kt);
         } else {
             compute_plain(kt & 1);
@@ -356,26 +405,28 @@ hipError_t launch_mode(int variant, const KArgs& a, int batch, hipStream_t s) {
 }  // namespace tsg
 
 // The instantiated tile shapes: X(BM, BN, BK, WM, WN, min waves per SIMD, SCHED).
-#define TSG_F32_TILES(X)          \
-    X(128, 128, 32, 64, 64, 2, 0) \
-    X(128, 128, 16, 64, 64, 2, 0) \
-    X(128, 128, 16, 64, 64, 2, 1) \
-    X(256, 128, 16, 64, 64, 2, 0) \
-    X(256, 128, 16, 64, 64, 2, 1) \
-    X(256, 128, 32, 64, 64, 2, 0) \
-    X(256, 128, 32, 64, 64, 2, 1) \
+#define TSG_F32_TILES(X)           \
+    X(128, 128, 32, 64, 64, 2, 0)  \
+    X(128, 128, 16, 64, 64, 2, 0)  \
+    X(128, 128, 16, 64, 64, 2, 2)  \
+    X(256, 128, 16, 64, 64, 2, 0)  \
+    X(256, 128, 16, 64, 64, 2, 1)  \
+    X(256, 128, 16, 64, 64, 2, 2)  \
+    X(256, 128, 32, 64, 64, 2, 0)  \
+    X(256, 128, 32, 64, 64, 2, 2)  \
     X(256, 128, 16, 128, 64, 2, 0) \
-    X(256, 128, 16, 128, 64, 2, 1) \
+    X(256, 128, 16, 128, 64, 2, 2) \
     X(256, 256, 16, 128, 64, 2, 0) \
-    X(256, 256, 16, 128, 64, 2, 1) \
-    X(128, 64, 32, 64, 32, 2, 0)  \
-    X(128, 64, 64, 64, 32, 2, 1)  \
-    X(64, 64, 32, 32, 32, 2, 0)   \
-    X(64, 64, 32, 32, 32, 2, 1)   \
-    X(64, 64, 16, 32, 32, 2, 0)   \
-    X(64, 64, 64, 32, 32, 2, 0)   \
-    X(64, 64, 64, 32, 32, 2, 1)   \
-    X(64, 64, 128, 32, 32, 1, 1)
+    X(256, 256, 16, 128, 64, 2, 2) \
+    X(128, 64, 32, 64, 32, 2, 0)   \
+    X(128, 64, 32, 64, 32, 2, 2)   \
+    X(128, 64, 64, 64, 32, 2, 2)   \
+    X(64, 64, 32, 32, 32, 2, 0)    \
+    X(64, 64, 32, 32, 32, 2, 2)    \
+    X(64, 64, 16, 32, 32, 2, 0)    \
+    X(64, 64, 64, 32, 32, 2, 0)    \
+    X(64, 64, 64, 32, 32, 2, 2)    \
+    X(64, 64, 128, 32, 32, 1, 2)
 
 // Each address mode is compiled in its own translation unit.
 #define TSG_F32_DEFINE_MODE(FN, AMODE)                                                              \
