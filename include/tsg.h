@@ -80,7 +80,8 @@ enum {
  *   sched      : form of the inner loop: 0 = fragments read where they are used, order
  *                left to the compiler; 1 = explicit software pipeline (fragments one k
  *                group ahead, next tile parked in LDS mid-step); 2 = the same pipeline
- *                one MFMA ahead.  -1 = library default.
+ *                one MFMA ahead; 3 = as 2 with three LDS stages and the barrier in the
+ *                middle of the step.  -1 = library default.
  *                Only (tile, sched) pairs that are instantiated are legal.
  */
 typedef struct {

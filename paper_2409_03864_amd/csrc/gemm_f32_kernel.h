@@ -36,6 +36,9 @@ constexpr int kGroupM = 8;    // tile rows per raster group
 //   2  as 1 but one MFMA k pair ahead instead of one group of four: every wave always has
 //      the operands of its next MFMAs in registers, so waves that the issue arbiter has
 //      put in lock step never wait for LDS together
+//   3  as 2 with THREE LDS stages: the one barrier of a step sits in its middle, right after
+//      the next tile has been parked, and the first operands of the next step are fetched
+//      before the current step ends, so no wave drains its MFMA queue around the barrier
 template <int BM_, int BN_, int BK_, int WM_, int WN_, int MINW_, int SCHED_>
 struct Tile {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, MINW = MINW_, SCHED = SCHED_;
@@ -55,7 +58,8 @@ struct Lds {
     static constexpr int B_LD = T::BN + 8;
     static constexpr int A_SIZE = A_ROWS * A_LD, B_SIZE = T::BK * B_LD;
     static constexpr int STAGE = A_SIZE + B_SIZE;
-    static constexpr int BYTES = 2 * STAGE * (int)sizeof(float);
+    static constexpr int STAGES = T::SCHED == 3 ? 3 : 2;
+    static constexpr int BYTES = STAGES * STAGE * (int)sizeof(float);
 };
 
 __device__ __forceinline__ void tile_coords(const KArgs& p, int bid, int& tm, int& tn) {
@@ -324,6 +328,62 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_kernel(const KArgs p)
         }
     };
 
+    // SCHED 3.  Step kt multiplies stage kt % 3.  Tile kt+1 is written to stage (kt+1) % 3 a
+    // quarter of the way in; that stage was last read in step kt-2, which every wave left
+    // before it passed the barrier of step kt-1.  The barrier of step kt follows the write,
+    // and the operands of step kt+1 are read from the new stage only after it.
+    auto run_three_stage = [&]() {
+        constexpr int G = BK / 8, S = 4 * G;
+        static_assert(G % 2 == 0, "operand double buffers alternate per group across steps");
+        f32x4 ag[2][MI];
+        float av[2][MI];
+        float bv[2][NI];
+        auto fetch = [&](int stage, int s1) {
+            const float* As = smem + stage * L::STAGE;
+            const float* Bs = As + L::A_SIZE;
+            const int g1 = s1 >> 2, t1 = s1 & 3;
+            const int krow = g1 * 8 + 4 * lh + t1;
+            if constexpr (AMODE == A_COL) {
+#pragma unroll
+                for (int i = 0; i < MI; ++i) av[s1 & 1][i] = As[krow * L::A_LD + wm0 + i * 32 + li];
+            } else {
+                if (t1 == 0) {
+#pragma unroll
+                    for (int i = 0; i < MI; ++i)
+                        ag[g1 & 1][i] = *(const f32x4*)(As + (wm0 + i * 32 + li) * L::A_LD + g1 * 8 + 4 * lh);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < NI; ++j) bv[s1 & 1][j] = Bs[krow * L::B_LD + wn0 + j * 32 + li];
+        };
+        fetch(0, 0);
+        int cur = 0;
+        for (int kt = 0; kt < nk; ++kt) {
+            const int nxt = cur == 2 ? 0 : cur + 1;
+#pragma unroll
+            for (int s = 0; s < S; ++s) {
+                // after the last step the fetch reads a stage nobody multiplies: harmless, and
+                // keeping it unconditional keeps the whole step one scheduling region
+                fetch(s + 1 < S ? cur : nxt, s + 1 < S ? s + 1 : 0);
+                if (s == S / 4) {
+                    if (kt + 1 < nk) store_tiles(nxt);
+                    if (kt + 2 < nk) load_tiles(kt + 2, EDGE ? (interior && kt + 2 < p.k_full) : true);
+                }
+                if (s == S / 2) __syncthreads();
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int j = 0; j < NI; ++j) {
+                        const float a = (AMODE == A_COL) ? av[s & 1][i] : ag[(s >> 2) & 1][i][s & 3];
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, bv[s & 1][j], acc[i][j], 0, 0, 0);
+                    }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            cur = nxt;
+        }
+    };
+
     // SCHED 0: the plain form of the same step
     auto compute_plain = [&](int stage) {
         const float* As = smem + stage * L::STAGE;
@@ -347,7 +407,8 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_kernel(const KArgs p)
     store_tiles(0);
     if (nk > 1) load_tiles(1, EDGE ? (interior && 1 < p.k_full) : true);
     __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
+    if constexpr (T::SCHED == 3) run_three_stage();
+    for (int kt = 0; T::SCHED != 3 && kt < nk; ++kt) {
         if constexpr (T::SCHED == 2) {
             compute_fine(kt & 1, kt);
         } else if constexpr (T::SCHED == 1) {
@@ -409,15 +470,19 @@ hipError_t launch_mode(int variant, const KArgs& a, int batch, hipStream_t s) {
     X(128, 128, 32, 64, 64, 2, 0)  \
     X(128, 128, 16, 64, 64, 2, 0)  \
     X(128, 128, 16, 64, 64, 2, 2)  \
+    X(128, 128, 16, 64, 64, 2, 3)  \
+    X(128, 128, 32, 64, 64, 2, 3)  \
     X(256, 128, 16, 64, 64, 2, 0)  \
     X(256, 128, 16, 64, 64, 2, 1)  \
     X(256, 128, 16, 64, 64, 2, 2)  \
+    X(256, 128, 16, 64, 64, 2, 3)  \
     X(256, 128, 32, 64, 64, 2, 0)  \
     X(256, 128, 32, 64, 64, 2, 2)  \
     X(256, 128, 16, 128, 64, 2, 0) \
     X(256, 128, 16, 128, 64, 2, 2) \
     X(256, 256, 16, 128, 64, 2, 0) \
     X(256, 256, 16, 128, 64, 2, 2) \
+    X(256, 256, 16, 128, 64, 2, 3) \
     X(128, 64, 32, 64, 32, 2, 0)   \
     X(128, 64, 32, 64, 32, 2, 2)   \
     X(128, 64, 64, 64, 32, 2, 2)   \
@@ -426,6 +491,8 @@ hipError_t launch_mode(int variant, const KArgs& a, int batch, hipStream_t s) {
     X(64, 64, 16, 32, 32, 2, 0)    \
     X(64, 64, 64, 32, 32, 2, 0)    \
     X(64, 64, 64, 32, 32, 2, 2)    \
+    X(64, 64, 32, 32, 32, 2, 3)    \
+    X(128, 64, 32, 64, 32, 2, 3)   \
     X(64, 64, 128, 32, 32, 1, 2)
 
 // Each address mode is compiled in its own translation unit.

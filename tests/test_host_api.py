@@ -49,7 +49,7 @@ def test_search_space_enumeration():
             for i in range(n):
                 c = tsg.tile_config_enum(op, dt, i)
                 assert c.bm % c.wm == 0 and c.bn % c.wn == 0 and c.wm % 32 == 0 and c.wn % 32 == 0
-                assert c.vec in (1, vmax) and c.raster in (0, 1) and c.sched in (0, 1, 2)
+                assert c.vec in (1, vmax) and c.raster in (0, 1) and c.sched in (0, 1, 2, 3)
                 key = tuple(c.as_dict().values())
                 assert key not in seen
                 seen.add(key)
