@@ -24,6 +24,33 @@ sys.path.insert(0, ROOT)
 PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
 METRIC = "TFLOP/s and % of MI355X matrix peak, fp32 GEMM 4096^3 (1 GPU)"
 
+# HBM bytes per launch of the dominant kernel, from two `rocprofv3 --pmc` passes
+# (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch) scaled by what the same counters read
+# for a plain 256 MiB device copy in the same run; the summaries are under profiles/.
+# An entry is reported only while the kernel sources still hash to the value it was taken
+# with and the launch uses the same tile config; otherwise `traffic` is null.
+TRAFFIC = {
+}
+
+
+def kernel_hash(dtype: str) -> str:
+    import hashlib
+    h = hashlib.sha256()
+    csrc = os.path.join(ROOT, "paper_2409_03864_amd", "csrc")
+    for f in ("tsg_internal.h", "gemm_f32_kernel.h" if dtype == "f32" else "gemm_bf16_kernel.h"):
+        with open(os.path.join(csrc, f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
+def traffic_bytes(k: int, dtype: str, tile: dict):
+    e = TRAFFIC.get(k)
+    if not e or e["kernel_hash"] != kernel_hash(dtype):
+        return None
+    if any(tile.get(key) != val for key, val in e["tile"].items()):
+        return None
+    return e["bytes"]
+
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
@@ -33,7 +60,7 @@ def workload_flops(c) -> int:
     """Algorithmic flop count: 2 per multiply-add; convolution taps that fall in the zero
     padding are not work."""
     if c["op"] != "conv2d_nhwc":
-        return 2 * c["M"] * c["N"] * c["K"]
+        return 2 * c.get("B", 1) * c["M"] * c["N"] * c["K"]
 
     def valid(L, Kk, s, p):
         Lo = (L + 2 * p - Kk) // s + 1
@@ -48,8 +75,8 @@ def describe(k, c) -> str:
         return ("cfg%d: %s conv2d NHWC N=%d H=W=%d Cin=%d Cout=%d %dx%d stride %d pad %d, seed %d"
                 % (k, c["dtype"], c["N"], c["H"], c["Cin"], c["Cout"], c["KH"], c["KW"], c["stride"], c["pad"],
                    c["seed"]))
-    return "cfg%d: %s %s M=%d N=%d K=%d, %s entries, seed %d%s" % (
-        k, c["dtype"], c["op"], c["M"], c["N"], c["K"], c["dist"], c["seed"],
+    return "cfg%d: %s %s %sM=%d N=%d K=%d, %s entries, seed %d%s" % (
+        k, c["dtype"], c["op"], "batch=%d " % c["B"] if "B" in c else "", c["M"], c["N"], c["K"], c["dist"], c["seed"],
         ", negate fused" if "negate" in c["flags"] else "")
 
 
@@ -58,7 +85,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", type=int, default=3, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--workload", type=int, default=3, choices=[1, 2, 3, 4, 5, 6])
     ap.add_argument("--no-tune", action="store_true", help="use the shape heuristic instead of the tuner")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--cpu-rows", type=int, default=4096, help="rows of the product the oracle is timed on")
@@ -108,6 +135,17 @@ def main() -> int:
 
         def tune():
             return tsg.autotune_conv2d_nhwc(dt, *geom, dA, dB, dC, flags, iters=5)
+    elif c["op"] == "gemm_batched":
+        nb, M, N, K = c["B"], c["M"], c["N"], c["K"]
+        op = tsg.OP_GEMM
+        dC = torch.zeros((nb, M, N), dtype=torch.float32, device=dev)
+
+        def step():
+            tsg.gemm_batched(dt, False, nb, M, N, K, dA, K, M * K, dB, N, K * N, dC, N, M * N, flags)
+
+        def tune():
+            # the tuner times one product of the batch; the pinned config then serves all of them
+            return tsg.autotune_gemm(dt, False, M, N, K, dA, K, dB, N, dC, N, flags, iters=5)
     else:
         M, N, K = c["M"], c["N"], c["K"]
         trans = c["op"] == "gemm_transA"
@@ -181,11 +219,13 @@ def main() -> int:
             sflops, sample = flops // c["N"], "image 0 of %d (direct convolution)" % c["N"]
         else:
             rows = min(args.cpu_rows, M)
-            sub = np.ascontiguousarray(a[:, :rows] if c["op"] == "gemm_transA" else a[:rows])
+            a0, b0 = (a[0], b[0]) if c["op"] == "gemm_batched" else (a, b)
+            sub = np.ascontiguousarray(a0[:, :rows] if c["op"] == "gemm_transA" else a0[:rows])
             t0 = time.perf_counter()
-            oracle.gemm(sub, b, trans_a=(c["op"] == "gemm_transA"), with_s=False)
+            oracle.gemm(sub, b0, trans_a=(c["op"] == "gemm_transA"), with_s=False)
             dtc = time.perf_counter() - t0
-            sflops, sample = 2 * rows * N * K, "rows 0..%d of C (%d x %d x %d triple loop)" % (rows - 1, rows, N, K)
+            sflops, sample = 2 * rows * N * K, "rows 0..%d of C%s (%d x %d x %d triple loop)" % (
+                rows - 1, " of batch 0" if c["op"] == "gemm_batched" else "", rows, N, K)
         cpu = {"value": sflops / dtc / 1e12, "unit": "TFLOP/s", "cores": oracle.threads(), "kind": "oracle",
                "sample": sample, "seconds": round(dtc, 3)}
         log("cpu oracle: %s in %.2f s on %d threads = %.4f TFLOP/s" % (sample, dtc, cpu["cores"], cpu["value"]))
@@ -200,8 +240,9 @@ def main() -> int:
                    "tile_config": li.config.as_dict(), "alternative": int(li.alternative),
                    "tuned": not args.no_tune},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                     "frac": achieved / peak, "traffic": None,
-                     "kernel_ms_avg": avg_kern_ms},
+                     "frac": achieved / peak,
+                     "traffic": traffic_bytes(k, c["dtype"], li.config.as_dict()),
+                     "kernel_ms_avg": avg_kern_ms, "kernel_hash": kernel_hash(c["dtype"])},
         "cpu_baseline": cpu,
     }
     if tuner_log is not None:

@@ -72,10 +72,13 @@ enum {
  *                the whole loop becomes remainder.
  *   wm, wn     : per-wavefront sub-tile (multiples of the 32x32 MFMA block).
  *   vec        : elements per global access along the contiguous dimension, the
- *                paper's `vect`: 1, or 4 (fp32) / 8 (bf16) = 16-byte accesses.  Legal
- *                only if every operand's leading dimension is a multiple of vec and
- *                its base pointer is 16-byte aligned (Fig. 10: vect = 0 unless the
- *                innermost extent is divisible by the vector size).
+ *                paper's `vect`: 1, or 4 (fp32) / 8 (bf16) = 16-byte accesses.  Fig. 10
+ *                allows vect only when the innermost extent is divisible by the vector
+ *                size.  Here the k tile always is, a loop's remainder is peeled into
+ *                masked scalar code (Fig. 8), and a matrix row is one contiguous run
+ *                whatever its leading dimension, so for the GEMM calls the wide form is
+ *                always legal; for the convolution the gathered operand is contiguous
+ *                only along Cin, and vec must divide Cin.
  *   raster     : 0 = tiles in row-major order, 1 = XCD-aware grouped order.
  *   sched      : form of the inner loop: 0 = fragments read where they are used, order
  *                left to the compiler; 1 = explicit software pipeline (fragments one k
@@ -83,6 +86,11 @@ enum {
  *                one MFMA ahead; 3 = as 2 with three LDS stages and the barrier in the
  *                middle of the step.  -1 = library default.
  *                Only (tile, sched) pairs that are instantiated are legal.
+ *   split_k    : number of workgroups that share one tile of C, each taking a contiguous
+ *                range of k steps (tiling the k loop at the grid level when i x j tiles
+ *                alone cannot fill the chip).  1 = none; 0 = library default.  Values
+ *                above 1 need a workspace (tsg_workspace_set) and at most 16; the partial
+ *                tiles are added in split order, so the result does not depend on timing.
  */
 typedef struct {
     int32_t bm, bn, bk;
@@ -90,6 +98,7 @@ typedef struct {
     int32_t vec;
     int32_t raster;
     int32_t sched;
+    int32_t split_k;
 } tsg_tile_config;
 
 /* What the most recent compute call on the calling thread enqueued. */
@@ -154,8 +163,9 @@ tsg_status tsg_tile_config_enum(tsg_op op, tsg_dtype dtype, int32_t idx, tsg_til
 /* Legality of a config for a problem with natural leading dimensions and aligned
  * pointers.  For convolution pass the implicit extents and Cin as `contig`
  * (the contiguous run of the gathered operand); for GEMM contig is ignored.
- * TSG_E_SILENCEABLE if the tile is not instantiated or `vec` violates Fig. 10's
- * divisibility rule; TSG_E_INVALID for malformed arguments. */
+ * TSG_E_SILENCEABLE if the tile is not instantiated, `vec` violates Fig. 10's
+ * divisibility rule, or split_k exceeds 16 or the number of k steps; TSG_E_INVALID for
+ * malformed arguments. */
 tsg_status tsg_tile_config_check(tsg_op op, tsg_dtype dtype, int64_t M, int64_t N, int64_t K,
                                  int64_t contig, const tsg_tile_config *cfg);
 
@@ -167,6 +177,20 @@ tsg_status tsg_tile_config_set(tsg_op op, tsg_dtype dtype, const tsg_tile_config
 /* The config a call with these extents would try first right now. */
 tsg_status tsg_tile_config_get(tsg_op op, tsg_dtype dtype, int64_t M, int64_t N, int64_t K,
                                tsg_tile_config *out);
+
+/* Workspace for split_k > 1: `ws` is a DEVICE buffer of `bytes` bytes, 256-byte aligned,
+ * owned by the caller, who keeps it alive and unused by anything else until it is replaced
+ * or cleared with (NULL, 0).  The library keeps arrival counters in its first 64 KiB (this
+ * call zeroes them, synchronously) and partial tiles after that.  Compute calls that use
+ * the workspace must be ordered on one stream: two of them in flight at once race.
+ * Without a workspace (or with one that is too small for a config) split_k > 1 is a
+ * silenceable failure and the chain of alternatives continues with split_k = 1. */
+tsg_status tsg_workspace_set(void *ws, int64_t bytes);
+
+/* Bytes of workspace a call with this batch, M, N and config needs (0 when split_k is 1);
+ * -1 for malformed arguments or a tile that is not instantiated. */
+int64_t tsg_workspace_bytes(tsg_dtype dtype, int64_t batch, int64_t M, int64_t N,
+                            const tsg_tile_config *cfg);
 
 /* Details of the last compute call made by the calling thread. */
 tsg_status tsg_last_launch(tsg_launch_info *out);

@@ -21,7 +21,7 @@ NEGATE, ACCUMULATE, STRICT = 1, 2, 4
 
 
 class TileConfig(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int32) for n in ("bm", "bn", "bk", "wm", "wn", "vec", "raster", "sched")]
+    _fields_ = [(n, ctypes.c_int32) for n in ("bm", "bn", "bk", "wm", "wn", "vec", "raster", "sched", "split_k")]
 
     def as_dict(self):
         return {n: int(getattr(self, n)) for n, _ in self._fields_}
@@ -68,6 +68,7 @@ def _load():
         "tsg_tile_config_set": [i32, i32, cfgp],
         "tsg_tile_config_get": [i32, i32, i64, i64, i64, cfgp],
         "tsg_last_launch": [ctypes.POINTER(LaunchInfo)],
+        "tsg_workspace_set": [vp, i64],
         "tsg_conv2d_index_map": [i64] * 10 + [vp],
         "tsg_gemm_index_map": [i32, i64, i64, i64, vp],
         "tsg_autotune_gemm": [i32, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, u32, vp, i32,
@@ -83,6 +84,8 @@ def _load():
         fn.restype = ctypes.c_int
     lib.tsg_tile_config_count.argtypes = [i32, i32]
     lib.tsg_tile_config_count.restype = i32
+    lib.tsg_workspace_bytes.argtypes = [i32, i64, i64, i64, cfgp]
+    lib.tsg_workspace_bytes.restype = i64
     lib.tsg_status_string.argtypes = [ctypes.c_int]
     lib.tsg_status_string.restype = ctypes.c_char_p
     lib.tsg_version.argtypes = []
@@ -94,7 +97,8 @@ _lib = _load()
 
 EXPORTS = ("tsg_gemm", "tsg_gemm_transA", "tsg_gemm_batched", "tsg_conv2d_nhwc", "tsg_split",
            "tsg_tile_config_count", "tsg_tile_config_enum", "tsg_tile_config_check",
-           "tsg_tile_config_set", "tsg_tile_config_get", "tsg_last_launch", "tsg_conv2d_index_map",
+           "tsg_tile_config_set", "tsg_tile_config_get", "tsg_last_launch", "tsg_workspace_set",
+           "tsg_workspace_bytes", "tsg_conv2d_index_map",
            "tsg_gemm_index_map", "tsg_autotune_gemm", "tsg_autotune_conv2d_nhwc",
            "tsg_status_string", "tsg_version")
 
@@ -192,6 +196,21 @@ def tile_config_get(op, dtype, M, N, K) -> TileConfig:
     return c
 
 
+def workspace_set(ws, nbytes=None):
+    """Hand the library a device buffer for split_k > 1 (a tensor, or a raw address plus
+    nbytes); None clears it.  The caller keeps the buffer alive."""
+    if ws is None:
+        _check(_lib.tsg_workspace_set(None, 0), "tsg_workspace_set")
+        return
+    if nbytes is None:
+        nbytes = ws.numel() * ws.element_size()
+    _check(_lib.tsg_workspace_set(_ptr(ws), nbytes), "tsg_workspace_set")
+
+
+def workspace_bytes(dtype, batch, M, N, cfg) -> int:
+    return int(_lib.tsg_workspace_bytes(dtype, batch, M, N, ctypes.byref(cfg)))
+
+
 def last_launch() -> LaunchInfo:
     li = LaunchInfo()
     _check(_lib.tsg_last_launch(ctypes.byref(li)), "tsg_last_launch")
@@ -216,7 +235,7 @@ def _tune_out(cap):
 
 
 def autotune_gemm(dtype, trans_a, M, N, K, A, lda, B, ldb, C, ldc, flags=0, stream=None, iters=5,
-                  log_cap=256):
+                  log_cap=512):
     best, ms, log, n = _tune_out(log_cap)
     _check(_lib.tsg_autotune_gemm(dtype, int(bool(trans_a)), M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C),
                                   ldc, flags, _stream(stream), iters, ctypes.byref(best), ctypes.byref(ms),
@@ -225,7 +244,7 @@ def autotune_gemm(dtype, trans_a, M, N, K, A, lda, B, ldb, C, ldc, flags=0, stre
 
 
 def autotune_conv2d_nhwc(dtype, N, H, W, Cin, Cout, KH, KW, stride_h, stride_w, pad_h, pad_w, x, w, y,
-                         flags=0, stream=None, iters=5, log_cap=256):
+                         flags=0, stream=None, iters=5, log_cap=512):
     best, ms, log, n = _tune_out(log_cap)
     _check(_lib.tsg_autotune_conv2d_nhwc(dtype, N, H, W, Cin, Cout, KH, KW, stride_h, stride_w, pad_h,
                                          pad_w, _ptr(x), _ptr(w), _ptr(y), flags, _stream(stream), iters,

@@ -34,6 +34,13 @@ struct Problem {
 std::mutex g_mu;
 bool g_pinned[kNumOps][kNumDtypes];
 tsg_tile_config g_pin[kNumOps][kNumDtypes];
+
+// Caller-owned workspace for split k: arrival counters first, partial tiles after them.
+constexpr int64_t kMaxSlots = 16384;                       // (batch x tile) counters
+constexpr int64_t kCounterBytes = kMaxSlots * 4;
+constexpr int kMaxSplit = 16;
+void* g_ws = nullptr;
+int64_t g_ws_bytes = 0;
 thread_local tsg_launch_info t_last;
 
 const KernelEntry* kernels(tsg_dtype dt, int* n) {
@@ -56,11 +63,17 @@ const KernelEntry* find_entry(tsg_dtype dt, const tsg_tile_config& c) {
     return nullptr;
 }
 
-tsg_tile_config config_of(const KernelEntry& e, int vec, int raster) {
+tsg_tile_config config_of(const KernelEntry& e, int vec, int raster, int split_k = 1) {
     tsg_tile_config c;
     c.bm = e.bm; c.bn = e.bn; c.bk = e.bk; c.wm = e.wm; c.wn = e.wn;
-    c.vec = vec; c.raster = raster; c.sched = e.sched;
+    c.vec = vec; c.raster = raster; c.sched = e.sched; c.split_k = split_k;
     return c;
+}
+
+int64_t ws_bytes_needed(const KernelEntry& e, int64_t batch, int64_t M, int64_t N, int split_k) {
+    if (split_k <= 1) return 0;
+    const int64_t tiles = ((M + e.bm - 1) / e.bm) * ((N + e.bn - 1) / e.bn);
+    return kCounterBytes + batch * tiles * split_k * (int64_t)e.bm * e.bn * 4;
 }
 
 // Shape heuristic: a small analytical model of one CU.  A workgroup step costs its MFMA
@@ -68,16 +81,22 @@ tsg_tile_config config_of(const KernelEntry& e, int vec, int raster) {
 // the global-memory latency its single prefetch has to cover; the kernel costs
 // (rounds of workgroups) x (steps x step cost + one latency).  The table entry with the
 // lowest estimate wins; the tuner (tsg_autotune_*) replaces the guess by measurement.
-tsg_tile_config heuristic(tsg_dtype dt, int64_t batch, int64_t M, int64_t N, int64_t K) {
+tsg_tile_config heuristic(tsg_dtype dt, int64_t batch, int64_t M, int64_t N, int64_t K, int64_t ws_bytes) {
     int n = 0;
     const KernelEntry* t = kernels(dt, &n);
     const double kLatency = 1400.0;      // cycles from issuing a tile's loads to LDS-ready
     const double kLds = 160.0 * 1024;
     double best = 0;
-    int best_i = 0;
-    for (int i = 0; i < n; ++i) {
+    int best_i = 0, best_split = 1;
+    bool first = true;
+    for (int i = 0; i < n; ++i)
+    for (int split = 1; split <= kMaxSplit; split *= 2) {
         const KernelEntry& e = t[i];
-        const double tiles = (double)((M + e.bm - 1) / e.bm) * (double)((N + e.bn - 1) / e.bn) * (double)batch;
+        const int64_t nk_all = (K + e.bk - 1) / e.bk;
+        if (split > 1 && (split * 2 > nk_all || ws_bytes_needed(e, batch, M, N, split) > ws_bytes ||
+                          batch * ((M + e.bm - 1) / e.bm) * ((N + e.bn - 1) / e.bn) > kMaxSlots))
+            break;
+        const double tiles = (double)((M + e.bm - 1) / e.bm) * (double)((N + e.bn - 1) / e.bn) * (double)batch * split;
         const double blocks = (e.wm / 32) * (e.wn / 32);
         const double wg_wps = e.threads / 256.0;                        // waves per SIMD of one workgroup
         const double wps_cap = (double)(int)(512.0 / (blocks * 16.0 + 64.0));   // register-file limit
@@ -85,7 +104,7 @@ tsg_tile_config heuristic(tsg_dtype dt, int64_t batch, int64_t M, int64_t N, int
                                                        (double)(int)(wps_cap / wg_wps)));
         const double rounds = (double)(int64_t)((tiles + kCUs * resident - 1) / (kCUs * resident));
         const double conc = std::min(resident, (double)(int64_t)((tiles + kCUs - 1) / kCUs));
-        const double steps = (double)((K + e.bk - 1) / e.bk);
+        const double steps = (double)((nk_all + split - 1) / split);
         // cycles one wave spends in MFMA per step: fp32 32x32x2 = 64 cycles, bf16 32x32x16 = 32
         const double wave_mfma = dt == TSG_F32 ? blocks * e.bk * 32.0 : blocks * e.bk * 2.0;
         const double wg_mfma = wave_mfma * wg_wps;
@@ -93,10 +112,13 @@ tsg_tile_config heuristic(tsg_dtype dt, int64_t batch, int64_t M, int64_t N, int
         // re-read LDS more often per MFMA (factors fitted to measured 4096^3 runs)
         const double ineff = (1.0 + 0.4 / (conc * wg_wps)) * (1.0 + 16.0 / (e.wm + e.wn));
         const double step_cost = std::max(conc * wg_mfma * ineff, kLatency + 0.2 * wg_mfma);
-        const double est = rounds * (steps * step_cost + kLatency + 600.0);
-        if (i == 0 || est < best * 0.999) { best = est; best_i = i; }
+        // split k: every partial tile is written once and read once (about 64 bytes per cycle
+        // and CU), and the arrival protocol costs two device-wide fences
+        const double reduce = split > 1 ? 2.0 * e.bm * e.bn * 4.0 / 64.0 * (1.0 + 1.0 / split) + 3000.0 : 0.0;
+        const double est = rounds * (steps * step_cost + kLatency + 600.0 + reduce);
+        if (first || est < best * 0.999) { best = est; best_i = i; best_split = split; first = false; }
     }
-    return config_of(t[best_i], vec_max(dt), dt == TSG_F32 ? 0 : 1);
+    return config_of(t[best_i], vec_max(dt), dt == TSG_F32 ? 0 : 1, best_split);
 }
 
 // Fill zero fields ("tiling by 0 is a no-op": the library default stands) from `def`.
@@ -111,21 +133,22 @@ tsg_tile_config fill_defaults(tsg_tile_config c, const tsg_tile_config& def) {
     if (c.vec <= 0) c.vec = def.vec;
     if (c.raster < 0) c.raster = def.raster;
     if (c.sched < 0) c.sched = def.sched;
+    if (c.split_k <= 0) c.split_k = tile_given ? 1 : def.split_k;
     return c;
 }
 
-bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-
-// Fig. 10's rule for `vect` on this hardware: wide accesses need every contiguous run to
-// start on a 16-byte boundary, i.e. leading dimensions (and Cin / Cout for the gathered
-// operand) divisible by the vector size and aligned bases.
+// Fig. 10's rule for `vect` on this hardware.  The k tile is a multiple of the vector size
+// by construction and the remainder of a loop is peeled into masked scalar code, so a wide
+// access only has to stay inside one contiguous run of its operand.  Rows of a matrix are
+// such runs whatever their leading dimension (the hardware fetches a 16-byte chunk from any
+// element-aligned address); the gathered operand of a convolution is contiguous only along
+// Cin, so there the innermost extent Cin must be divisible by the vector size.
 bool vec_legal(const Problem& p, int vec) {
     if (vec == 1) return true;
     if (vec != vec_max(p.dtype)) return false;
-    if (!aligned16(p.A) || !aligned16(p.B)) return false;
-    if (p.op == TSG_OP_CONV2D_NHWC) return p.Cin % vec == 0 && p.ldb % vec == 0;
-    if (p.lda % vec || p.ldb % vec) return false;
-    if (p.batch > 1 && (p.stride_a % vec || p.stride_b % vec)) return false;
+    const uintptr_t es = (uintptr_t)elem_size(p.dtype);
+    if (reinterpret_cast<uintptr_t>(p.A) % es || reinterpret_cast<uintptr_t>(p.B) % es) return false;
+    if (p.op == TSG_OP_CONV2D_NHWC) return p.Cin % vec == 0;
     return true;
 }
 
@@ -143,13 +166,23 @@ tsg_status make_plan(const Problem& p, const tsg_tile_config& cfg, int alternati
     if (!e) return TSG_E_SILENCEABLE;
     if (!vec_legal(p, cfg.vec)) return TSG_E_SILENCEABLE;
     if (cfg.raster != 0 && cfg.raster != 1) return TSG_E_SILENCEABLE;
+    if (cfg.split_k < 1 || cfg.split_k > kMaxSplit) return TSG_E_SILENCEABLE;
 
     int64_t m_main, m_rest, n_main, n_rest, k_main, k_rest, t;
     tsg_split(p.M, e->bm, &m_main, &m_rest, &t);
     tsg_split(p.N, e->bn, &n_main, &n_rest, &t);
     tsg_split(p.K, e->bk, &k_main, &k_rest, &t);
     const int64_t tiles_m = (p.M + e->bm - 1) / e->bm, tiles_n = (p.N + e->bn - 1) / e->bn;
-    if (tiles_m * tiles_n > 0x7fffffff / 2 || p.batch > 65535) return TSG_E_SILENCEABLE;
+    if (tiles_m * tiles_n * cfg.split_k > 0x7fffffff / 2 || p.batch > 65535) return TSG_E_SILENCEABLE;
+    void* ws = nullptr;
+    if (cfg.split_k > 1) {
+        // every split needs at least one k step, and the partial tiles need the workspace
+        if (cfg.split_k > (p.K + e->bk - 1) / e->bk) return TSG_E_SILENCEABLE;
+        if (p.batch * tiles_m * tiles_n > kMaxSlots) return TSG_E_SILENCEABLE;
+        std::lock_guard<std::mutex> g(g_mu);
+        if (!g_ws || ws_bytes_needed(*e, p.batch, p.M, p.N, cfg.split_k) > g_ws_bytes) return TSG_E_SILENCEABLE;
+        ws = g_ws;
+    }
 
     const bool edge = m_rest || n_rest || k_rest;
     out->entry = e;
@@ -166,6 +199,9 @@ tsg_status make_plan(const Problem& p, const tsg_tile_config& cfg, int alternati
     a.m_main = (int)m_main; a.n_main = (int)n_main; a.k_full = (int)(k_main / e->bk);
     a.flags = p.flags & (TSG_NEGATE | TSG_ACCUMULATE);
     a.raster = cfg.raster;
+    a.split_k = cfg.split_k;
+    a.counters = (int*)ws;
+    a.ws = ws ? (float*)((char*)ws + kCounterBytes) : nullptr;
     a.H = (int)p.H; a.W = (int)p.W; a.Cin = (int)p.Cin; a.Ho = (int)p.Ho; a.Wo = (int)p.Wo;
     a.KW = (int)p.KW; a.sh = (int)p.sh; a.sw = (int)p.sw; a.ph = (int)p.ph; a.pw = (int)p.pw;
 
@@ -201,7 +237,12 @@ tsg_status run(const Problem& p, hipStream_t s) {
         pinned = g_pinned[p.op][p.dtype];
         pin = g_pin[p.op][p.dtype];
     }
-    const tsg_tile_config heur = heuristic(p.dtype, p.batch, p.M, p.N, p.K);
+    int64_t ws_bytes;
+    {
+        std::lock_guard<std::mutex> g(g_mu);
+        ws_bytes = g_ws ? g_ws_bytes : 0;
+    }
+    const tsg_tile_config heur = heuristic(p.dtype, p.batch, p.M, p.N, p.K, ws_bytes);
     Plan pl;
     if (pinned) {
         if (make_plan(p, pin, 0, &pl) == TSG_OK) return enqueue(p, pl, s);
@@ -253,21 +294,25 @@ tsg_status conv_problem(int dtype, int64_t N, int64_t H, int64_t W, int64_t Cin,
     return TSG_OK;
 }
 
-// Enumerated search space: every instantiated tile x {wide, scalar} access x raster order.
+// Enumerated search space: every instantiated tile x {wide access with either raster order,
+// scalar access, wide access with the k loop split 2, 4, 8 or 16 ways}.
+constexpr int kPointsPerTile = 7;
 int space_size(tsg_dtype dt) {
     int n = 0;
     kernels(dt, &n);
-    return 3 * n;
+    return kPointsPerTile * n;
 }
 
 tsg_tile_config space_point(tsg_dtype dt, int idx) {
     int n = 0;
     const KernelEntry* t = kernels(dt, &n);
-    const KernelEntry& e = t[idx / 3];
-    switch (idx % 3) {
+    const KernelEntry& e = t[idx / kPointsPerTile];
+    const int k = idx % kPointsPerTile;
+    switch (k) {
         case 0: return config_of(e, vec_max(dt), 1);
         case 1: return config_of(e, vec_max(dt), 0);
-        default: return config_of(e, 1, 1);
+        case 2: return config_of(e, 1, 1);
+        default: return config_of(e, vec_max(dt), 0, 1 << (k - 2));
     }
 }
 
@@ -288,7 +333,10 @@ tsg_status autotune(Problem p, hipStream_t s, int iters, tsg_tile_config* best, 
         const tsg_tile_config c = space_point(p.dtype, i);
         Plan pl;
         float med = -1.f;
-        if (make_plan(p, c, 0, &pl) == TSG_OK) {
+        // splitting k only pays while the unsplit tiles cannot fill the chip twice over
+        const bool worth = c.split_k == 1 ||
+                           p.batch * ((p.M + c.bm - 1) / c.bm) * ((p.N + c.bn - 1) / c.bn) < 2 * kCUs;
+        if (worth && make_plan(p, c, 0, &pl) == TSG_OK) {
             st = enqueue(p, pl, s);   // warm-up
             // best of three batches of `iters` back-to-back calls, mean time per call
             for (int round = 0; round < 3 && st == TSG_OK; ++round) {
@@ -302,7 +350,9 @@ tsg_status autotune(Problem p, hipStream_t s, int iters, tsg_tile_config* best, 
                 if (med < 0 || t < med) med = t;
             }
             if (st != TSG_OK) break;
-            if (bms < 0 || med < bms) { bms = med; bcfg = c; }
+            // a later point must win by more than timing noise: among ties the earlier point
+            // (XCD-aware raster first, which fetches fewer bytes) stays
+            if (bms < 0 || med < bms * 0.995f) { bms = med; bcfg = c; }
         }
         if (written < log_cap) {
             log[written].config = c;
@@ -402,17 +452,19 @@ tsg_status tsg_tile_config_check(tsg_op op, tsg_dtype dtype, int64_t M, int64_t 
                                  const tsg_tile_config* cfg) {
     if (!valid_op(op) || !valid_dtype(dtype) || !cfg) return TSG_E_INVALID;
     if (M <= 0 || N <= 0 || K <= 0) return TSG_E_INVALID;
-    if (cfg->bm < 0 || cfg->bn < 0 || cfg->bk < 0 || cfg->wm < 0 || cfg->wn < 0 || cfg->vec < 0) return TSG_E_INVALID;
-    const tsg_tile_config c = fill_defaults(*cfg, heuristic(dtype, 1, M, N, K));
-    if (!find_entry(dtype, c)) return TSG_E_SILENCEABLE;
+    if (cfg->bm < 0 || cfg->bn < 0 || cfg->bk < 0 || cfg->wm < 0 || cfg->wn < 0 || cfg->vec < 0 || cfg->split_k < 0)
+        return TSG_E_INVALID;
+    if (op == TSG_OP_CONV2D_NHWC && contig <= 0) return TSG_E_INVALID;
+    const tsg_tile_config c = fill_defaults(*cfg, heuristic(dtype, 1, M, N, K, 0));
+    const KernelEntry* e = find_entry(dtype, c);
+    if (!e) return TSG_E_SILENCEABLE;
     if (c.raster != 0 && c.raster != 1) return TSG_E_SILENCEABLE;
+    if (c.split_k < 1 || c.split_k > kMaxSplit || c.split_k > (K + e->bk - 1) / e->bk) return TSG_E_SILENCEABLE;
     if (c.vec == 1) return TSG_OK;
     if (c.vec != vec_max(dtype)) return TSG_E_SILENCEABLE;
-    // natural leading dimensions: A rows have K (or M when transposed, or Cin-long runs
-    // when gathered) elements, B rows have N
-    const int64_t a_run = op == TSG_OP_GEMM ? K : op == TSG_OP_GEMM_TRANSA ? M : contig;
-    if (op == TSG_OP_CONV2D_NHWC && contig <= 0) return TSG_E_INVALID;
-    if (a_run % c.vec || N % c.vec) return TSG_E_SILENCEABLE;
+    // the innermost contiguous extent of the gathered operand is Cin; matrix rows are
+    // contiguous runs of any length and their remainder is peeled (see vec_legal)
+    if (op == TSG_OP_CONV2D_NHWC && contig % c.vec) return TSG_E_SILENCEABLE;
     return TSG_OK;
 }
 
@@ -420,11 +472,13 @@ tsg_status tsg_tile_config_set(tsg_op op, tsg_dtype dtype, const tsg_tile_config
     if (!valid_op(op) || !valid_dtype(dtype)) return TSG_E_INVALID;
     std::lock_guard<std::mutex> g(g_mu);
     if (!cfg) { g_pinned[op][dtype] = false; return TSG_OK; }
-    if (cfg->bm < 0 || cfg->bn < 0 || cfg->bk < 0 || cfg->wm < 0 || cfg->wn < 0 || cfg->vec < 0) return TSG_E_INVALID;
+    if (cfg->bm < 0 || cfg->bn < 0 || cfg->bk < 0 || cfg->wm < 0 || cfg->wn < 0 || cfg->vec < 0 || cfg->split_k < 0)
+        return TSG_E_INVALID;
     int n = 0;
     const KernelEntry* t = kernels(dtype, &n);
     const tsg_tile_config c = fill_defaults(*cfg, config_of(t[0], vec_max(dtype), 1));
     if (!find_entry(dtype, c)) return TSG_E_SILENCEABLE;
+    if (c.split_k > kMaxSplit) return TSG_E_SILENCEABLE;
     if (c.vec != 1 && c.vec != vec_max(dtype)) return TSG_E_SILENCEABLE;
     if (c.raster != 0 && c.raster != 1) return TSG_E_SILENCEABLE;
     g_pin[op][dtype] = c;
@@ -436,8 +490,25 @@ tsg_status tsg_tile_config_get(tsg_op op, tsg_dtype dtype, int64_t M, int64_t N,
     if (!valid_op(op) || !valid_dtype(dtype) || !out) return TSG_E_INVALID;
     if (M <= 0 || N <= 0 || K <= 0) return TSG_E_INVALID;
     std::lock_guard<std::mutex> g(g_mu);
-    *out = g_pinned[op][dtype] ? g_pin[op][dtype] : heuristic(dtype, 1, M, N, K);
+    *out = g_pinned[op][dtype] ? g_pin[op][dtype] : heuristic(dtype, 1, M, N, K, g_ws ? g_ws_bytes : 0);
     return TSG_OK;
+}
+
+tsg_status tsg_workspace_set(void* ws, int64_t bytes) {
+    if ((ws == nullptr) != (bytes == 0) || bytes < 0) return TSG_E_INVALID;
+    if (ws && (bytes <= kCounterBytes || (reinterpret_cast<uintptr_t>(ws) & 255u))) return TSG_E_INVALID;
+    if (ws && hipMemset(ws, 0, kCounterBytes) != hipSuccess) return TSG_E_RUNTIME;   // counters start at zero
+    std::lock_guard<std::mutex> g(g_mu);
+    g_ws = ws;
+    g_ws_bytes = bytes;
+    return TSG_OK;
+}
+
+int64_t tsg_workspace_bytes(tsg_dtype dtype, int64_t batch, int64_t M, int64_t N, const tsg_tile_config* cfg) {
+    if (!valid_dtype(dtype) || !cfg || batch <= 0 || M <= 0 || N <= 0) return -1;
+    const KernelEntry* e = find_entry(dtype, *cfg);
+    if (!e || cfg->split_k < 1 || cfg->split_k > kMaxSplit) return -1;
+    return ws_bytes_needed(*e, batch, M, N, cfg->split_k);
 }
 
 tsg_status tsg_last_launch(tsg_launch_info* out) {

@@ -19,6 +19,8 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned short u16;
 typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
+// 16-byte global access that only promises element alignment (odd leading dimensions)
+typedef u16x8 u16x8_u __attribute__((aligned(2)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) bf16x4* lds_bf16x4_ptr;
 
@@ -71,15 +73,20 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_kernel(const KArgs p
     const int wm0 = (wave / T::WAVES_N) * T::WM, wn0 = (wave % T::WAVES_N) * T::WN;
     const int li = lane & 31, lh = lane >> 5;
 
+    const int tiles = p.tiles_m * p.tiles_n;
+    const int split = blockIdx.x / tiles, tile = blockIdx.x - split * tiles;   // split is the slow index
     int tm, tn;
-    tile_coords(p, blockIdx.x, tm, tn);
+    tile_coords(p, tile, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
     const u16* __restrict__ A = (const u16*)p.A + (long long)blockIdx.y * p.stride_a;
     const u16* __restrict__ B = (const u16*)p.B + (long long)blockIdx.y * p.stride_b;
     float* __restrict__ C = p.C + (long long)blockIdx.y * p.stride_c;
 
     const bool interior = !EDGE || (m0 + BM <= p.m_main && n0 + BN <= p.n_main);
-    const int nk = (p.K + BK - 1) / BK;
+    // this workgroup's k steps: [kb, kb + nk) of the whole loop (split k, see the fp32 kernels)
+    const int nk_all = (p.K + BK - 1) / BK;
+    const int kb = (int)((long long)nk_all * split / p.split_k);
+    const int nk = (int)((long long)nk_all * (split + 1) / p.split_k) - kb;
 
     // 8-element (16-byte) chunks along the contiguous dimension of each stored operand.
     // kmaj == true: the stored rows run along k (A_ROW, A_CONV); false: along i or j.
@@ -131,7 +138,9 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_kernel(const KArgs p
         }
     };
 
-    auto load_tiles = [&](int kt, bool fast) {
+    auto load_tiles = [&](int kt_local) {
+        const int kt = kb + kt_local;
+        const bool fast = EDGE ? (interior && kt < p.k_full) : true;
         const int k0 = kt * BK;
 #pragma unroll
         for (int q = 0; q < PA; ++q) {
@@ -139,7 +148,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_kernel(const KArgs p
             if constexpr (AMODE == A_ROW) {
                 const int k = k0 + a_c;
                 if (VEC == 8 && (fast || (m0 + r < p.M && k + 8 <= p.K))) {
-                    ra[q] = *(const u16x8*)(A + (long long)(m0 + r) * p.lda + k);
+                    ra[q] = *(const u16x8_u*)(A + (long long)(m0 + r) * p.lda + k);
                 } else {
 #pragma unroll
                     for (int e = 0; e < 8; ++e) ra[q][e] = a_elem(q, r, k + e);
@@ -147,7 +156,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_kernel(const KArgs p
             } else if constexpr (AMODE == A_COL) {
                 const int k = k0 + r, m = m0 + a_c;
                 if (VEC == 8 && (fast || (k < p.K && m + 8 <= p.M))) {
-                    ra[q] = *(const u16x8*)(A + (long long)k * p.lda + m);
+                    ra[q] = *(const u16x8_u*)(A + (long long)k * p.lda + m);
                 } else {
 #pragma unroll
                     for (int e = 0; e < 8; ++e) ra[q][e] = a_elem(q, k, m + e);
@@ -161,7 +170,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_kernel(const KArgs p
                         const int kh = tap / p.KW, kw = tap - kh * p.KW;
                         const int hi = cv_hi0[q] + kh, wi = cv_wi0[q] + kw;
                         if (hi >= 0 && hi < p.H && wi >= 0 && wi < p.W)
-                            v = *(const u16x8*)(A + ((long long)(cv_base[q] + hi) * p.W + wi) * p.Cin + ci);
+                            v = *(const u16x8_u*)(A + ((long long)(cv_base[q] + hi) * p.W + wi) * p.Cin + ci);
                     }
                     ra[q] = v;
                 } else {
@@ -174,7 +183,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_kernel(const KArgs p
         for (int q = 0; q < PB; ++q) {
             const int k = k0 + b_r + q * B_RPP, n = n0 + b_c;
             if (VEC == 8 && (fast || (k < p.K && n + 8 <= p.N))) {
-                rb[q] = *(const u16x8*)(B + (long long)k * p.ldb + n);
+                rb[q] = *(const u16x8_u*)(B + (long long)k * p.ldb + n);
             } else {
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
@@ -241,7 +250,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_kernel(const KArgs p
                 // tile kt+1 has had a whole step to arrive: park it in the other stage, then
                 // reuse the same registers for the loads of tile kt+2
                 if (kt + 1 < nk) store_tiles(stage ^ 1);
-                if (kt + 2 < nk) load_tiles(kt + 2, EDGE ? (interior && kt + 2 < p.k_full) : true);
+                if (kt + 2 < nk) load_tiles(kt + 2);
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -270,9 +279,9 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_kernel(const KArgs p
     };
 
     // tile t+1 sits in registers and tile t+2 is in flight while step t is multiplied
-    load_tiles(0, EDGE ? (interior && 0 < p.k_full) : true);
+    load_tiles(0);
     store_tiles(0);
-    if (nk > 1) load_tiles(1, EDGE ? (interior && 1 < p.k_full) : true);
+    if (nk > 1) load_tiles(1);
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
         if constexpr (T::SCHED == 1) {
@@ -280,9 +289,41 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_kernel(const KArgs p
         } else {
             compute_plain(kt & 1);
             if (kt + 1 < nk) store_tiles((kt & 1) ^ 1);
-            if (kt + 2 < nk) load_tiles(kt + 2, EDGE ? (interior && kt + 2 < p.k_full) : true);
+            if (kt + 2 < nk) load_tiles(kt + 2);
         }
         __syncthreads();
+    }
+
+    // split k: park the partial tile, count the arrival, and let the last arrival reduce
+    if (p.split_k > 1) {
+        __shared__ int arrived;
+        const long long slot = (long long)blockIdx.y * tiles + tile;
+        float* ws = p.ws + slot * p.split_k * (BM * BN);
+        float* mine = ws + (long long)split * (BM * BN);
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mine[((i * NI + j) * 16 + r) * NT + tid] = acc[i][j][r];
+        __threadfence();   // partial visible device-wide before the arrival is counted
+        __syncthreads();
+        if (tid == 0) arrived = atomicAdd(p.counters + slot, 1);
+        __syncthreads();
+        if (arrived != p.split_k - 1) return;
+        __threadfence();   // the other partials are visible after their arrivals were seen
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int e = ((i * NI + j) * 16 + r) * NT + tid;
+                    float v = ws[e];
+                    for (int sp = 1; sp < p.split_k; ++sp) v += ws[(long long)sp * (BM * BN) + e];
+                    acc[i][j][r] = v;
+                }
+        if (tid == 0) p.counters[slot] = 0;   // ready for the next launch on this workspace
     }
 
     const bool neg = p.flags & FLAG_NEGATE, accum = p.flags & FLAG_ACCUMULATE;
@@ -307,7 +348,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_kernel(const KArgs p
 
 template <class T, int AMODE>
 hipError_t launch_mode(int variant, const KArgs& a, int batch, hipStream_t s) {
-    const dim3 grid(a.tiles_m * a.tiles_n, batch, 1), block(T::NT, 1, 1);
+    const dim3 grid(a.tiles_m * a.tiles_n * a.split_k, batch, 1), block(T::NT, 1, 1);
     constexpr int A_SIZE = (AMODE != A_COL) ? T::BM * T::LDK : T::BK * T::LDA_T;
     constexpr int BYTES = 2 * (A_SIZE + T::BK * T::LDB) * 2;
     void (*fn)(const KArgs) = nullptr;

@@ -15,6 +15,11 @@
 // The main/remainder split of Fig. 8 is taken per tile: tiles inside
 // [0,m_main) x [0,n_main) and k steps below k_full run the unmasked loaders, the
 // remainder runs masked ones (zero fill), chosen by a wavefront-uniform branch.
+//
+// Split k: with split_k = S > 1, S workgroups share one tile of C, each taking a contiguous
+// range of k steps.  Each parks its partial tile in the workspace and bumps the tile's
+// arrival counter; the workgroup that arrives last adds the S partials in split order (so
+// the sum does not depend on who was last), applies the epilogue and resets the counter.
 #pragma once
 #include "tsg_internal.h"
 
@@ -23,6 +28,10 @@ namespace {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+// 16-byte global access that only promises element alignment: rows of an operand with an
+// odd leading dimension start on any 4-byte boundary, and the hardware fetches such a chunk
+// with one instruction all the same
+typedef f32x4 f32x4_u __attribute__((aligned(4)));
 
 constexpr unsigned FLAG_NEGATE = 1u, FLAG_ACCUMULATE = 2u;
 constexpr int kXcds = 8;      // workgroup ids are dealt round-robin over this many L2 domains
@@ -94,8 +103,10 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_kernel(const KArgs p)
     const int wm0 = (wave / T::WAVES_N) * T::WM, wn0 = (wave % T::WAVES_N) * T::WN;
     const int li = lane & 31, lh = lane >> 5;
 
+    const int tiles = p.tiles_m * p.tiles_n;
+    const int split = blockIdx.x / tiles, tile = blockIdx.x - split * tiles;   // split is the slow index
     int tm, tn;
-    tile_coords(p, blockIdx.x, tm, tn);
+    tile_coords(p, tile, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
     const float* __restrict__ A = (const float*)p.A + (long long)blockIdx.y * p.stride_a;
     const float* __restrict__ B = (const float*)p.B + (long long)blockIdx.y * p.stride_b;
@@ -103,7 +114,10 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_kernel(const KArgs p)
 
     // Remainder tiles (Fig. 8's %rest) take the masked loaders for every k step.
     const bool interior = !EDGE || (m0 + BM <= p.m_main && n0 + BN <= p.n_main);
-    const int nk = (p.K + BK - 1) / BK;
+    // this workgroup's k steps: [kb, kb + nk) of the (K + BK - 1) / BK steps of the whole loop
+    const int nk_all = (p.K + BK - 1) / BK;
+    const int kb = (int)((long long)nk_all * split / p.split_k);
+    const int nk = (int)((long long)nk_all * (split + 1) / p.split_k) - kb;
 
     // ---- per-thread global->LDS assignment: 4-element chunks along the contiguous dim
     constexpr int A_CPR = (AMODE == A_COL) ? BM / 4 : BK / 4;   // chunks per stored row
@@ -157,7 +171,9 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_kernel(const KArgs p)
         }
     };
 
-    auto load_tiles = [&](int kt, bool fast) {
+    auto load_tiles = [&](int kt_local) {
+        const int kt = kb + kt_local;
+        const bool fast = EDGE ? (interior && kt < p.k_full) : true;
         const int k0 = kt * BK;
         // ---------------- A
 #pragma unroll
@@ -166,7 +182,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_kernel(const KArgs p)
             if constexpr (AMODE == A_ROW) {
                 const int k = k0 + a_c;
                 if (VEC == 4 && (fast || (m0 + r < p.M && k + 4 <= p.K))) {
-                    ra[q] = *(const f32x4*)(A + (long long)(m0 + r) * p.lda + k);
+                    ra[q] = *(const f32x4_u*)(A + (long long)(m0 + r) * p.lda + k);
                 } else {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) ra[q][e] = a_elem(q, r, k + e);
@@ -174,7 +190,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_kernel(const KArgs p)
             } else if constexpr (AMODE == A_COL) {
                 const int k = k0 + r, m = m0 + a_c;
                 if (VEC == 4 && (fast || (k < p.K && m + 4 <= p.M))) {
-                    ra[q] = *(const f32x4*)(A + (long long)k * p.lda + m);
+                    ra[q] = *(const f32x4_u*)(A + (long long)k * p.lda + m);
                 } else {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) ra[q][e] = a_elem(q, k, m + e);
@@ -189,7 +205,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_kernel(const KArgs p)
                         const int kh = tap / p.KW, kw = tap - kh * p.KW;
                         const int hi = cv_hi0[q] + kh, wi = cv_wi0[q] + kw;
                         if (hi >= 0 && hi < p.H && wi >= 0 && wi < p.W)
-                            v = *(const f32x4*)(A + ((long long)(cv_base[q] + hi) * p.W + wi) * p.Cin + ci);
+                            v = *(const f32x4_u*)(A + ((long long)(cv_base[q] + hi) * p.W + wi) * p.Cin + ci);
                     }
                     ra[q] = v;
                 } else {
@@ -203,7 +219,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_kernel(const KArgs p)
         for (int q = 0; q < PB; ++q) {
             const int k = k0 + b_r + q * B_RPP, n = n0 + b_c;
             if (VEC == 4 && (fast || (k < p.K && n + 4 <= p.N))) {
-                rb[q] = *(const f32x4*)(B + (long long)k * p.ldb + n);
+                rb[q] = *(const f32x4_u*)(B + (long long)k * p.ldb + n);
             } else {
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
@@ -270,7 +286,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_kernel(const KArgs p)
                 // tile kt+1 has had a whole step to arrive: park it in the other stage, then
                 // reuse the same registers for the loads of tile kt+2
                 if (kt + 1 < nk) store_tiles(stage ^ 1);
-                if (kt + 2 < nk) load_tiles(kt + 2, EDGE ? (interior && kt + 2 < p.k_full) : true);
+                if (kt + 2 < nk) load_tiles(kt + 2);
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -314,7 +330,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_kernel(const KArgs p)
             if (s + 1 < S) fetch(s + 1);
             if (s == S / 2) {
                 if (kt + 1 < nk) store_tiles(stage ^ 1);
-                if (kt + 2 < nk) load_tiles(kt + 2, EDGE ? (interior && kt + 2 < p.k_full) : true);
+                if (kt + 2 < nk) load_tiles(kt + 2);
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -367,7 +383,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_kernel(const KArgs p)
                 fetch(s + 1 < S ? cur : nxt, s + 1 < S ? s + 1 : 0);
                 if (s == S / 4) {
                     if (kt + 1 < nk) store_tiles(nxt);
-                    if (kt + 2 < nk) load_tiles(kt + 2, EDGE ? (interior && kt + 2 < p.k_full) : true);
+                    if (kt + 2 < nk) load_tiles(kt + 2);
                 }
                 if (s == S / 2) __syncthreads();
                 __builtin_amdgcn_sched_barrier(0);
@@ -403,9 +419,9 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_kernel(const KArgs p)
     };
 
     // ---- main loop: tile t+1 sits in registers and tile t+2 is in flight while step t is multiplied
-    load_tiles(0, EDGE ? (interior && 0 < p.k_full) : true);
+    load_tiles(0);
     store_tiles(0);
-    if (nk > 1) load_tiles(1, EDGE ? (interior && 1 < p.k_full) : true);
+    if (nk > 1) load_tiles(1);
     __syncthreads();
     if constexpr (T::SCHED == 3) run_three_stage();
     for (int kt = 0; T::SCHED != 3 && kt < nk; ++kt) {
@@ -416,9 +432,41 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_kernel(const KArgs p)
         } else {
             compute_plain(kt & 1);
             if (kt + 1 < nk) store_tiles((kt & 1) ^ 1);
-            if (kt + 2 < nk) load_tiles(kt + 2, EDGE ? (interior && kt + 2 < p.k_full) : true);
+            if (kt + 2 < nk) load_tiles(kt + 2);
         }
         __syncthreads();
+    }
+
+    // ---- split k: park the partial tile, count the arrival, and let the last arrival reduce
+    if (p.split_k > 1) {
+        __shared__ int arrived;
+        const long long slot = (long long)blockIdx.y * tiles + tile;
+        float* ws = p.ws + slot * p.split_k * (BM * BN);
+        float* mine = ws + (long long)split * (BM * BN);
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mine[((i * NI + j) * 16 + r) * NT + tid] = acc[i][j][r];
+        __threadfence();   // partial visible device-wide before the arrival is counted
+        __syncthreads();
+        if (tid == 0) arrived = atomicAdd(p.counters + slot, 1);
+        __syncthreads();
+        if (arrived != p.split_k - 1) return;
+        __threadfence();   // the other partials are visible after their arrivals were seen
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int e = ((i * NI + j) * 16 + r) * NT + tid;
+                    float v = ws[e];
+                    for (int sp = 1; sp < p.split_k; ++sp) v += ws[(long long)sp * (BM * BN) + e];
+                    acc[i][j][r] = v;
+                }
+        if (tid == 0) p.counters[slot] = 0;   // ready for the next launch on this workspace
     }
 
     // ---- epilogue: sign, optional accumulate, masked at the remainder
@@ -445,7 +493,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_kernel(const KArgs p)
 template <class T, int AMODE>
 hipError_t launch_mode(int variant, const KArgs& a, int batch, hipStream_t s) {
     using L = Lds<T, AMODE>;
-    const dim3 grid(a.tiles_m * a.tiles_n, batch, 1), block(T::NT, 1, 1);
+    const dim3 grid(a.tiles_m * a.tiles_n * a.split_k, batch, 1), block(T::NT, 1, 1);
     void (*fn)(const KArgs) = nullptr;
     switch (variant) {
         case 0: fn = gemm_f32_kernel<T, AMODE, 4, false>; break;

@@ -25,6 +25,12 @@ struct KArgs {
     int k_full;              // number of complete BK steps (the rest of k is masked)
     unsigned flags;
     int raster;
+    // split of the k loop over `split_k` workgroups per tile (1 = none); partial tiles meet in
+    // `ws` ([batch][tile][split][BM*BN] floats, register order) and `counters` ([batch][tile])
+    // counts the arrivals: the last workgroup to arrive sums the partials in split order
+    int split_k;
+    float* ws;
+    int* counters;
     // convolution geometry (A_CONV only)
     int H, W, Cin, Ho, Wo, KW, sh, sw, ph, pw;
 };

@@ -142,15 +142,22 @@ CONFIGS = {
     4: dict(op="conv2d_nhwc", dtype="f32", N=8, H=56, W=56, Cin=64, Cout=64, KH=3, KW=3,
             stride=1, pad=1, seed=3, flags=()),
     5: dict(op="gemm", dtype="bf16", M=8192, N=8192, K=8192, dist="normal", seed=4, flags=("negate",)),
+    # Case Study 4 / Fig. 7 of the paper: one ResNet-50 layer's loop nest, batch loop included
+    6: dict(op="gemm_batched", dtype="f32", B=6, M=196, N=256, K=2305, dist="uniform", seed=5, flags=()),
 }
 
-# Case Study 4 / Fig. 7 of the paper: one ResNet-50 layer's loop nest.
 PAPER_BATCH_MATMUL = dict(B=6, M=196, N=256, K=2305)
 
 
 def config_inputs(k: int):
     """Host arrays for workload configuration k (1-based)."""
     c = CONFIGS[k]
+    if c["op"] == "gemm_batched":
+        # one stream per tensor: the batch index is the slowest dimension of A and of B
+        a, b = gemm_inputs(c["B"] * c["M"], c["N"], c["K"], seed=c["seed"], dist=c["dist"])
+        nb = c["B"] * c["K"] * c["N"]
+        b = (uniform_pm1(c["seed"], 1, nb) if c["dist"] == "uniform" else small_ints(c["seed"], 1, nb))
+        return c, a.reshape(c["B"], c["M"], c["K"]), b.reshape(c["B"], c["K"], c["N"])
     if c["op"] in ("gemm", "gemm_transA"):
         a, b = gemm_inputs(c["M"], c["N"], c["K"], seed=c["seed"], dist=c["dist"],
                            trans_a=(c["op"] == "gemm_transA"), bf16=(c["dtype"] == "bf16"))

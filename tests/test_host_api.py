@@ -50,6 +50,7 @@ def test_search_space_enumeration():
                 c = tsg.tile_config_enum(op, dt, i)
                 assert c.bm % c.wm == 0 and c.bn % c.wn == 0 and c.wm % 32 == 0 and c.wn % 32 == 0
                 assert c.vec in (1, vmax) and c.raster in (0, 1) and c.sched in (0, 1, 2, 3)
+                assert c.split_k in (1, 2, 4, 8, 16)
                 key = tuple(c.as_dict().values())
                 assert key not in seen
                 seen.add(key)
@@ -60,27 +61,58 @@ def test_search_space_enumeration():
 
 
 def test_vect_constraint_matches_fig10_rule():
-    """vec > 1 is legal exactly when the contiguous extents are multiples of the vector
-    size: the library's check must agree with the oracle's statement of Fig. 10."""
+    """Fig. 10: vect is legal only when the innermost extent is divisible by the vector size.
+    For the gathered operand of a convolution that extent is Cin and the library's check
+    must agree with the oracle's statement of the rule; a matrix row is one contiguous run
+    whose remainder is peeled, so the GEMM calls accept the wide form for every shape."""
     c = tsg.tile_config_enum(tsg.OP_GEMM, tsg.F32, 0)
     assert c.vec == 4
-    for K in (2304, 2305, 2306, 2308, 64):
-        for N in (256, 255, 64, 66):
-            legal = oracle.vect_legal(K, 0, 4, 1) and oracle.vect_legal(N, 0, 4, 1)
-            st = tsg.tile_config_check(tsg.OP_GEMM, tsg.F32, 196, N, K, c)
-            assert st == (tsg.OK if legal else tsg.E_SILENCEABLE), (K, N)
-    # transposed left operand: its contiguous extent is M
-    assert tsg.tile_config_check(tsg.OP_GEMM_TRANSA, tsg.F32, 196, 256, 2305, c) == tsg.OK
-    assert tsg.tile_config_check(tsg.OP_GEMM_TRANSA, tsg.F32, 197, 256, 2304, c) == tsg.E_SILENCEABLE
-    # gathered operand: runs of Cin
-    assert tsg.tile_config_check(tsg.OP_CONV2D_NHWC, tsg.F32, 25088, 64, 576, c, contig=64) == tsg.OK
-    assert tsg.tile_config_check(tsg.OP_CONV2D_NHWC, tsg.F32, 25088, 64, 27, c, contig=3) == tsg.E_SILENCEABLE
+    for cin in (64, 3, 4, 6, 8, 30):
+        legal = oracle.vect_legal(cin, 0, 4, 1)
+        st = tsg.tile_config_check(tsg.OP_CONV2D_NHWC, tsg.F32, 25088, 64, 9 * cin, c, contig=cin)
+        assert st == (tsg.OK if legal else tsg.E_SILENCEABLE), cin
+    c8 = tsg.tile_config_enum(tsg.OP_CONV2D_NHWC, tsg.BF16_F32ACC, 0)
+    assert c8.vec == 8
+    for cin in (64, 8, 12, 4):
+        legal = oracle.vect_legal(cin, 0, 8, 1)
+        st = tsg.tile_config_check(tsg.OP_CONV2D_NHWC, tsg.BF16_F32ACC, 25088, 64, 9 * cin, c8, contig=cin)
+        assert st == (tsg.OK if legal else tsg.E_SILENCEABLE), cin
+    for K in (2304, 2305, 2306, 64):
+        for N in (256, 255, 66):
+            assert tsg.tile_config_check(tsg.OP_GEMM, tsg.F32, 196, N, K, c) == tsg.OK
+            assert tsg.tile_config_check(tsg.OP_GEMM_TRANSA, tsg.F32, 197, N, K, c) == tsg.OK
     # vec = 1 has no precondition
     c.vec = 1
-    assert tsg.tile_config_check(tsg.OP_GEMM, tsg.F32, 196, 255, 2305, c) == tsg.OK
+    assert tsg.tile_config_check(tsg.OP_CONV2D_NHWC, tsg.F32, 25088, 64, 27, c, contig=3) == tsg.OK
     # a vector size the hardware path does not have
     c.vec = 2
     assert tsg.tile_config_check(tsg.OP_GEMM, tsg.F32, 196, 256, 2304, c) == tsg.E_SILENCEABLE
+
+
+def test_split_k_legality_and_workspace_size():
+    """split_k tiles the k loop at the grid level: at most 16 ways, never more ways than
+    there are k steps, and a call needs batch * tiles * split_k partial tiles of workspace
+    after the 64 KiB of counters."""
+    op, dt = tsg.OP_GEMM, tsg.F32
+    c = tsg.TileConfig(bm=64, bn=64, bk=64, wm=32, wn=32, vec=4, raster=0, sched=0, split_k=4)
+    assert tsg.tile_config_check(op, dt, 196, 256, 2305, c) == tsg.OK
+    assert tsg.tile_config_check(op, dt, 196, 256, 200, c) == tsg.OK          # 4 steps of 64
+    assert tsg.tile_config_check(op, dt, 196, 256, 192, c) == tsg.E_SILENCEABLE   # 3 steps
+    c.split_k = 32
+    assert tsg.tile_config_check(op, dt, 196, 256, 1 << 20, c) == tsg.E_SILENCEABLE
+    c.split_k = -1
+    assert tsg.tile_config_check(op, dt, 196, 256, 2305, c) == tsg.E_INVALID
+    c.split_k = 4
+    tiles = oracle.split(196 + 63, 64)[2] * oracle.split(256, 64)[2]
+    assert tsg.workspace_bytes(dt, 6, 196, 256, c) == 65536 + 6 * tiles * 4 * 64 * 64 * 4
+    c.split_k = 1
+    assert tsg.workspace_bytes(dt, 6, 196, 256, c) == 0
+    # a workspace must be a 256-byte aligned device buffer larger than the counter area
+    for ws, nbytes in ((FAKE + 4, 1 << 20), (FAKE, 1024), (FAKE, 0)):
+        with pytest.raises(tsg.TsgError) as e:
+            tsg.workspace_set(ws, nbytes)
+        assert e.value.status == tsg.E_INVALID
+    tsg.workspace_set(None)
 
 
 def test_tile_zero_means_default_and_oversized_tile_is_legal():
@@ -169,18 +201,27 @@ def test_invalid_arguments_are_definite_errors():
 
 
 def test_strict_call_with_failed_precondition_is_silenceable_and_enqueues_nothing():
-    """The pinned config wants 16-byte accesses; lda = 9 breaks the divisibility rule.
+    """The pinned config splits the k loop, which needs a workspace that was never given.
     With TSG_STRICT there is no further alternative: silenceable, nothing launched (the
     pointers are fake, so a launch attempt would have been a runtime error instead)."""
     op, dt = tsg.OP_GEMM, tsg.F32
-    c = tsg.tile_config_enum(op, dt, 0)
-    assert c.vec == 4
+    c = tsg.TileConfig(bm=64, bn=64, bk=64, wm=32, wn=32, vec=4, raster=0, sched=0, split_k=2)
+    tsg.workspace_set(None)
     tsg.tile_config_set(op, dt, c)
     try:
         with pytest.raises(tsg.SilenceableError):
-            tsg.gemm(dt, 8, 8, 8, FAKE, 9, FAKE, 8, FAKE, 8, tsg.STRICT, 0)
+            tsg.gemm(dt, 8, 8, 256, FAKE, 256, FAKE, 8, FAKE, 8, tsg.STRICT, 0)
+        # more splits than k steps
         with pytest.raises(tsg.SilenceableError):
-            tsg.gemm(dt, 8, 8, 8, FAKE + 4, 8, FAKE, 8, FAKE, 8, tsg.STRICT, 0)   # misaligned base
+            tsg.gemm(dt, 8, 8, 8, FAKE, 8, FAKE, 8, FAKE, 8, tsg.STRICT, 0)
+    finally:
+        tsg.tile_config_set(op, dt, None)
+    # the gathered operand: Cin = 3 cannot take 16-byte accesses
+    op = tsg.OP_CONV2D_NHWC
+    tsg.tile_config_set(op, dt, tsg.tile_config_enum(op, dt, 0))
+    try:
+        with pytest.raises(tsg.SilenceableError):
+            tsg.conv2d_nhwc(dt, 1, 8, 8, 3, 8, 3, 3, 1, 1, 1, 1, FAKE, FAKE, FAKE, tsg.STRICT, 0)
     finally:
         tsg.tile_config_set(op, dt, None)
 
