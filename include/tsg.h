@@ -84,7 +84,9 @@ enum {
  *                left to the compiler; 1 = explicit software pipeline (fragments one k
  *                group ahead, next tile parked in LDS mid-step); 2 = the same pipeline
  *                one MFMA ahead; 3 = as 2 with three LDS stages and the barrier in the
- *                middle of the step.  -1 = library default.
+ *                middle of the step; 4 / 5 = operand tiles loaded from global memory
+ *                straight into a ring of 3 / 4 LDS stages (two / three k steps in flight),
+ *                wide accesses only.  -1 = library default.
  *                Only (tile, sched) pairs that are instantiated are legal.
  *   split_k    : number of workgroups that share one tile of C, each taking a contiguous
  *                range of k steps (tiling the k loop at the grid level when i x j tiles

@@ -165,6 +165,7 @@ tsg_status make_plan(const Problem& p, const tsg_tile_config& cfg, int alternati
     const KernelEntry* e = find_entry(p.dtype, cfg);
     if (!e) return TSG_E_SILENCEABLE;
     if (!vec_legal(p, cfg.vec)) return TSG_E_SILENCEABLE;
+    if (e->sched >= 4 && cfg.vec == 1) return TSG_E_SILENCEABLE;   // direct-to-LDS forms move 16-byte chunks
     if (cfg.raster != 0 && cfg.raster != 1) return TSG_E_SILENCEABLE;
     if (cfg.split_k < 1 || cfg.split_k > kMaxSplit) return TSG_E_SILENCEABLE;
 
@@ -460,7 +461,7 @@ tsg_status tsg_tile_config_check(tsg_op op, tsg_dtype dtype, int64_t M, int64_t 
     if (!e) return TSG_E_SILENCEABLE;
     if (c.raster != 0 && c.raster != 1) return TSG_E_SILENCEABLE;
     if (c.split_k < 1 || c.split_k > kMaxSplit || c.split_k > (K + e->bk - 1) / e->bk) return TSG_E_SILENCEABLE;
-    if (c.vec == 1) return TSG_OK;
+    if (c.vec == 1) return e->sched >= 4 ? TSG_E_SILENCEABLE : TSG_OK;
     if (c.vec != vec_max(dtype)) return TSG_E_SILENCEABLE;
     // the innermost contiguous extent of the gathered operand is Cin; matrix rows are
     // contiguous runs of any length and their remainder is peeled (see vec_legal)

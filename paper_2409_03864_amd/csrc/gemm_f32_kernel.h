@@ -93,6 +93,66 @@ __device__ __forceinline__ void tile_coords(const KArgs& p, int bid, int& tm, in
     tn = id - tm * p.tiles_n;
 }
 
+// What follows the k loop.  Split k: park the partial tile, count the arrival, and let the
+// last arrival add the partials in split order.  Epilogue: sign, optional accumulate, masked
+// at the remainder.
+template <class T>
+__device__ __forceinline__ void finish_tile(const KArgs& p, f32x16 (&acc)[T::MI][T::NI], float* __restrict__ C,
+                                            int tile, int split, int tiles, int m0, int n0, int wm0, int wn0,
+                                            bool interior) {
+    constexpr int BM = T::BM, BN = T::BN, NT = T::NT, MI = T::MI, NI = T::NI;
+    const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, lh = lane >> 5;
+    if (p.split_k > 1) {
+        __shared__ int arrived;
+        const long long slot = (long long)blockIdx.y * tiles + tile;
+        float* ws = p.ws + slot * p.split_k * (BM * BN);
+        float* mine = ws + (long long)split * (BM * BN);
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mine[((i * NI + j) * 16 + r) * NT + tid] = acc[i][j][r];
+        __threadfence();   // partial visible device-wide before the arrival is counted
+        __syncthreads();
+        if (tid == 0) arrived = atomicAdd(p.counters + slot, 1);
+        __syncthreads();
+        if (arrived != p.split_k - 1) return;
+        __threadfence();   // the other partials are visible after their arrivals were seen
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int e = ((i * NI + j) * 16 + r) * NT + tid;
+                    float v = ws[e];
+                    for (int sp = 1; sp < p.split_k; ++sp) v += ws[(long long)sp * (BM * BN) + e];
+                    acc[i][j][r] = v;
+                }
+        if (tid == 0) p.counters[slot] = 0;   // ready for the next launch on this workspace
+    }
+
+    const bool neg = p.flags & FLAG_NEGATE, accum = p.flags & FLAG_ACCUMULATE;
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            const int col = n0 + wn0 + j * 32 + li;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = m0 + wm0 + i * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+                if (interior || (row < p.M && col < p.N)) {
+                    float* c = C + (long long)row * p.ldc + col;
+                    float v = acc[i][j][r];
+                    if (neg) v = -v;
+                    if (accum) v += *c;
+                    *c = v;
+                }
+            }
+        }
+}
+
 template <class T, int AMODE, int VEC, bool EDGE>
 __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_kernel(const KArgs p) {
     constexpr int BM = T::BM, BN = T::BN, BK = T::BK, NT = T::NT, MI = T::MI, NI = T::NI;
@@ -437,76 +497,306 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_kernel(const KArgs p)
         __syncthreads();
     }
 
-    // ---- split k: park the partial tile, count the arrival, and let the last arrival reduce
-    if (p.split_k > 1) {
-        __shared__ int arrived;
-        const long long slot = (long long)blockIdx.y * tiles + tile;
-        float* ws = p.ws + slot * p.split_k * (BM * BN);
-        float* mine = ws + (long long)split * (BM * BN);
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
-#pragma unroll
-            for (int j = 0; j < NI; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) mine[((i * NI + j) * 16 + r) * NT + tid] = acc[i][j][r];
-        __threadfence();   // partial visible device-wide before the arrival is counted
-        __syncthreads();
-        if (tid == 0) arrived = atomicAdd(p.counters + slot, 1);
-        __syncthreads();
-        if (arrived != p.split_k - 1) return;
-        __threadfence();   // the other partials are visible after their arrivals were seen
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
-#pragma unroll
-            for (int j = 0; j < NI; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int e = ((i * NI + j) * 16 + r) * NT + tid;
-                    float v = ws[e];
-                    for (int sp = 1; sp < p.split_k; ++sp) v += ws[(long long)sp * (BM * BN) + e];
-                    acc[i][j][r] = v;
-                }
-        if (tid == 0) p.counters[slot] = 0;   // ready for the next launch on this workspace
+    finish_tile<T>(p, acc, C, tile, split, tiles, m0, n0, wm0, wn0, interior);
+}
+
+// ---------------------------------------------------------------------------------------
+// SCHED 4 / 5: operand tiles travel from global memory straight into LDS (no register
+// staging, no LDS store instructions) through a ring of 3 / 4 stages, so the loads of two /
+// three k steps are in flight while one step is multiplied: the form for launches whose few
+// resident waves cannot hide the memory latency by themselves.
+//
+// One direct load moves 64 lanes x 16 bytes to 1 KiB of consecutive LDS, so a tile is kept
+// as a plain array of 16-byte chunks in thread order, without row padding.  For k-contiguous
+// rows the chunk stored at position c of row r is chunk c ^ swz(r) of that row, which spreads
+// the 16-byte fragment reads of 16 consecutive rows over all banks; the swizzle is applied
+// to the global address on the way in and to the LDS address on the way out.
+//
+// Every lane of every direct load is active: a chunk that lies wholly outside its operand
+// (remainder rows, k beyond K, a convolution tap in the zero padding) is fetched from a
+// 16-byte block of zeros instead, so padding is still never read and the number of loads in
+// flight is known exactly (the wait before a step counts them).  A chunk that straddles the
+// end of a row cannot be fetched whole; the steps or tiles where that happens go through
+// registers with masked accesses, as in the other forms.
+__device__ __attribute__((aligned(16))) float g_zero_chunk[4] = {0.f, 0.f, 0.f, 0.f};
+
+__device__ __forceinline__ void load_to_lds16(const void* g, unsigned lds_byte_base) {
+    // M0 carries the wave's LDS destination; lane l lands at base + 16 * l
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_byte_base)
+                 : "memory", "m0");
+}
+template <int N>
+__device__ __forceinline__ void wait_loads_outstanding() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <class T, int AMODE>
+struct LdsDirect {
+    static constexpr int STAGES = T::SCHED == 5 ? 4 : 3;
+    static constexpr int A_FLOATS = T::BM * T::BK, B_FLOATS = T::BK * T::BN, STAGE = A_FLOATS + B_FLOATS;
+    static constexpr int BYTES = STAGES * STAGE * (int)sizeof(float);
+};
+
+template <class T, int AMODE, bool EDGE>
+__global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const KArgs p) {
+    constexpr int BM = T::BM, BN = T::BN, BK = T::BK, NT = T::NT, MI = T::MI, NI = T::NI;
+    using L = LdsDirect<T, AMODE>;
+    constexpr int STAGES = L::STAGES, D = STAGES - 1;
+    constexpr bool A_KMAJ = AMODE != A_COL;
+    constexpr int A_CPR = A_KMAJ ? BK / 4 : BM / 4;   // 16-byte chunks per stored row of A
+    constexpr int A_ROWS = A_KMAJ ? BM : BK;
+    constexpr int A_RPP = NT / A_CPR, PA = A_ROWS / A_RPP;
+    constexpr int B_CPR = BN / 4, B_RPP = NT / B_CPR, PB = BK / B_RPP;
+    constexpr int LPT = PA + PB;                       // direct loads per thread and step
+    static_assert(NT % A_CPR == 0 && A_ROWS % A_RPP == 0 && PA >= 1, "A staging shape");
+    static_assert(NT % B_CPR == 0 && BK % B_RPP == 0 && PB >= 1, "B staging shape");
+    static_assert((D - 1) * LPT <= 63, "outstanding-load counter range");
+    constexpr int SW_MOD = A_CPR < 16 ? A_CPR : 16, SW_DIV = 16 / SW_MOD;
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm0 = (wave / T::WAVES_N) * T::WM, wn0 = (wave % T::WAVES_N) * T::WN;
+    const int li = lane & 31, lh = lane >> 5;
+
+    const int tiles = p.tiles_m * p.tiles_n;
+    const int split = blockIdx.x / tiles, tile = blockIdx.x - split * tiles;
+    int tm, tn;
+    tile_coords(p, tile, tm, tn);
+    const int m0 = tm * BM, n0 = tn * BN;
+    const float* __restrict__ A = (const float*)p.A + (long long)blockIdx.y * p.stride_a;
+    const float* __restrict__ B = (const float*)p.B + (long long)blockIdx.y * p.stride_b;
+    float* __restrict__ C = p.C + (long long)blockIdx.y * p.stride_c;
+
+    const bool interior = !EDGE || (m0 + BM <= p.m_main && n0 + BN <= p.n_main);
+    const int nk_all = (p.K + BK - 1) / BK;
+    const int kb = (int)((long long)nk_all * split / p.split_k);
+    const int nk = (int)((long long)nk_all * (split + 1) / p.split_k) - kb;
+
+    // Leading steps of this workgroup whose chunks are all whole (inside or outside).
+    int n_direct = nk;
+    if constexpr (EDGE) {
+        bool whole_tile = !((p.N & 3) && n0 + BN > p.N);                       // rows of B are cut mid-chunk
+        if (AMODE == A_COL && (p.M & 3) && m0 + BM > p.M) whole_tile = false;  // so are rows of A^T
+        if (!whole_tile) n_direct = 0;
+        else if (AMODE == A_ROW && (p.K & 3)) n_direct = max(0, min(nk, p.k_full - kb));
     }
 
-    // ---- epilogue: sign, optional accumulate, masked at the remainder
-    const bool neg = p.flags & FLAG_NEGATE, accum = p.flags & FLAG_ACCUMULATE;
+    // LDS byte address of this wave's 1 KiB slice of pass 0 of stage 0 (wave-uniform)
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) float*)smem +
+                          (unsigned)__builtin_amdgcn_readfirstlane(tid & ~63) * 16u;
+    const int a_r = tid / A_CPR, a_cp = tid % A_CPR;
+    const int b_r = tid / B_CPR, b_cp = tid % B_CPR;
+    auto swz = [](int row) -> int { return A_KMAJ ? (row / SW_DIV) % SW_MOD : 0; };
+
+    // per-thread source of each of its chunks at k0 = 0
+    const float* a_src[PA];
+    int a_k[PA];          // k offset of the chunk inside a step (k-contiguous A)
+    bool a_in[PA];        // the chunk's row (A_ROW: m, A_COL: m range) lies inside the operand
+    int cv_base[PA], cv_hi0[PA], cv_wi0[PA];
+#pragma unroll
+    for (int q = 0; q < PA; ++q) {
+        const int row = a_r + q * A_RPP;
+        if constexpr (AMODE == A_ROW) {
+            a_k[q] = (a_cp ^ swz(row)) * 4;
+            a_in[q] = !EDGE || m0 + row < p.M;
+            a_src[q] = A + (long long)(m0 + row) * p.lda + a_k[q];
+        } else if constexpr (AMODE == A_COL) {
+            a_k[q] = row;   // the stored row is the k index
+            a_in[q] = !EDGE || m0 + a_cp * 4 < p.M;
+            a_src[q] = A + (long long)row * p.lda + m0 + a_cp * 4;
+        } else {
+            a_k[q] = (a_cp ^ swz(row)) * 4;
+            const int m = m0 + row;
+            a_in[q] = !EDGE || m < p.M;
+            a_src[q] = A;
+            const int mm = a_in[q] ? m : 0;
+            const int wo = mm % p.Wo, t = mm / p.Wo;
+            const int ho = t % p.Ho, n = t / p.Ho;
+            cv_base[q] = n * p.H;
+            cv_hi0[q] = ho * p.sh - p.ph;
+            cv_wi0[q] = wo * p.sw - p.pw;
+        }
+    }
+    const float* b_src[PB];
+    const bool b_in = !EDGE || n0 + b_cp * 4 < p.N;
+#pragma unroll
+    for (int q = 0; q < PB; ++q) b_src[q] = B + (long long)(b_r + q * B_RPP) * p.ldb + n0 + b_cp * 4;
+
+    // ---- one tile into one stage, direct
+    auto issue_direct = [&](int kt, int stage) {
+        const int k0 = kt * BK;
+        const unsigned as = lds0 + (unsigned)(stage * L::STAGE) * 4u;
+        const unsigned bs = as + (unsigned)L::A_FLOATS * 4u;
+#pragma unroll
+        for (int q = 0; q < PA; ++q) {
+            const float* src;
+            if constexpr (AMODE == A_ROW) {
+                const bool in = a_in[q] && (!EDGE || k0 + a_k[q] < p.K);
+                src = in ? a_src[q] + k0 : g_zero_chunk;
+            } else if constexpr (AMODE == A_COL) {
+                const bool in = a_in[q] && (!EDGE || k0 + a_k[q] < p.K);
+                src = in ? a_src[q] + (long long)k0 * p.lda : g_zero_chunk;
+            } else {
+                const int k = k0 + a_k[q];
+                const int tap = k / p.Cin, ci = k - tap * p.Cin;
+                const int kh = tap / p.KW, kw = tap - kh * p.KW;
+                const int hi = cv_hi0[q] + kh, wi = cv_wi0[q] + kw;
+                const bool in = a_in[q] && k < p.K && hi >= 0 && hi < p.H && wi >= 0 && wi < p.W;
+                src = in ? A + ((long long)(cv_base[q] + hi) * p.W + wi) * p.Cin + ci : g_zero_chunk;
+            }
+            load_to_lds16(src, as + (unsigned)(q * NT) * 16u);
+        }
+#pragma unroll
+        for (int q = 0; q < PB; ++q) {
+            const bool in = b_in && (!EDGE || k0 + b_r + q * B_RPP < p.K);
+            const float* src = in ? b_src[q] + (long long)k0 * p.ldb : g_zero_chunk;
+            load_to_lds16(src, bs + (unsigned)(q * NT) * 16u);
+        }
+    };
+
+    // ---- the same tile through registers with element masks (chunks cut by the end of a row)
+    auto issue_masked = [&](int kt, int stage) {
+        const int k0 = kt * BK;
+        float* As = smem + stage * L::STAGE;
+        float* Bs = As + L::A_FLOATS;
+#pragma unroll
+        for (int q = 0; q < PA; ++q) {
+            const int row = a_r + q * A_RPP;
+            f32x4 v = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if constexpr (AMODE == A_ROW) {
+                    const int m = m0 + row, k = k0 + a_k[q] + e;
+                    if (m < p.M && k < p.K) v[e] = A[(long long)m * p.lda + k];
+                } else if constexpr (AMODE == A_COL) {
+                    const int k = k0 + row, m = m0 + a_cp * 4 + e;
+                    if (k < p.K && m < p.M) v[e] = A[(long long)k * p.lda + m];
+                } else {
+                    const int k = k0 + a_k[q] + e;
+                    const int tap = k / p.Cin, ci = k - tap * p.Cin;
+                    const int kh = tap / p.KW, kw = tap - kh * p.KW;
+                    const int hi = cv_hi0[q] + kh, wi = cv_wi0[q] + kw;
+                    if (a_in[q] && k < p.K && hi >= 0 && hi < p.H && wi >= 0 && wi < p.W)
+                        v[e] = A[((long long)(cv_base[q] + hi) * p.W + wi) * p.Cin + ci];
+                }
+            }
+            *(f32x4*)(As + (q * NT + tid) * 4) = v;
+        }
+#pragma unroll
+        for (int q = 0; q < PB; ++q) {
+            const int k = k0 + b_r + q * B_RPP;
+            f32x4 v = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int n = n0 + b_cp * 4 + e;
+                if (k < p.K && n < p.N) v[e] = B[(long long)k * p.ldb + n];
+            }
+            *(f32x4*)(Bs + (q * NT + tid) * 4) = v;
+        }
+    };
+    auto issue = [&](int kt_local, int stage) {
+        if (!EDGE || kt_local < n_direct) issue_direct(kb + kt_local, stage);
+        else issue_masked(kb + kt_local, stage);
+    };
+
+    f32x16 acc[MI][NI];
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int j = 0; j < NI; ++j) {
-            const int col = n0 + wn0 + j * 32 + li;
+        for (int j = 0; j < NI; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = m0 + wm0 + i * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
-                if (interior || (row < p.M && col < p.N)) {
-                    float* c = C + (long long)row * p.ldc + col;
-                    float v = acc[i][j][r];
-                    if (neg) v = -v;
-                    if (accum) v += *c;
-                    *c = v;
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // fragment addressing: lane (li, lh) reads row wm0 + 32 i + li, chunk 2 g + lh of k group g
+    int a_row_off[MI];   // float offset of the lane's row (k-contiguous A)
+#pragma unroll
+    for (int i = 0; i < MI; ++i) a_row_off[i] = (wm0 + i * 32 + li) * BK;
+    const int a_x = lh ^ swz(li);   // wm0 + 32 i is a multiple of 32, so the swizzle depends on li alone
+
+    // operands are fetched one k pair (= one MFMA per block) ahead of their use
+    auto compute = [&](int stage) {
+        const float* As = smem + stage * L::STAGE;
+        const float* Bs = As + L::A_FLOATS;
+        constexpr int G = BK / 8, S = 4 * G;
+        f32x4 ag[2][MI];
+        float av[2][MI];
+        float bv[2][NI];
+        auto fetch = [&](int s1) {
+            const int g1 = s1 >> 2, t1 = s1 & 3;
+            const int krow = g1 * 8 + 4 * lh + t1;
+            if constexpr (A_KMAJ) {
+                if (t1 == 0) {
+#pragma unroll
+                    for (int i = 0; i < MI; ++i)
+                        ag[g1 & 1][i] = *(const f32x4*)(As + a_row_off[i] + (((2 * g1) ^ a_x) << 2));
                 }
+            } else {
+#pragma unroll
+                for (int i = 0; i < MI; ++i) av[s1 & 1][i] = As[krow * BM + wm0 + i * 32 + li];
             }
+#pragma unroll
+            for (int j = 0; j < NI; ++j) bv[s1 & 1][j] = Bs[krow * BN + wn0 + j * 32 + li];
+        };
+        fetch(0);
+#pragma unroll
+        for (int s = 0; s < S; ++s) {
+            if (s + 1 < S) fetch(s + 1);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NI; ++j) {
+                    const float a = A_KMAJ ? ag[(s >> 2) & 1][i][s & 3] : av[s & 1][i];
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, bv[s & 1][j], acc[i][j], 0, 0, 0);
+                }
+            __builtin_amdgcn_sched_barrier(0);
         }
+    };
+
+    // ---- ring: step kt is multiplied from stage kt % STAGES while steps kt+1 .. kt+D-1 are in
+    // flight and step kt+D is issued into the stage that step kt-1 has just left
+    for (int t = 0; t < D; ++t)
+        if (t < nk) issue(t, t);
+    int cur = 0;
+    for (int kt = 0; kt < nk; ++kt) {
+        // own loads of step kt have landed once no more than the loads of the D-1 later steps
+        // are outstanding; the barrier then covers the other waves' loads and frees stage cur-1
+        if (kt + D <= n_direct) wait_loads_outstanding<(D - 1) * LPT>();
+        else wait_loads_outstanding<0>();
+        __syncthreads();
+        if (kt + D < nk) issue(kt + D, cur == 0 ? STAGES - 1 : cur - 1);
+        compute(cur);
+        cur = cur + 1 == STAGES ? 0 : cur + 1;
+    }
+
+    finish_tile<T>(p, acc, C, tile, split, tiles, m0, n0, wm0, wn0, interior);
 }
 
 template <class T, int AMODE>
 hipError_t launch_mode(int variant, const KArgs& a, int batch, hipStream_t s) {
-    using L = Lds<T, AMODE>;
     const dim3 grid(a.tiles_m * a.tiles_n * a.split_k, batch, 1), block(T::NT, 1, 1);
     void (*fn)(const KArgs) = nullptr;
-    switch (variant) {
-        case 0: fn = gemm_f32_kernel<T, AMODE, 4, false>; break;
-        case 1: fn = gemm_f32_kernel<T, AMODE, 4, true>; break;
-        default: fn = gemm_f32_kernel<T, AMODE, 1, true>; break;
+    int bytes;
+    if constexpr (T::SCHED >= 4) {
+        // the direct-to-LDS forms move whole 16-byte chunks only
+        if (variant == 2) return hipErrorInvalidValue;
+        bytes = LdsDirect<T, AMODE>::BYTES;
+        fn = variant == 0 ? gemm_f32_direct_kernel<T, AMODE, false> : gemm_f32_direct_kernel<T, AMODE, true>;
+    } else {
+        bytes = Lds<T, AMODE>::BYTES;
+        switch (variant) {
+            case 0: fn = gemm_f32_kernel<T, AMODE, 4, false>; break;
+            case 1: fn = gemm_f32_kernel<T, AMODE, 4, true>; break;
+            default: fn = gemm_f32_kernel<T, AMODE, 1, true>; break;
+        }
     }
     static bool attr_done[3] = {false, false, false};
-    if (L::BYTES > 48 * 1024 && !attr_done[variant]) {
-        hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, L::BYTES);
+    if (bytes > 48 * 1024 && !attr_done[variant]) {
+        hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
         if (e != hipSuccess) return e;
         attr_done[variant] = true;
     }
-    hipLaunchKernelGGL(fn, grid, block, L::BYTES, s, a);
+    hipLaunchKernelGGL(fn, grid, block, bytes, s, a);
     return hipGetLastError();
 }
 
@@ -541,7 +831,16 @@ hipError_t launch_mode(int variant, const KArgs& a, int batch, hipStream_t s) {
     X(64, 64, 64, 32, 32, 2, 2)    \
     X(64, 64, 32, 32, 32, 2, 3)    \
     X(128, 64, 32, 64, 32, 2, 3)   \
-    X(64, 64, 128, 32, 32, 1, 2)
+    X(64, 64, 128, 32, 32, 1, 2)   \
+    X(64, 64, 32, 32, 32, 2, 4)    \
+    X(64, 64, 64, 32, 32, 2, 4)    \
+    X(64, 64, 64, 32, 32, 1, 5)    \
+    X(128, 64, 32, 64, 32, 2, 4)   \
+    X(128, 128, 16, 64, 64, 2, 4)  \
+    X(128, 128, 32, 64, 64, 2, 4)  \
+    X(256, 128, 16, 64, 64, 2, 4)  \
+    X(256, 128, 16, 64, 64, 2, 5)  \
+    X(256, 256, 16, 128, 64, 2, 4)
 
 // Each address mode is compiled in its own translation unit.
 #define TSG_F32_DEFINE_MODE(FN, AMODE)                                                              \

@@ -17,7 +17,9 @@ hipError_t launch_any(int tile, int amode, int variant, const KArgs& a, int batc
 }
 #define TSG_F32_ENTRY(bm, bn, bk, wm, wn, mw, sc)                                                     \
     KernelEntry{bm, bn, bk, wm, wn, sc, Tile<bm, bn, bk, wm, wn, mw, sc>::NT, 4,                       \
-                Lds<Tile<bm, bn, bk, wm, wn, mw, sc>, A_ROW>::BYTES, &launch_any},
+                (sc >= 4 ? LdsDirect<Tile<bm, bn, bk, wm, wn, mw, sc>, A_ROW>::BYTES                   \
+                         : Lds<Tile<bm, bn, bk, wm, wn, mw, sc>, A_ROW>::BYTES),                          \
+                &launch_any},
 const KernelEntry kTable[] = {TSG_F32_TILES(TSG_F32_ENTRY)};
 }  // namespace
 
