@@ -89,7 +89,7 @@ def main() -> int:
     ap.add_argument("--no-tune", action="store_true", help="use the shape heuristic instead of the tuner")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--cpu-rows", type=int, default=4096, help="rows of the product the oracle is timed on")
-    ap.add_argument("--pin", default="", help="bm,bn,bk,wm,wn,vec,raster,sched: pin this tile config instead of tuning")
+    ap.add_argument("--pin", default="", help="bm,bn,bk,wm,wn,vec,raster,sched[,split_k]: pin this tile config instead of tuning")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="also run one plain device copy of this many MiB (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -122,6 +122,9 @@ def main() -> int:
         return torch.from_numpy(x.view(np.int16) if x.dtype == np.uint16 else x).to(dev)
 
     dA, dB = up(a), up(b)
+    # device memory for the split of the k loop (used by shapes whose tiles cannot fill the chip)
+    workspace = torch.empty(64 << 20, dtype=torch.uint8, device=dev)
+    tsg.workspace_set(workspace)
     if c["op"] == "conv2d_nhwc":
         Ho = (c["H"] + 2 * c["pad"] - c["KH"]) // c["stride"] + 1
         dC = torch.zeros((c["N"], Ho, Ho, c["Cout"]), dtype=torch.float32, device=dev)
@@ -144,8 +147,8 @@ def main() -> int:
             tsg.gemm_batched(dt, False, nb, M, N, K, dA, K, M * K, dB, N, K * N, dC, N, M * N, flags)
 
         def tune():
-            # the tuner times one product of the batch; the pinned config then serves all of them
-            return tsg.autotune_gemm(dt, False, M, N, K, dA, K, dB, N, dC, N, flags, iters=5)
+            return tsg.autotune_gemm_batched(dt, False, nb, M, N, K, dA, K, M * K, dB, N, K * N, dC, N, M * N,
+                                             flags, iters=5)
     else:
         M, N, K = c["M"], c["N"], c["K"]
         trans = c["op"] == "gemm_transA"
@@ -173,7 +176,8 @@ def main() -> int:
     tuner_log = None
     if args.pin:
         v = [int(t) for t in args.pin.split(",")]
-        tsg.tile_config_set(op, dt, tsg.TileConfig(bm=v[0], bn=v[1], bk=v[2], wm=v[3], wn=v[4], vec=v[5], raster=v[6], sched=v[7]))
+        tsg.tile_config_set(op, dt, tsg.TileConfig(bm=v[0], bn=v[1], bk=v[2], wm=v[3], wn=v[4], vec=v[5], raster=v[6], sched=v[7],
+                                                   split_k=(v[8] if len(v) > 8 else 1)))
         args.no_tune = True
     if not args.no_tune:
         best, best_ms, recs = tune()

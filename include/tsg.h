@@ -221,6 +221,16 @@ tsg_status tsg_autotune_gemm(tsg_dtype dtype, int32_t trans_a, int64_t M, int64_
                              tsg_tile_config *best, float *best_ms,
                              tsg_tune_record *log, int32_t log_cap, int32_t *n_log);
 
+/* The same search on a batched call (the config that is fastest for the whole batch). */
+tsg_status tsg_autotune_gemm_batched(tsg_dtype dtype, int32_t trans_a, int64_t batch,
+                                     int64_t M, int64_t N, int64_t K,
+                                     const void *A, int64_t lda, int64_t stride_a,
+                                     const void *B, int64_t ldb, int64_t stride_b,
+                                     float *C, int64_t ldc, int64_t stride_c,
+                                     uint32_t flags, void *stream, int32_t iters,
+                                     tsg_tile_config *best, float *best_ms,
+                                     tsg_tune_record *log, int32_t log_cap, int32_t *n_log);
+
 tsg_status tsg_autotune_conv2d_nhwc(tsg_dtype dtype, int64_t N, int64_t H, int64_t W, int64_t Cin,
                                     int64_t Cout, int64_t KH, int64_t KW,
                                     int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,

@@ -74,6 +74,9 @@ def _load():
         "tsg_autotune_gemm": [i32, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, u32, vp, i32,
                               cfgp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(TuneRecord), i32,
                               ctypes.POINTER(i32)],
+        "tsg_autotune_gemm_batched": [i32, i32, i64, i64, i64, i64, vp, i64, i64, vp, i64, i64, vp, i64, i64, u32,
+                                      vp, i32, cfgp, ctypes.POINTER(ctypes.c_float),
+                                      ctypes.POINTER(TuneRecord), i32, ctypes.POINTER(i32)],
         "tsg_autotune_conv2d_nhwc": [i32] + [i64] * 11 + [vp, vp, vp, u32, vp, i32,
                                                           cfgp, ctypes.POINTER(ctypes.c_float),
                                                           ctypes.POINTER(TuneRecord), i32, ctypes.POINTER(i32)],
@@ -99,7 +102,7 @@ EXPORTS = ("tsg_gemm", "tsg_gemm_transA", "tsg_gemm_batched", "tsg_conv2d_nhwc",
            "tsg_tile_config_count", "tsg_tile_config_enum", "tsg_tile_config_check",
            "tsg_tile_config_set", "tsg_tile_config_get", "tsg_last_launch", "tsg_workspace_set",
            "tsg_workspace_bytes", "tsg_conv2d_index_map",
-           "tsg_gemm_index_map", "tsg_autotune_gemm", "tsg_autotune_conv2d_nhwc",
+           "tsg_gemm_index_map", "tsg_autotune_gemm", "tsg_autotune_gemm_batched", "tsg_autotune_conv2d_nhwc",
            "tsg_status_string", "tsg_version")
 
 
@@ -240,6 +243,16 @@ def autotune_gemm(dtype, trans_a, M, N, K, A, lda, B, ldb, C, ldc, flags=0, stre
     _check(_lib.tsg_autotune_gemm(dtype, int(bool(trans_a)), M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C),
                                   ldc, flags, _stream(stream), iters, ctypes.byref(best), ctypes.byref(ms),
                                   log, log_cap, ctypes.byref(n)), "tsg_autotune_gemm")
+    return best, float(ms.value), [log[i] for i in range(n.value)]
+
+
+def autotune_gemm_batched(dtype, trans_a, batch, M, N, K, A, lda, stride_a, B, ldb, stride_b, C, ldc, stride_c,
+                          flags=0, stream=None, iters=5, log_cap=512):
+    best, ms, log, n = _tune_out(log_cap)
+    _check(_lib.tsg_autotune_gemm_batched(dtype, int(bool(trans_a)), batch, M, N, K, _ptr(A), lda, stride_a,
+                                          _ptr(B), ldb, stride_b, _ptr(C), ldc, stride_c, flags, _stream(stream),
+                                          iters, ctypes.byref(best), ctypes.byref(ms), log, log_cap,
+                                          ctypes.byref(n)), "tsg_autotune_gemm_batched")
     return best, float(ms.value), [log[i] for i in range(n.value)]
 
 

@@ -548,20 +548,33 @@ tsg_status tsg_gemm_index_map(int32_t trans_a, int64_t M, int64_t K, int64_t lda
     return TSG_OK;
 }
 
+tsg_status tsg_autotune_gemm_batched(tsg_dtype dtype, int32_t trans_a, int64_t batch, int64_t M, int64_t N,
+                                     int64_t K, const void* A, int64_t lda, int64_t stride_a, const void* B,
+                                     int64_t ldb, int64_t stride_b, float* C, int64_t ldc, int64_t stride_c,
+                                     uint32_t flags, void* stream, int32_t iters, tsg_tile_config* best,
+                                     float* best_ms, tsg_tune_record* log, int32_t log_cap, int32_t* n_log) {
+    const tsg_status v = check_gemm(dtype, batch, M, N, K, A, lda, B, ldb, C, ldc, trans_a != 0, flags);
+    if (v != TSG_OK) return v;
+    if (stride_a < 0 || stride_b < 0 || stride_c < 0) return TSG_E_INVALID;
+    if (batch > 1 && stride_c < (M - 1) * ldc + N) return TSG_E_INVALID;
+    Problem p;
+    p.op = trans_a ? TSG_OP_GEMM_TRANSA : TSG_OP_GEMM;
+    p.dtype = dtype;
+    p.batch = batch;
+    p.M = M; p.N = N; p.K = K;
+    p.A = A; p.B = B; p.C = C;
+    p.lda = lda; p.ldb = ldb; p.ldc = ldc;
+    p.stride_a = stride_a; p.stride_b = stride_b; p.stride_c = stride_c;
+    p.flags = flags;
+    return autotune(p, (hipStream_t)stream, iters, best, best_ms, log, log_cap, n_log);
+}
+
 tsg_status tsg_autotune_gemm(tsg_dtype dtype, int32_t trans_a, int64_t M, int64_t N, int64_t K, const void* A,
                              int64_t lda, const void* B, int64_t ldb, float* C, int64_t ldc, uint32_t flags,
                              void* stream, int32_t iters, tsg_tile_config* best, float* best_ms,
                              tsg_tune_record* log, int32_t log_cap, int32_t* n_log) {
-    const tsg_status v = check_gemm(dtype, 1, M, N, K, A, lda, B, ldb, C, ldc, trans_a != 0, flags);
-    if (v != TSG_OK) return v;
-    Problem p;
-    p.op = trans_a ? TSG_OP_GEMM_TRANSA : TSG_OP_GEMM;
-    p.dtype = dtype;
-    p.M = M; p.N = N; p.K = K;
-    p.A = A; p.B = B; p.C = C;
-    p.lda = lda; p.ldb = ldb; p.ldc = ldc;
-    p.flags = flags;
-    return autotune(p, (hipStream_t)stream, iters, best, best_ms, log, log_cap, n_log);
+    return tsg_autotune_gemm_batched(dtype, trans_a, 1, M, N, K, A, lda, 0, B, ldb, 0, C, ldc, 0, flags, stream,
+                                     iters, best, best_ms, log, log_cap, n_log);
 }
 
 tsg_status tsg_autotune_conv2d_nhwc(tsg_dtype dtype, int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,

@@ -106,30 +106,44 @@ __device__ __forceinline__ void finish_tile(const KArgs& p, f32x16 (&acc)[T::MI]
         __shared__ int arrived;
         const long long slot = (long long)blockIdx.y * tiles + tile;
         float* ws = p.ws + slot * p.split_k * (BM * BN);
+        // A partial tile is kept in register order.  Partials cross between L2 domains, so
+        // they are written and read with device-scope accesses that go through to memory; once
+        // a wave's stores are acknowledged (the wait) and all waves are at the barrier, the
+        // arrival is counted, and whoever sees the last count finds every partial in memory.
+        // This takes no cache-wide write-back or invalidate.
         float* mine = ws + (long long)split * (BM * BN);
 #pragma unroll
         for (int i = 0; i < MI; ++i)
 #pragma unroll
             for (int j = 0; j < NI; ++j)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) mine[((i * NI + j) * 16 + r) * NT + tid] = acc[i][j][r];
-        __threadfence();   // partial visible device-wide before the arrival is counted
+                for (int r = 0; r < 16; ++r)
+                    __hip_atomic_store(mine + ((i * NI + j) * 16 + r) * NT + tid, acc[i][j][r], __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        if (tid == 0) arrived = atomicAdd(p.counters + slot, 1);
+        if (tid == 0) arrived = __hip_atomic_fetch_add(p.counters + slot, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __syncthreads();
         if (arrived != p.split_k - 1) return;
-        __threadfence();   // the other partials are visible after their arrivals were seen
+        // acc = ((P0 + P1) + P2) + ...: one partial tile at a time, all of its loads in flight together
+        for (int sp = 0; sp < p.split_k; ++sp) {
+            const float* part = ws + (long long)sp * (BM * BN);
+            float t[MI][NI][16];
 #pragma unroll
-        for (int i = 0; i < MI; ++i)
+            for (int i = 0; i < MI; ++i)
 #pragma unroll
-            for (int j = 0; j < NI; ++j)
+                for (int j = 0; j < NI; ++j)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int e = ((i * NI + j) * 16 + r) * NT + tid;
-                    float v = ws[e];
-                    for (int sp = 1; sp < p.split_k; ++sp) v += ws[(long long)sp * (BM * BN) + e];
-                    acc[i][j][r] = v;
-                }
+                    for (int r = 0; r < 16; ++r)
+                        t[i][j][r] = __hip_atomic_load(part + ((i * NI + j) * 16 + r) * NT + tid, __ATOMIC_RELAXED,
+                                                       __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NI; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[i][j][r] = sp == 0 ? t[i][j][r] : acc[i][j][r] + t[i][j][r];
+        }
         if (tid == 0) p.counters[slot] = 0;   // ready for the next launch on this workspace
     }
 
