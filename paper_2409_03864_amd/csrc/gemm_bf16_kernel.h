@@ -119,6 +119,17 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_kernel(const KArgs p
         }
     }
 
+    // convolution: (kh, kw, ci) of the first k of the next step to load, advanced step by step
+    // (steps are loaded in order); with Cin a multiple of BK a step lies inside one tap
+    int cs_kh = 0, cs_kw = 0, cs_ci = 0;
+    const bool one_tap = AMODE == A_CONV && p.Cin % BK == 0;
+    if constexpr (AMODE == A_CONV) {
+        const int k = kb * BK, tap = k / p.Cin;
+        cs_ci = k - tap * p.Cin;
+        cs_kh = tap / p.KW;
+        cs_kw = tap - cs_kh * p.KW;
+    }
+
     u16x8 ra[PA], rb[PB];
 
     auto a_elem = [&](int q, int row_or_k, int e) -> u16 {
@@ -167,8 +178,13 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_kernel(const KArgs p
                 if constexpr (VEC == 8) {
                     u16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
                     if (fast || k < p.K) {
-                        const int tap = k / p.Cin, ci = k - tap * p.Cin;
-                        const int kh = tap / p.KW, kw = tap - kh * p.KW;
+                        int kh = cs_kh, kw = cs_kw, ci = cs_ci + a_c;
+                        if (!one_tap) {
+                            const int tap = k / p.Cin;
+                            ci = k - tap * p.Cin;
+                            kh = tap / p.KW;
+                            kw = tap - kh * p.KW;
+                        }
                         const int hi = cv_hi0[q] + kh, wi = cv_wi0[q] + kw;
                         if (hi >= 0 && hi < p.H && wi >= 0 && wi < p.W)
                             v = *(const u16x8_u*)(A + ((long long)(cv_base[q] + hi) * p.W + wi) * p.Cin + ci);
@@ -178,6 +194,13 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_kernel(const KArgs p
 #pragma unroll
                     for (int e = 0; e < 8; ++e) ra[q][e] = a_elem(q, r, k + e);
                 }
+            }
+        }
+        if constexpr (AMODE == A_CONV) {
+            cs_ci += BK;
+            while (cs_ci >= p.Cin) {
+                cs_ci -= p.Cin;
+                if (++cs_kw == p.KW) { cs_kw = 0; ++cs_kh; }
             }
         }
 #pragma unroll

@@ -224,6 +224,18 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_kernel(const KArgs p)
         }
     }
 
+    // convolution: (kh, kw, ci) of the first k of the next step to load.  Steps are loaded in
+    // order, so the triple is advanced instead of being divided out of k every time; when Cin
+    // is a multiple of BK a whole step lies inside one tap and no chunk needs a division.
+    int cs_kh = 0, cs_kw = 0, cs_ci = 0;
+    const bool one_tap = AMODE == A_CONV && p.Cin % BK == 0;
+    if constexpr (AMODE == A_CONV) {
+        const int k = kb * BK, tap = k / p.Cin;
+        cs_ci = k - tap * p.Cin;
+        cs_kh = tap / p.KW;
+        cs_kw = tap - cs_kh * p.KW;
+    }
+
     f32x4 ra[PA], rb[PB];
 
     // One element of op(A) for the scalar path (row/col relative to the problem).
@@ -275,8 +287,13 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_kernel(const KArgs p)
                     // Cin % 4 == 0: the chunk lies inside one tap
                     f32x4 v = {0.f, 0.f, 0.f, 0.f};
                     if (fast || k < p.K) {
-                        const int tap = k / p.Cin, ci = k - tap * p.Cin;
-                        const int kh = tap / p.KW, kw = tap - kh * p.KW;
+                        int kh = cs_kh, kw = cs_kw, ci = cs_ci + a_c;
+                        if (!one_tap) {
+                            const int tap = k / p.Cin;
+                            ci = k - tap * p.Cin;
+                            kh = tap / p.KW;
+                            kw = tap - kh * p.KW;
+                        }
                         const int hi = cv_hi0[q] + kh, wi = cv_wi0[q] + kw;
                         if (hi >= 0 && hi < p.H && wi >= 0 && wi < p.W)
                             v = *(const f32x4_u*)(A + ((long long)(cv_base[q] + hi) * p.W + wi) * p.Cin + ci);
@@ -286,6 +303,13 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_kernel(const KArgs p)
 #pragma unroll
                     for (int e = 0; e < 4; ++e) ra[q][e] = a_elem(q, r, k + e);
                 }
+            }
+        }
+        if constexpr (AMODE == A_CONV) {
+            cs_ci += BK;
+            while (cs_ci >= p.Cin) {
+                cs_ci -= p.Cin;
+                if (++cs_kw == p.KW) { cs_kw = 0; ++cs_kh; }
             }
         }
         // ---------------- B (K x N, j contiguous)
@@ -631,6 +655,16 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
             cv_wi0[q] = wo * p.sw - p.pw;
         }
     }
+    // (kh, kw, ci) of the first k of the next step to issue, advanced step by step (see the
+    // register-staged kernel)
+    int cs_kh = 0, cs_kw = 0, cs_ci = 0;
+    const bool one_tap = AMODE == A_CONV && p.Cin % BK == 0;
+    if constexpr (AMODE == A_CONV) {
+        const int k = kb * BK, tap = k / p.Cin;
+        cs_ci = k - tap * p.Cin;
+        cs_kh = tap / p.KW;
+        cs_kw = tap - cs_kh * p.KW;
+    }
     const float* b_src[PB];
     const bool b_in = !EDGE || n0 + b_cp * 4 < p.N;
 #pragma unroll
@@ -652,8 +686,13 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
                 src = in ? a_src[q] + (long long)k0 * p.lda : g_zero_chunk;
             } else {
                 const int k = k0 + a_k[q];
-                const int tap = k / p.Cin, ci = k - tap * p.Cin;
-                const int kh = tap / p.KW, kw = tap - kh * p.KW;
+                int kh = cs_kh, kw = cs_kw, ci = cs_ci + a_k[q];
+                if (!one_tap) {
+                    const int tap = k / p.Cin;
+                    ci = k - tap * p.Cin;
+                    kh = tap / p.KW;
+                    kw = tap - kh * p.KW;
+                }
                 const int hi = cv_hi0[q] + kh, wi = cv_wi0[q] + kw;
                 const bool in = a_in[q] && k < p.K && hi >= 0 && hi < p.H && wi >= 0 && wi < p.W;
                 src = in ? A + ((long long)(cv_base[q] + hi) * p.W + wi) * p.Cin + ci : g_zero_chunk;
@@ -711,6 +750,13 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
     auto issue = [&](int kt_local, int stage) {
         if (!EDGE || kt_local < n_direct) issue_direct(kb + kt_local, stage);
         else issue_masked(kb + kt_local, stage);
+        if constexpr (AMODE == A_CONV) {
+            cs_ci += BK;
+            while (cs_ci >= p.Cin) {
+                cs_ci -= p.Cin;
+                if (++cs_kw == p.KW) { cs_kw = 0; ++cs_kh; }
+            }
+        }
     };
 
     f32x16 acc[MI][NI];
@@ -727,42 +773,40 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
     for (int i = 0; i < MI; ++i) a_row_off[i] = (wm0 + i * 32 + li) * BK;
     const int a_x = lh ^ swz(li);   // wm0 + 32 i is a multiple of 32, so the swizzle depends on li alone
 
-    // operands are fetched one k pair (= one MFMA per block) ahead of their use
+    // Operands are fetched a whole k group (8 values of k = 4 MFMAs per block) ahead of their
+    // use: with one wave per SIMD nothing else covers the LDS latency, and one MFMA does not.
     auto compute = [&](int stage) {
         const float* As = smem + stage * L::STAGE;
         const float* Bs = As + L::A_FLOATS;
-        constexpr int G = BK / 8, S = 4 * G;
-        f32x4 ag[2][MI];
-        float av[2][MI];
-        float bv[2][NI];
-        auto fetch = [&](int s1) {
-            const int g1 = s1 >> 2, t1 = s1 & 3;
-            const int krow = g1 * 8 + 4 * lh + t1;
-            if constexpr (A_KMAJ) {
-                if (t1 == 0) {
+        constexpr int G = BK / 8;
+        f32x4 af[2][MI], bf[2][NI];
+        auto fetch = [&](int g) {
 #pragma unroll
-                    for (int i = 0; i < MI; ++i)
-                        ag[g1 & 1][i] = *(const f32x4*)(As + a_row_off[i] + (((2 * g1) ^ a_x) << 2));
+            for (int i = 0; i < MI; ++i) {
+                if constexpr (A_KMAJ) {
+                    af[g & 1][i] = *(const f32x4*)(As + a_row_off[i] + (((2 * g) ^ a_x) << 2));
+                } else {
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) af[g & 1][i][t] = As[(g * 8 + 4 * lh + t) * BM + wm0 + i * 32 + li];
                 }
-            } else {
-#pragma unroll
-                for (int i = 0; i < MI; ++i) av[s1 & 1][i] = As[krow * BM + wm0 + i * 32 + li];
             }
 #pragma unroll
-            for (int j = 0; j < NI; ++j) bv[s1 & 1][j] = Bs[krow * BN + wn0 + j * 32 + li];
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) bf[g & 1][j][t] = Bs[(g * 8 + 4 * lh + t) * BN + wn0 + j * 32 + li];
         };
         fetch(0);
 #pragma unroll
-        for (int s = 0; s < S; ++s) {
-            if (s + 1 < S) fetch(s + 1);
+        for (int g = 0; g < G; ++g) {
+            if (g + 1 < G) fetch(g + 1);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int i = 0; i < MI; ++i)
+            for (int t = 0; t < 4; ++t)
 #pragma unroll
-                for (int j = 0; j < NI; ++j) {
-                    const float a = A_KMAJ ? ag[(s >> 2) & 1][i][s & 3] : av[s & 1][i];
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, bv[s & 1][j], acc[i][j], 0, 0, 0);
-                }
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int j = 0; j < NI; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[g & 1][i][t], bf[g & 1][j][t], acc[i][j], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
