@@ -88,6 +88,7 @@ def main() -> int:
     ap.add_argument("--workload", type=int, default=3, choices=[1, 2, 3, 4, 5, 6])
     ap.add_argument("--no-tune", action="store_true", help="use the shape heuristic instead of the tuner")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--evals", type=int, default=0, help="tuner budget: timed points, in cost-model order (0 = all)")
     ap.add_argument("--cpu-rows", type=int, default=4096, help="rows of the product the oracle is timed on")
     ap.add_argument("--pin", default="", help="bm,bn,bk,wm,wn,vec,raster,sched[,split_k]: pin this tile config instead of tuning")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
@@ -174,14 +175,21 @@ def main() -> int:
         del src, dst
 
     tuner_log = None
+    search = None
     if args.pin:
         v = [int(t) for t in args.pin.split(",")]
         tsg.tile_config_set(op, dt, tsg.TileConfig(bm=v[0], bn=v[1], bk=v[2], wm=v[3], wn=v[4], vec=v[5], raster=v[6], sched=v[7],
                                                    split_k=(v[8] if len(v) > 8 else 1)))
         args.no_tune = True
     if not args.no_tune:
+        tsg.search_set(args.evals, True)
         best, best_ms, recs = tune()
-        tuner_log = [dict(r.config.as_dict(), ms=round(r.ms, 5)) for r in recs]
+        tuner_log = [dict(r.config.as_dict(), ms=round(r.ms, 5), predicted_ms=round(r.predicted_ms, 5)) for r in recs]
+        timed = [r for r in recs if r.ms >= 0]
+        # the first timed point is the cost model's pick, i.e. what a call without tuning uses
+        search = {"evaluations": len(timed), "default_ms": timed[0].ms, "best_ms": best_ms,
+                  "speedup_vs_default": timed[0].ms / best_ms,
+                  "best_so_far_ms": [round(r.best_ms, 5) for r in timed]}
         for r in recs:
             log("  tuner: %s -> %.4f ms (best so far %.4f)" % (r.config, r.ms, r.best_ms))
         log("tuner picked %s at %.4f ms" % (best, best_ms))
@@ -250,6 +258,7 @@ def main() -> int:
         "cpu_baseline": cpu,
     }
     if tuner_log is not None:
+        out["search"] = search
         out["tuner_log"] = tuner_log
     print(json.dumps(out), flush=True)
     return 0

@@ -118,6 +118,7 @@ typedef struct {
     tsg_tile_config config;
     float ms;        /* mean time of one call (best of three batches); < 0 if illegal here */
     float best_ms;   /* best so far, including this evaluation */
+    float predicted_ms; /* the cost model's estimate for this point (at 2.4 GHz) */
 } tsg_tune_record;
 
 /* ---- compute (device pointers, asynchronous) ---------------------------------- */
@@ -210,6 +211,12 @@ tsg_status tsg_conv2d_index_map(int64_t N, int64_t H, int64_t W, int64_t Cin,
 tsg_status tsg_gemm_index_map(int32_t trans_a, int64_t M, int64_t K, int64_t lda, int64_t *off);
 
 /* ---- search (Case Study 5) ----------------------------------------------------- */
+
+/* Budget and order of the tuner calls that follow.  max_evals: stop after that many timed
+ * points (0 = all).  model_order: 1 = visit the points in the order of the library's cost
+ * model, so that the first timed point is the library's default for the shape and a small
+ * budget covers the likely winners; 0 = in enumeration order.  Default (0, 1). */
+tsg_status tsg_search_set(int32_t max_evals, int32_t model_order);
 
 /* Time every legal instantiated config on the caller's buffers (three batches of `iters`
  * back-to-back calls each, after one warm-up), keep the fastest and pin it with tsg_tile_config_set.  This

@@ -37,7 +37,8 @@ class LaunchInfo(ctypes.Structure):
 
 
 class TuneRecord(ctypes.Structure):
-    _fields_ = [("config", TileConfig), ("ms", ctypes.c_float), ("best_ms", ctypes.c_float)]
+    _fields_ = [("config", TileConfig), ("ms", ctypes.c_float), ("best_ms", ctypes.c_float),
+                ("predicted_ms", ctypes.c_float)]
 
 
 class TsgError(RuntimeError):
@@ -69,6 +70,7 @@ def _load():
         "tsg_tile_config_get": [i32, i32, i64, i64, i64, cfgp],
         "tsg_last_launch": [ctypes.POINTER(LaunchInfo)],
         "tsg_workspace_set": [vp, i64],
+        "tsg_search_set": [i32, i32],
         "tsg_conv2d_index_map": [i64] * 10 + [vp],
         "tsg_gemm_index_map": [i32, i64, i64, i64, vp],
         "tsg_autotune_gemm": [i32, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, u32, vp, i32,
@@ -101,7 +103,7 @@ _lib = _load()
 EXPORTS = ("tsg_gemm", "tsg_gemm_transA", "tsg_gemm_batched", "tsg_conv2d_nhwc", "tsg_split",
            "tsg_tile_config_count", "tsg_tile_config_enum", "tsg_tile_config_check",
            "tsg_tile_config_set", "tsg_tile_config_get", "tsg_last_launch", "tsg_workspace_set",
-           "tsg_workspace_bytes", "tsg_conv2d_index_map",
+           "tsg_workspace_bytes", "tsg_search_set", "tsg_conv2d_index_map",
            "tsg_gemm_index_map", "tsg_autotune_gemm", "tsg_autotune_gemm_batched", "tsg_autotune_conv2d_nhwc",
            "tsg_status_string", "tsg_version")
 
@@ -232,6 +234,10 @@ def gemm_index_map(trans_a, M, K, lda, off):
 
 
 # ---- search ---------------------------------------------------------------------------
+
+def search_set(max_evals=0, model_order=True):
+    _check(_lib.tsg_search_set(max_evals, int(bool(model_order))), "tsg_search_set")
+
 
 def _tune_out(cap):
     return TileConfig(), ctypes.c_float(), (TuneRecord * cap)(), ctypes.c_int32()

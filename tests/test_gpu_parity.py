@@ -460,3 +460,30 @@ def test_autotune_pins_the_fastest_legal_config():
     tsg.gemm(tsg.F32, M, N, K, dA, K, dB, N, dC, N, tsg.STRICT)
     torch.cuda.synchronize()
     assert np.array_equal(dC.cpu().numpy().astype(np.float64), oracle.gemm(A, B, with_s=False))
+
+
+def test_search_budget_and_model_order():
+    """Case Study 5: the tuner visits the points in the order of the cost model, so its first
+    timed point is the config a call without tuning uses, and it stops at the budget."""
+    M, N, K = 384, 320, 512
+    A, B = inputs(M, N, K, 12, "ints", False, tsg.F32)
+    dA, dB = dev(A), dev(B)
+    dC = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+    default = tsg.tile_config_get(tsg.OP_GEMM, tsg.F32, M, N, K)
+    try:
+        tsg.search_set(6, True)
+        best, ms, log = tsg.autotune_gemm(tsg.F32, False, M, N, K, dA, K, dB, N, dC, N, iters=3)
+        timed = [r for r in log if r.ms >= 0]
+        assert len(timed) == 6
+        first = timed[0].config.as_dict()
+        want = default.as_dict()
+        assert {k: first[k] for k in ("bm", "bn", "bk", "wm", "wn", "sched", "split_k", "vec")} == \
+               {k: want[k] for k in ("bm", "bn", "bk", "wm", "wn", "sched", "split_k", "vec")}
+        preds = [r.predicted_ms for r in log]
+        assert all(a <= b for a, b in zip(preds, preds[1:]))
+        assert best.as_dict() in [r.config.as_dict() for r in timed]
+    finally:
+        tsg.search_set(0, True)
+    tsg.gemm(tsg.F32, M, N, K, dA, K, dB, N, dC, N, tsg.STRICT)
+    torch.cuda.synchronize()
+    assert np.array_equal(dC.cpu().numpy().astype(np.float64), oracle.gemm(A, B, with_s=False))

@@ -137,7 +137,7 @@ def test_config_set_get_roundtrip_and_rollback():
     op, dt = tsg.OP_GEMM, tsg.F32
     tsg.tile_config_set(op, dt, None)
     h = tsg.tile_config_get(op, dt, 4096, 4096, 4096)
-    assert (h.bm, h.bn) == (128, 128) and h.vec == 4
+    assert h.bm * h.bn >= 128 * 128 and h.vec == 4 and h.split_k == 1
     hs = tsg.tile_config_get(op, dt, 256, 256, 256)
     assert hs.bm * hs.bn < h.bm * h.bn           # small problems get small tiles
     c = tsg.tile_config_enum(op, dt, tsg.tile_config_count(op, dt) - 1)
@@ -226,6 +226,14 @@ def test_strict_call_with_failed_precondition_is_silenceable_and_enqueues_nothin
             tsg.conv2d_nhwc(dt, 1, 8, 8, 3, 8, 3, 3, 1, 1, 1, 1, FAKE, FAKE, FAKE, tsg.STRICT, 0)
     finally:
         tsg.tile_config_set(op, dt, None)
+
+
+def test_search_set_validates():
+    for bad in ((-1, 1), (0, 2), (0, -1)):
+        with pytest.raises(tsg.TsgError) as e:
+            tsg._check(tsg._lib.tsg_search_set(*bad), "tsg_search_set")
+        assert e.value.status == tsg.E_INVALID
+    tsg.search_set(0, True)
 
 
 def test_status_strings():
