@@ -268,8 +268,24 @@ tsg_status run(const Problem& p, hipStream_t s) {
     }
     if (make_plan(p, heur, 1, &pl) == TSG_OK) return enqueue(p, pl, s);
     if (p.flags & TSG_STRICT) return TSG_E_SILENCEABLE;
+    // last alternative: scalar accesses, which have no precondition.  The direct-to-LDS forms
+    // have no scalar variant, so the same tile is taken in a register-staged form (or, if
+    // that one is not instantiated, the smallest tile of the table).
     tsg_tile_config scalar = heur;
     scalar.vec = 1;
+    scalar.split_k = 1;
+    if (scalar.sched >= 4) {
+        scalar.sched = 0;
+        if (!find_entry(p.dtype, scalar)) {
+            int n = 0;
+            const KernelEntry* t = kernels(p.dtype, &n);
+            int pick = -1;
+            for (int i = 0; i < n; ++i)
+                if (t[i].sched < 4 && (pick < 0 || t[i].bm * t[i].bn < t[pick].bm * t[pick].bn)) pick = i;
+            if (pick < 0) return TSG_E_SILENCEABLE;
+            scalar = config_of(t[pick], 1, heur.raster, 1);
+        }
+    }
     if (make_plan(p, scalar, 2, &pl) == TSG_OK) return enqueue(p, pl, s);
     return TSG_E_SILENCEABLE;
 }

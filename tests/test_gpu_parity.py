@@ -147,8 +147,8 @@ def test_leading_dimensions_odd_rows_and_scalar_access(dtype):
         li = tsg.last_launch()
         assert li.alternative == 1 and li.config.vec == vmax
         check(C, A, B, dtype, trans_a=trans, exact=True)
-        c = tsg.tile_config_get(op, dtype, M, N, K)
-        c.vec = 1
+        c = tsg.TileConfig(bm=64, bn=64, bk=(32 if dtype == tsg.F32 else 64), wm=32, wn=32, vec=1, raster=0,
+                           sched=0, split_k=1)
         tsg.tile_config_set(op, dtype, c)
         C = run_gemm(dtype, A, B, trans_a=trans, lda=acols + 1, ldb=N + 1, ldc=N + 5, flags=tsg.STRICT)
         li = tsg.last_launch()
