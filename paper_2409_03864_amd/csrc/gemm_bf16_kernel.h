@@ -62,6 +62,79 @@ __device__ __forceinline__ void tile_coords(const KArgs& p, int bid, int& tm, in
     tn = bid - tm * p.tiles_n;
 }
 
+// What follows the k loop: the split-k reduction (see the fp32 kernels) and the epilogue.
+template <class T>
+__device__ __forceinline__ void finish_tile(const KArgs& p, f32x16 (&acc)[T::MI][T::NI], float* __restrict__ C,
+                                            int tile, int split, int tiles, int m0, int n0, int wm0, int wn0,
+                                            bool interior) {
+    constexpr int BM = T::BM, BN = T::BN, NT = T::NT, MI = T::MI, NI = T::NI;
+    const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, lh = lane >> 5;
+    // split k: park the partial tile, count the arrival, and let the last arrival reduce
+    if (p.split_k > 1) {
+        __shared__ int arrived;
+        const long long slot = (long long)blockIdx.y * tiles + tile;
+        float* ws = p.ws + slot * p.split_k * (BM * BN);
+        // A partial tile is kept in register order.  Partials cross between L2 domains, so
+        // they are written and read with device-scope accesses that go through to memory; once
+        // a wave's stores are acknowledged (the wait) and all waves are at the barrier, the
+        // arrival is counted, and whoever sees the last count finds every partial in memory.
+        // This takes no cache-wide write-back or invalidate.
+        float* mine = ws + (long long)split * (BM * BN);
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    __hip_atomic_store(mine + ((i * NI + j) * 16 + r) * NT + tid, acc[i][j][r], __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (tid == 0) arrived = __hip_atomic_fetch_add(p.counters + slot, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (arrived != p.split_k - 1) return;
+        // acc = ((P0 + P1) + P2) + ...: one partial tile at a time, all of its loads in flight together
+        for (int sp = 0; sp < p.split_k; ++sp) {
+            const float* part = ws + (long long)sp * (BM * BN);
+            float t[MI][NI][16];
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NI; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r)
+                        t[i][j][r] = __hip_atomic_load(part + ((i * NI + j) * 16 + r) * NT + tid, __ATOMIC_RELAXED,
+                                                       __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NI; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[i][j][r] = sp == 0 ? t[i][j][r] : acc[i][j][r] + t[i][j][r];
+        }
+        if (tid == 0) p.counters[slot] = 0;   // ready for the next launch on this workspace
+    }
+
+    const bool neg = p.flags & FLAG_NEGATE, accum = p.flags & FLAG_ACCUMULATE;
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            const int col = n0 + wn0 + j * 32 + li;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = m0 + wm0 + i * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+                if (interior || (row < p.M && col < p.N)) {
+                    float* c = C + (long long)row * p.ldc + col;
+                    float v = acc[i][j][r];
+                    if (neg) v = -v;
+                    if (accum) v += *c;
+                    *c = v;
+                }
+            }
+        }
+}
+
 template <class T, int AMODE, int VEC, bool EDGE>
 __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_kernel(const KArgs p) {
     constexpr int BM = T::BM, BN = T::BN, BK = T::BK, NT = T::NT, MI = T::MI, NI = T::NI;
@@ -318,90 +391,320 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_kernel(const KArgs p
         __syncthreads();
     }
 
-    // split k: park the partial tile, count the arrival, and let the last arrival reduce
-    if (p.split_k > 1) {
-        __shared__ int arrived;
-        const long long slot = (long long)blockIdx.y * tiles + tile;
-        float* ws = p.ws + slot * p.split_k * (BM * BN);
-        // A partial tile is kept in register order.  Partials cross between L2 domains, so
-        // they are written and read with device-scope accesses that go through to memory; once
-        // a wave's stores are acknowledged (the wait) and all waves are at the barrier, the
-        // arrival is counted, and whoever sees the last count finds every partial in memory.
-        // This takes no cache-wide write-back or invalidate.
-        float* mine = ws + (long long)split * (BM * BN);
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
-#pragma unroll
-            for (int j = 0; j < NI; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r)
-                    __hip_atomic_store(mine + ((i * NI + j) * 16 + r) * NT + tid, acc[i][j][r], __ATOMIC_RELAXED,
-                                       __HIP_MEMORY_SCOPE_AGENT);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        if (tid == 0) arrived = __hip_atomic_fetch_add(p.counters + slot, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __syncthreads();
-        if (arrived != p.split_k - 1) return;
-        // acc = ((P0 + P1) + P2) + ...: one partial tile at a time, all of its loads in flight together
-        for (int sp = 0; sp < p.split_k; ++sp) {
-            const float* part = ws + (long long)sp * (BM * BN);
-            float t[MI][NI][16];
-#pragma unroll
-            for (int i = 0; i < MI; ++i)
-#pragma unroll
-                for (int j = 0; j < NI; ++j)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r)
-                        t[i][j][r] = __hip_atomic_load(part + ((i * NI + j) * 16 + r) * NT + tid, __ATOMIC_RELAXED,
-                                                       __HIP_MEMORY_SCOPE_AGENT);
-#pragma unroll
-            for (int i = 0; i < MI; ++i)
-#pragma unroll
-                for (int j = 0; j < NI; ++j)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[i][j][r] = sp == 0 ? t[i][j][r] : acc[i][j][r] + t[i][j][r];
-        }
-        if (tid == 0) p.counters[slot] = 0;   // ready for the next launch on this workspace
+    finish_tile<T>(p, acc, C, tile, split, tiles, m0, n0, wm0, wn0, interior);
+}
+
+// ---------------------------------------------------------------------------------------
+// SCHED 4 / 5: operand tiles travel from global memory straight into a ring of 3 / 4 LDS
+// stages, as in the fp32 kernels (one direct load = 64 lanes x 16 bytes = 1 KiB of
+// consecutive LDS; chunks wholly outside the operand come from a block of zeros; steps or
+// tiles with chunks cut by the end of a row go through registers with masks).
+//
+// Unpadded tiles need a swizzle on both kinds of fragment read.  [row][k] tiles: chunk c
+// (8 values of k) of row r sits at position c ^ swz(r), so the 16-byte reads of 16
+// consecutive rows cover all banks.  [k][j] tiles: the transposing read of a 16-lane group
+// touches four consecutive k rows, 32 bytes each, at the same j; chunk c of row k sits at
+// position c ^ 2 (k % 4), which puts those four pieces in four different 32-byte bank ranges.
+__device__ __attribute__((aligned(16))) u16 g_zero_chunk[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+
+__device__ __forceinline__ void load_to_lds16(const void* g, unsigned lds_byte_base) {
+    // M0 carries the wave's LDS destination; lane l lands at base + 16 * l
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_byte_base)
+                 : "memory", "m0");
+}
+template <int N>
+__device__ __forceinline__ void wait_loads_outstanding() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <class T>
+struct LdsDirect {
+    static constexpr int STAGES = T::SCHED == 5 ? 4 : 3;
+    static constexpr int A_ELEMS = T::BM * T::BK, B_ELEMS = T::BK * T::BN, STAGE = A_ELEMS + B_ELEMS;
+    static constexpr int BYTES = STAGES * STAGE * 2;
+};
+
+template <class T, int AMODE, bool EDGE>
+__global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const KArgs p) {
+    constexpr int BM = T::BM, BN = T::BN, BK = T::BK, NT = T::NT, MI = T::MI, NI = T::NI;
+    using L = LdsDirect<T>;
+    constexpr int STAGES = L::STAGES, D = STAGES - 1;
+    constexpr bool A_KMAJ = AMODE != A_COL;
+    constexpr int A_CPR = A_KMAJ ? BK / 8 : BM / 8;   // 16-byte chunks per stored row of A
+    constexpr int A_ROWS = A_KMAJ ? BM : BK;
+    constexpr int A_RPP = NT / A_CPR, PA = A_ROWS / A_RPP;
+    constexpr int B_CPR = BN / 8, B_RPP = NT / B_CPR, PB = BK / B_RPP;
+    constexpr int LPT = PA + PB;
+    static_assert(NT % A_CPR == 0 && A_ROWS % A_RPP == 0 && PA >= 1, "A staging shape");
+    static_assert(NT % B_CPR == 0 && BK % B_RPP == 0 && PB >= 1, "B staging shape");
+    static_assert((D - 1) * LPT <= 63, "outstanding-load counter range");
+    static_assert(B_CPR >= 8 && (A_KMAJ || A_CPR >= 8), "the [k][j] swizzle permutes chunks in groups of eight");
+    constexpr int SW_MOD = A_CPR < 16 ? A_CPR : 16, SW_DIV = 16 / SW_MOD;
+    extern __shared__ __attribute__((aligned(16))) u16 smem16[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm0 = (wave / T::WAVES_N) * T::WM, wn0 = (wave % T::WAVES_N) * T::WN;
+    const int li = lane & 31, lh = lane >> 5;
+
+    const int tiles = p.tiles_m * p.tiles_n;
+    const int split = blockIdx.x / tiles, tile = blockIdx.x - split * tiles;
+    int tm, tn;
+    tile_coords(p, tile, tm, tn);
+    const int m0 = tm * BM, n0 = tn * BN;
+    const u16* __restrict__ A = (const u16*)p.A + (long long)blockIdx.y * p.stride_a;
+    const u16* __restrict__ B = (const u16*)p.B + (long long)blockIdx.y * p.stride_b;
+    float* __restrict__ C = p.C + (long long)blockIdx.y * p.stride_c;
+
+    const bool interior = !EDGE || (m0 + BM <= p.m_main && n0 + BN <= p.n_main);
+    const int nk_all = (p.K + BK - 1) / BK;
+    const int kb = (int)((long long)nk_all * split / p.split_k);
+    const int nk = (int)((long long)nk_all * (split + 1) / p.split_k) - kb;
+
+    // leading steps of this workgroup whose chunks are all whole (inside or outside)
+    int n_direct = nk;
+    if constexpr (EDGE) {
+        bool whole_tile = !((p.N & 7) && n0 + BN > p.N);
+        if (AMODE == A_COL && (p.M & 7) && m0 + BM > p.M) whole_tile = false;
+        if (!whole_tile) n_direct = 0;
+        else if (AMODE == A_ROW && (p.K & 7)) n_direct = max(0, min(nk, p.k_full - kb));
     }
 
-    const bool neg = p.flags & FLAG_NEGATE, accum = p.flags & FLAG_ACCUMULATE;
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) u16*)smem16 +
+                          (unsigned)__builtin_amdgcn_readfirstlane(tid & ~63) * 16u;
+    const int a_r = tid / A_CPR, a_cp = tid % A_CPR;
+    const int b_r = tid / B_CPR, b_cp = tid % B_CPR;
+    auto swz_k = [](int row) -> int { return (row / SW_DIV) % SW_MOD; };   // [row][k] tiles
+    auto swz_j = [](int krow) -> int { return (krow & 3) << 1; };          // [k][j] tiles
+
+    const u16* a_src[PA];
+    int a_k[PA];
+    bool a_in[PA];
+    int cv_base[PA], cv_hi0[PA], cv_wi0[PA];
+#pragma unroll
+    for (int q = 0; q < PA; ++q) {
+        const int row = a_r + q * A_RPP;
+        if constexpr (AMODE == A_ROW) {
+            a_k[q] = (a_cp ^ swz_k(row)) * 8;
+            a_in[q] = !EDGE || m0 + row < p.M;
+            a_src[q] = A + (long long)(m0 + row) * p.lda + a_k[q];
+        } else if constexpr (AMODE == A_COL) {
+            a_k[q] = row;   // the stored row is the k index
+            const int mc = (a_cp ^ swz_j(row)) * 8;
+            a_in[q] = !EDGE || m0 + mc < p.M;
+            a_src[q] = A + (long long)row * p.lda + m0 + mc;
+        } else {
+            a_k[q] = (a_cp ^ swz_k(row)) * 8;
+            const int m = m0 + row;
+            a_in[q] = !EDGE || m < p.M;
+            a_src[q] = A;
+            const int mm = a_in[q] ? m : 0;
+            const int wo = mm % p.Wo, t = mm / p.Wo;
+            const int ho = t % p.Ho, n = t / p.Ho;
+            cv_base[q] = n * p.H;
+            cv_hi0[q] = ho * p.sh - p.ph;
+            cv_wi0[q] = wo * p.sw - p.pw;
+        }
+    }
+    int cs_kh = 0, cs_kw = 0, cs_ci = 0;
+    const bool one_tap = AMODE == A_CONV && p.Cin % BK == 0;
+    if constexpr (AMODE == A_CONV) {
+        const int k = kb * BK, tap = k / p.Cin;
+        cs_ci = k - tap * p.Cin;
+        cs_kh = tap / p.KW;
+        cs_kw = tap - cs_kh * p.KW;
+    }
+    const u16* b_src[PB];
+    bool b_in[PB];
+#pragma unroll
+    for (int q = 0; q < PB; ++q) {
+        const int krow = b_r + q * B_RPP;
+        const int nc = (b_cp ^ swz_j(krow)) * 8;
+        b_in[q] = !EDGE || n0 + nc < p.N;
+        b_src[q] = B + (long long)krow * p.ldb + n0 + nc;
+    }
+
+    auto issue_direct = [&](int kt, int stage) {
+        const int k0 = kt * BK;
+        const unsigned as = lds0 + (unsigned)(stage * L::STAGE) * 2u;
+        const unsigned bs = as + (unsigned)L::A_ELEMS * 2u;
+#pragma unroll
+        for (int q = 0; q < PA; ++q) {
+            const u16* src;
+            if constexpr (AMODE == A_ROW) {
+                const bool in = a_in[q] && (!EDGE || k0 + a_k[q] < p.K);
+                src = in ? a_src[q] + k0 : g_zero_chunk;
+            } else if constexpr (AMODE == A_COL) {
+                const bool in = a_in[q] && (!EDGE || k0 + a_k[q] < p.K);
+                src = in ? a_src[q] + (long long)k0 * p.lda : g_zero_chunk;
+            } else {
+                const int k = k0 + a_k[q];
+                int kh = cs_kh, kw = cs_kw, ci = cs_ci + a_k[q];
+                if (!one_tap) {
+                    const int tap = k / p.Cin;
+                    ci = k - tap * p.Cin;
+                    kh = tap / p.KW;
+                    kw = tap - kh * p.KW;
+                }
+                const int hi = cv_hi0[q] + kh, wi = cv_wi0[q] + kw;
+                const bool in = a_in[q] && k < p.K && hi >= 0 && hi < p.H && wi >= 0 && wi < p.W;
+                src = in ? A + ((long long)(cv_base[q] + hi) * p.W + wi) * p.Cin + ci : g_zero_chunk;
+            }
+            load_to_lds16(src, as + (unsigned)(q * NT) * 16u);
+        }
+#pragma unroll
+        for (int q = 0; q < PB; ++q) {
+            const bool in = b_in[q] && (!EDGE || k0 + b_r + q * B_RPP < p.K);
+            const u16* src = in ? b_src[q] + (long long)k0 * p.ldb : g_zero_chunk;
+            load_to_lds16(src, bs + (unsigned)(q * NT) * 16u);
+        }
+    };
+
+    auto issue_masked = [&](int kt, int stage) {
+        const int k0 = kt * BK;
+        u16* As = smem16 + stage * L::STAGE;
+        u16* Bs = As + L::A_ELEMS;
+#pragma unroll
+        for (int q = 0; q < PA; ++q) {
+            const int row = a_r + q * A_RPP;
+            u16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                if constexpr (AMODE == A_ROW) {
+                    const int m = m0 + row, k = k0 + a_k[q] + e;
+                    if (m < p.M && k < p.K) v[e] = A[(long long)m * p.lda + k];
+                } else if constexpr (AMODE == A_COL) {
+                    const int k = k0 + row, m = m0 + (a_cp ^ swz_j(row)) * 8 + e;
+                    if (k < p.K && m < p.M) v[e] = A[(long long)k * p.lda + m];
+                } else {
+                    const int k = k0 + a_k[q] + e;
+                    const int tap = k / p.Cin, ci = k - tap * p.Cin;
+                    const int kh = tap / p.KW, kw = tap - kh * p.KW;
+                    const int hi = cv_hi0[q] + kh, wi = cv_wi0[q] + kw;
+                    if (a_in[q] && k < p.K && hi >= 0 && hi < p.H && wi >= 0 && wi < p.W)
+                        v[e] = A[((long long)(cv_base[q] + hi) * p.W + wi) * p.Cin + ci];
+                }
+            }
+            *(u16x8*)(As + (q * NT + tid) * 8) = v;
+        }
+#pragma unroll
+        for (int q = 0; q < PB; ++q) {
+            const int krow = b_r + q * B_RPP, k = k0 + krow;
+            u16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int n = n0 + (b_cp ^ swz_j(krow)) * 8 + e;
+                if (k < p.K && n < p.N) v[e] = B[(long long)k * p.ldb + n];
+            }
+            *(u16x8*)(Bs + (q * NT + tid) * 8) = v;
+        }
+    };
+    auto issue = [&](int kt_local, int stage) {
+        if (!EDGE || kt_local < n_direct) issue_direct(kb + kt_local, stage);
+        else issue_masked(kb + kt_local, stage);
+        if constexpr (AMODE == A_CONV) {
+            cs_ci += BK;
+            while (cs_ci >= p.Cin) {
+                cs_ci -= p.Cin;
+                if (++cs_kw == p.KW) { cs_kw = 0; ++cs_kh; }
+            }
+        }
+    };
+
+    f32x16 acc[MI][NI];
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int j = 0; j < NI; ++j) {
-            const int col = n0 + wn0 + j * 32 + li;
+        for (int j = 0; j < NI; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = m0 + wm0 + i * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
-                if (interior || (row < p.M && col < p.N)) {
-                    float* c = C + (long long)row * p.ldc + col;
-                    float v = acc[i][j][r];
-                    if (neg) v = -v;
-                    if (accum) v += *c;
-                    *c = v;
-                }
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    // [row][k] fragment: row wm0 + 32 i + li, chunk 2 g + lh of k step g, swizzled by the row
+    int a_row_off[MI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i) a_row_off[i] = (wm0 + i * 32 + li) * BK;
+    const int a_x = lh ^ swz_k(li);
+    // [k][j] fragment by transposing reads: lane s of a 16-lane group points at row
+    // 8 lh + s / 4 (and that row + 4) of the k step, columns 16 (lane / 16 % 2) + 4 (s % 4) of the block
+    const int tr_row = 8 * lh + ((lane & 15) >> 2);
+    const int tr_col = (lane & 16) + 4 * (lane & 3);
+    const int tr_x = swz_j(tr_row);   // (row + 4) % 4 == row % 4: both reads share the mask
+    auto read_tr = [&](const u16* t, int ld, int k, int col) -> bf16x8 {
+        const int c = col + tr_col;
+        const u16* p0 = t + (k + tr_row) * ld + (((c >> 3) ^ tr_x) << 3) + (c & 7);
+        const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p0));
+        const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p0 + 4 * ld));
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    };
+
+    // fragments of k step g+1 are fetched while the MFMAs of step g run
+    auto compute = [&](int stage) {
+        const u16* As = smem16 + stage * L::STAGE;
+        const u16* Bs = As + L::A_ELEMS;
+        constexpr int G = BK / 16;
+        bf16x8 af[2][MI], bf[2][NI];
+        auto fetch = [&](int g) {
+#pragma unroll
+            for (int i = 0; i < MI; ++i) {
+                if constexpr (A_KMAJ) af[g & 1][i] = *(const bf16x8*)(As + a_row_off[i] + (((2 * g) ^ a_x) << 3));
+                else af[g & 1][i] = read_tr(As, BM, g * 16, wm0 + i * 32);
             }
+#pragma unroll
+            for (int j = 0; j < NI; ++j) bf[g & 1][j] = read_tr(Bs, BN, g * 16, wn0 + j * 32);
+        };
+        fetch(0);
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            if (g + 1 < G) fetch(g + 1);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NI; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[g & 1][i], bf[g & 1][j], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
+    };
+
+    for (int t = 0; t < D; ++t)
+        if (t < nk) issue(t, t);
+    int cur = 0;
+    for (int kt = 0; kt < nk; ++kt) {
+        if (kt + D <= n_direct) wait_loads_outstanding<(D - 1) * LPT>();
+        else wait_loads_outstanding<0>();
+        __syncthreads();
+        if (kt + D < nk) issue(kt + D, cur == 0 ? STAGES - 1 : cur - 1);
+        compute(cur);
+        cur = cur + 1 == STAGES ? 0 : cur + 1;
+    }
+
+    finish_tile<T>(p, acc, C, tile, split, tiles, m0, n0, wm0, wn0, interior);
 }
 
 template <class T, int AMODE>
 hipError_t launch_mode(int variant, const KArgs& a, int batch, hipStream_t s) {
     const dim3 grid(a.tiles_m * a.tiles_n * a.split_k, batch, 1), block(T::NT, 1, 1);
-    constexpr int A_SIZE = (AMODE != A_COL) ? T::BM * T::LDK : T::BK * T::LDA_T;
-    constexpr int BYTES = 2 * (A_SIZE + T::BK * T::LDB) * 2;
     void (*fn)(const KArgs) = nullptr;
-    switch (variant) {
-        case 0: fn = gemm_bf16_kernel<T, AMODE, 8, false>; break;
-        case 1: fn = gemm_bf16_kernel<T, AMODE, 8, true>; break;
-        default: fn = gemm_bf16_kernel<T, AMODE, 1, true>; break;
+    int bytes;
+    if constexpr (T::SCHED >= 4) {
+        if (variant == 2) return hipErrorInvalidValue;   // whole 16-byte chunks only
+        bytes = LdsDirect<T>::BYTES;
+        fn = variant == 0 ? gemm_bf16_direct_kernel<T, AMODE, false> : gemm_bf16_direct_kernel<T, AMODE, true>;
+    } else {
+        constexpr int A_SIZE = (AMODE != A_COL) ? T::BM * T::LDK : T::BK * T::LDA_T;
+        bytes = 2 * (A_SIZE + T::BK * T::LDB) * 2;
+        switch (variant) {
+            case 0: fn = gemm_bf16_kernel<T, AMODE, 8, false>; break;
+            case 1: fn = gemm_bf16_kernel<T, AMODE, 8, true>; break;
+            default: fn = gemm_bf16_kernel<T, AMODE, 1, true>; break;
+        }
     }
     static bool attr_done[3] = {false, false, false};
-    if (BYTES > 48 * 1024 && !attr_done[variant]) {
-        hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, BYTES);
+    if (bytes > 48 * 1024 && !attr_done[variant]) {
+        hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
         if (e != hipSuccess) return e;
         attr_done[variant] = true;
     }
-    hipLaunchKernelGGL(fn, grid, block, BYTES, s, a);
+    hipLaunchKernelGGL(fn, grid, block, bytes, s, a);
     return hipGetLastError();
 }
 
@@ -420,7 +723,14 @@ hipError_t launch_mode(int variant, const KArgs& a, int batch, hipStream_t s) {
     X(128, 128, 32, 64, 64, 2, 1)   \
     X(128, 128, 32, 64, 64, 2, 0)   \
     X(64, 64, 64, 32, 32, 2, 1)     \
-    X(64, 64, 64, 32, 32, 2, 0)
+    X(64, 64, 64, 32, 32, 2, 0)     \
+    X(256, 256, 32, 128, 64, 2, 4)  \
+    X(256, 256, 32, 128, 64, 2, 5)  \
+    X(256, 256, 32, 128, 128, 1, 5) \
+    X(256, 128, 64, 64, 64, 2, 4)   \
+    X(128, 128, 64, 64, 64, 2, 4)   \
+    X(128, 128, 32, 64, 64, 2, 5)   \
+    X(64, 64, 64, 32, 32, 2, 4)
 
 #define TSG_BF16_DEFINE_MODE(FN, AMODE)                                                             \
     namespace tsg {                                                                                 \

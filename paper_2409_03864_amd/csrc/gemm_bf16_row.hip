@@ -17,7 +17,9 @@ hipError_t launch_any(int tile, int amode, int variant, const KArgs& a, int batc
 }
 #define TSG_BF16_ENTRY(bm, bn, bk, wm, wn, mw, sc)                                                    \
     KernelEntry{bm, bn, bk, wm, wn, sc, Tile<bm, bn, bk, wm, wn, mw, sc>::NT, 8,                       \
-                4 * (bm * Tile<bm, bn, bk, wm, wn, mw, sc>::LDK + bk * Tile<bm, bn, bk, wm, wn, mw, sc>::LDB), \
+                (sc >= 4 ? LdsDirect<Tile<bm, bn, bk, wm, wn, mw, sc>>::BYTES                          \
+                         : 4 * (bm * Tile<bm, bn, bk, wm, wn, mw, sc>::LDK +                          \
+                                bk * Tile<bm, bn, bk, wm, wn, mw, sc>::LDB)),                          \
                 &launch_any},
 const KernelEntry kTable[] = {TSG_BF16_TILES(TSG_BF16_ENTRY)};
 }  // namespace
