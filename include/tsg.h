@@ -152,6 +152,20 @@ tsg_status tsg_conv2d_nhwc(tsg_dtype dtype, int64_t N, int64_t H, int64_t W, int
                            const void *x, const void *w, float *y,
                            uint32_t flags, void *stream);
 
+/* The same convolution with its result placed in a window of a larger NHWC tensor: output
+ * pixel (n, ho, wo), channel co goes to y[n*y_stride_n + ho*y_stride_h + wo*y_stride_w + co]
+ * (strides in elements, y = address of pixel (0, 0, 0)).  With TSG_ACCUMULATE this adds the
+ * result to the interior of a zero-padded tensor without forming the padded result (Case
+ * Study 3, the add-of-zero-pad rewrite); elements outside the window are never touched.
+ * The same for a GEMM needs no extra call: pass C = &C_big[r0][c0] and ldc = pitch of C_big.
+ * TSG_E_INVALID if the strides let two pixels of the window overlap. */
+tsg_status tsg_conv2d_nhwc_window(tsg_dtype dtype, int64_t N, int64_t H, int64_t W, int64_t Cin,
+                                  int64_t Cout, int64_t KH, int64_t KW,
+                                  int64_t stride_h, int64_t stride_w, int64_t pad_h, int64_t pad_w,
+                                  const void *x, const void *w, float *y,
+                                  int64_t y_stride_n, int64_t y_stride_h, int64_t y_stride_w,
+                                  uint32_t flags, void *stream);
+
 /* ---- schedule parameters (host only; no GPU needed) --------------------------- */
 
 /* Loop split of Fig. 1 / Fig. 8: main = largest multiple of d <= ub, rest = ub - main

@@ -144,6 +144,17 @@ def epilogue(R, flags: int = 0, C_old=None):
     return out
 
 
+def add_of_zero_pad(big, R, lo, sign: int = 1):
+    """big + pad0(sign * R): R placed at offset `lo` (one index per axis) inside an array of
+    zeros of big's shape, then added (Case Study 3: the sum with a zero-padded tensor).  The
+    definition is written with the padded tensor formed explicitly, which is exactly what
+    the library avoids."""
+    big = np.asarray(big, dtype=np.float64)
+    padded = np.zeros_like(big)
+    padded[tuple(slice(o, o + n) for o, n in zip(lo, R.shape))] = sign * np.asarray(R, dtype=np.float64)
+    return big + padded
+
+
 def split(ub: int, d: int):
     """(main, rest, tiles) of splitting a loop of trip count ub by divisor d (Fig. 1,
     Fig. 8): main % d == 0, rest < d, main + rest == ub."""

@@ -30,6 +30,9 @@ struct Problem {
     uint32_t flags;
     // convolution geometry
     int64_t H = 0, W = 0, Cin = 0, Ho = 0, Wo = 0, KH = 0, KW = 0, sh = 1, sw = 1, ph = 0, pw = 0;
+    // output window strides (elements); y_window = 0: y is a plain [N*Ho*Wo][Cout] matrix
+    int y_window = 0;
+    int64_t y_sn = 0, y_sh = 0, y_sw = 0;
 };
 
 std::mutex g_mu;
@@ -222,6 +225,7 @@ tsg_status make_plan(const Problem& p, const tsg_tile_config& cfg, int alternati
     a.ws = ws ? (float*)((char*)ws + kCounterBytes) : nullptr;
     a.H = (int)p.H; a.W = (int)p.W; a.Cin = (int)p.Cin; a.Ho = (int)p.Ho; a.Wo = (int)p.Wo;
     a.KW = (int)p.KW; a.sh = (int)p.sh; a.sw = (int)p.sw; a.ph = (int)p.ph; a.pw = (int)p.pw;
+    a.y_window = p.y_window; a.y_sn = p.y_sn; a.y_sh = p.y_sh; a.y_sw = p.y_sw;
 
     tsg_launch_info& li = out->info;
     li.config = cfg;
@@ -495,6 +499,24 @@ tsg_status tsg_conv2d_nhwc(tsg_dtype dtype, int64_t N, int64_t H, int64_t W, int
     const tsg_status v = conv_problem(dtype, N, H, W, Cin, Cout, KH, KW, stride_h, stride_w, pad_h, pad_w, x, w, y,
                                       flags, &p);
     if (v != TSG_OK) return v;
+    return run(p, (hipStream_t)stream);
+}
+
+tsg_status tsg_conv2d_nhwc_window(tsg_dtype dtype, int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,
+                                  int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w, int64_t pad_h,
+                                  int64_t pad_w, const void* x, const void* w, float* y, int64_t y_stride_n,
+                                  int64_t y_stride_h, int64_t y_stride_w, uint32_t flags, void* stream) {
+    Problem p;
+    const tsg_status v = conv_problem(dtype, N, H, W, Cin, Cout, KH, KW, stride_h, stride_w, pad_h, pad_w, x, w, y,
+                                      flags, &p);
+    if (v != TSG_OK) return v;
+    // pixels of the window must not overlap: each stride covers the extent below it
+    if (y_stride_w < Cout || y_stride_h < (p.Wo - 1) * y_stride_w + Cout ||
+        y_stride_n < (p.Ho - 1) * y_stride_h + (p.Wo - 1) * y_stride_w + Cout)
+        return TSG_E_INVALID;
+    if (y_stride_n > (int64_t)0x7fffffff * 64) return TSG_E_INVALID;
+    p.y_window = 1;
+    p.y_sn = y_stride_n; p.y_sh = y_stride_h; p.y_sw = y_stride_w;
     return run(p, (hipStream_t)stream);
 }
 

@@ -125,7 +125,12 @@ __device__ __forceinline__ void finish_tile(const KArgs& p, f32x16 (&acc)[T::MI]
             for (int r = 0; r < 16; ++r) {
                 const int row = m0 + wm0 + i * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
                 if (interior || (row < p.M && col < p.N)) {
-                    float* c = C + (long long)row * p.ldc + col;
+                    long long off = (long long)row * p.ldc;
+                    if (p.y_window) {   // output pixel row -> (n, ho, wo) -> its place in the larger tensor
+                        const int wo = row % p.Wo, t = row / p.Wo;
+                        off = (long long)(t / p.Ho) * p.y_sn + (long long)(t % p.Ho) * p.y_sh + (long long)wo * p.y_sw;
+                    }
+                    float* c = C + off + col;
                     float v = acc[i][j][r];
                     if (neg) v = -v;
                     if (accum) v += *c;

@@ -33,6 +33,10 @@ struct KArgs {
     int* counters;
     // convolution geometry (A_CONV only)
     int H, W, Cin, Ho, Wo, KW, sh, sw, ph, pw;
+    // convolution output written into a window of a larger NHWC tensor: pixel (n, ho, wo) at
+    // C + n*y_sn + ho*y_sh + wo*y_sw (elements) instead of row m of a matrix with pitch ldc
+    int y_window;
+    long long y_sn, y_sh, y_sw;
 };
 
 // One instantiated tile shape.  `launch` takes the entry's index in its table.

@@ -372,6 +372,55 @@ def test_conv_all_ones_counts_valid_taps_on_device():
     assert np.all(y[:, 0, 0] == 256) and np.all(y[:, 0, 1:-1] == 384) and np.all(y[:, 1:-1, 1:-1] == 576)
 
 
+def test_gemm_accumulated_into_window_of_zero_padded_tensor():
+    """Case Study 3, add of zero pad: C_big += pad0(A.B) without forming the padded product.
+    The window is addressed through C and ldc; elements outside it keep their bits."""
+    M, N, K, r0, c0 = 100, 72, 130, 3, 5
+    A, B = inputs(M, N, K, 41, "ints", False, tsg.F32)
+    big = synth.small_ints(42, 2, (M + 7) * (N + 9)).reshape(M + 7, N + 9)
+    d_big = dev(big)
+    ld = N + 9
+    win = d_big.data_ptr() + 4 * (r0 * ld + c0)
+    tsg.gemm(tsg.F32, M, N, K, dev(A), K, dev(B), N, win, ld, tsg.ACCUMULATE)
+    torch.cuda.synchronize()
+    want = oracle.add_of_zero_pad(big, oracle.gemm(A, B, with_s=False), (r0, c0))
+    assert np.array_equal(d_big.cpu().numpy().astype(np.float64), want)
+
+
+@pytest.mark.parametrize("dtype", [tsg.F32, tsg.BF16_F32ACC])
+def test_conv_into_window_of_larger_nhwc_tensor(dtype):
+    """The convolution result lands in (or is added to) a spatial and channel window of a
+    larger NHWC tensor; everything outside the window is untouched."""
+    N, H, W, Cin, Cout = 2, 9, 11, 8, 12
+    x, w = synth.conv_inputs(N, H, W, Cin, Cout, 3, 3, seed=43, dist="ints")
+    if dtype == tsg.BF16_F32ACC:
+        x, w = synth.f32_to_bf16_bits(x), synth.f32_to_bf16_bits(w)
+    R = oracle.conv2d_nhwc(x, w, pad=(1, 1), with_s=False)
+    Ho, Wo = R.shape[1], R.shape[2]
+    a, b, c0, Cbig = 2, 3, 4, Cout + 7
+    big = synth.small_ints(44, 2, N * (Ho + 5) * (Wo + 4) * Cbig).reshape(N, Ho + 5, Wo + 4, Cbig)
+    sw, sh, sn = Cbig, (Wo + 4) * Cbig, (Ho + 5) * (Wo + 4) * Cbig
+    for flags, want in ((tsg.ACCUMULATE, oracle.add_of_zero_pad(big, R, (0, a, b, c0))),
+                        (tsg.ACCUMULATE | tsg.NEGATE, oracle.add_of_zero_pad(big, R, (0, a, b, c0), sign=-1))):
+        d_big = dev(big)
+        win = d_big.data_ptr() + 4 * (a * sh + b * sw + c0)
+        tsg.conv2d_nhwc_window(dtype, N, H, W, Cin, Cout, 3, 3, 1, 1, 1, 1, dev(x), dev(w), win, sn, sh, sw, flags)
+        torch.cuda.synchronize()
+        assert np.array_equal(d_big.cpu().numpy().astype(np.float64), want)
+    # overwrite form: the window takes the result, the rest keeps its bits
+    d_big = dev(big)
+    win = d_big.data_ptr() + 4 * (a * sh + b * sw + c0)
+    tsg.conv2d_nhwc_window(dtype, N, H, W, Cin, Cout, 3, 3, 1, 1, 1, 1, dev(x), dev(w), win, sn, sh, sw, 0)
+    torch.cuda.synchronize()
+    want = big.astype(np.float64).copy()
+    want[:, a:a + Ho, b:b + Wo, c0:c0 + Cout] = R
+    assert np.array_equal(d_big.cpu().numpy().astype(np.float64), want)
+    # overlapping pixels are a definite error
+    with pytest.raises(tsg.TsgError) as e:
+        tsg.conv2d_nhwc_window(dtype, N, H, W, Cin, Cout, 3, 3, 1, 1, 1, 1, dev(x), dev(w), win, sn, sh, Cout - 1, 0)
+    assert e.value.status == tsg.E_INVALID
+
+
 # ------------------------------------------------------------------ the five workloads
 
 def test_config1_gemm_256():

@@ -329,3 +329,18 @@ def test_error_metric_definition():
     assert abs(nw - 0.001) < 1e-12 and abs(cw - 0.001) < 1e-12
     C[1, 0] = 1e-30
     assert oracle.errors(C, ref, S)[1] == float("inf")
+
+
+def test_add_of_zero_pad_touches_only_the_interior():
+    """x + pad0(y): outside the window the sum is x bit for bit, inside it is x + y; checked
+    against literal loops on a small case."""
+    big = _rand((5, 7), 3).astype(np.float64)
+    R = _rand((2, 3), 4, tid=1).astype(np.float64)
+    out = oracle.add_of_zero_pad(big, R, (1, 2))
+    for i in range(5):
+        for j in range(7):
+            inside = 1 <= i < 3 and 2 <= j < 5
+            want = big[i, j] + (R[i - 1, j - 2] if inside else 0.0)
+            assert out[i, j] == want
+    neg = oracle.add_of_zero_pad(big, R, (1, 2), sign=-1)
+    assert np.array_equal(neg[1:3, 2:5], big[1:3, 2:5] - R)
