@@ -22,6 +22,7 @@ sys.path.insert(0, ROOT)
 
 # published dense peaks of the part (TFLOP/s), by the arithmetic type of the contraction
 PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
+PEAK_HBM_GBS = 8000.0
 METRIC = "TFLOP/s and % of MI355X matrix peak, fp32 GEMM 4096^3 (1 GPU)"
 
 # HBM bytes per launch of the dominant kernel, from two `rocprofv3 --pmc` passes
@@ -36,19 +37,20 @@ TRAFFIC = {
 }
 
 
-def kernel_hash(dtype: str) -> str:
+def kernel_hash(dtype: str, op: str = "") -> str:
     import hashlib
     h = hashlib.sha256()
     csrc = os.path.join(ROOT, "paper_2409_03864_amd", "csrc")
-    for f in ("tsg_internal.h", "gemm_f32_kernel.h" if dtype == "f32" else "gemm_bf16_kernel.h"):
+    kernel = "reduce.hip" if op == "reduce_sum" else "gemm_f32_kernel.h" if dtype == "f32" else "gemm_bf16_kernel.h"
+    for f in ("tsg_internal.h", kernel):
         with open(os.path.join(csrc, f), "rb") as fh:
             h.update(fh.read())
     return h.hexdigest()[:16]
 
 
-def traffic_bytes(k: int, dtype: str, tile: dict):
+def traffic_bytes(k: int, dtype: str, tile: dict, op: str = ""):
     for e in TRAFFIC.get(k, ()):
-        if e["kernel_hash"] == kernel_hash(dtype) and all(tile.get(key) == val for key, val in e["tile"].items()):
+        if e["kernel_hash"] == kernel_hash(dtype, op) and all(tile.get(key) == val for key, val in e["tile"].items()):
             return e["bytes"]
     return None
 
@@ -59,7 +61,9 @@ def log(*a):
 
 def workload_flops(c) -> int:
     """Algorithmic flop count: 2 per multiply-add; convolution taps that fall in the zero
-    padding are not work."""
+    padding are not work.  The reduce does one add per element."""
+    if c["op"] == "reduce_sum":
+        return c["rows"] * c["cols"]
     if c["op"] != "conv2d_nhwc":
         return 2 * c.get("B", 1) * c["M"] * c["N"] * c["K"]
 
@@ -72,6 +76,9 @@ def workload_flops(c) -> int:
 
 
 def describe(k, c) -> str:
+    if c["op"] == "reduce_sum":
+        return "cfg%d: %s full additive reduce of a %d x %d tensor, %s entries, seed %d" % (
+            k, c["dtype"], c["rows"], c["cols"], c["dist"], c["seed"])
     if c["op"] == "conv2d_nhwc":
         return ("cfg%d: %s conv2d NHWC N=%d H=W=%d Cin=%d Cout=%d %dx%d stride %d pad %d, seed %d"
                 % (k, c["dtype"], c["N"], c["H"], c["Cin"], c["Cout"], c["KH"], c["KW"], c["stride"], c["pad"],
@@ -86,7 +93,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", type=int, default=3, choices=[1, 2, 3, 4, 5, 6])
+    ap.add_argument("--workload", type=int, default=3, choices=[1, 2, 3, 4, 5, 6, 7])
     ap.add_argument("--no-tune", action="store_true", help="use the shape heuristic instead of the tuner")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--evals", type=int, default=0, help="tuner budget: timed points, in cost-model order (0 = all)")
@@ -123,11 +130,21 @@ def main() -> int:
         x = np.ascontiguousarray(x)
         return torch.from_numpy(x.view(np.int16) if x.dtype == np.uint16 else x).to(dev)
 
-    dA, dB = up(a), up(b)
+    dA = up(a)
+    dB = up(b) if b is not None else None
     # device memory for the split of the k loop (used by shapes whose tiles cannot fill the chip)
     workspace = torch.empty(64 << 20, dtype=torch.uint8, device=dev)
     tsg.workspace_set(workspace)
-    if c["op"] == "conv2d_nhwc":
+    if c["op"] == "reduce_sum":
+        M, N, K = c["rows"], c["cols"], 1
+        op = None
+        dC = torch.zeros((1,), dtype=torch.float32, device=dev)
+
+        def step():
+            tsg.reduce_sum(dt, M, N, dA, N, dC, flags)
+
+        args.no_tune = True      # one kernel form, nothing to search
+    elif c["op"] == "conv2d_nhwc":
         Ho = (c["H"] + 2 * c["pad"] - c["KH"]) // c["stride"] + 1
         dC = torch.zeros((c["N"], Ho, Ho, c["Cout"]), dtype=torch.float32, device=dev)
         geom = (c["N"], c["H"], c["W"], c["Cin"], c["Cout"], c["KH"], c["KW"], c["stride"], c["stride"],
@@ -215,16 +232,32 @@ def main() -> int:
 
     flops = workload_flops(c)
     ms_per_step = wall * 1e3 / args.steps
-    value = flops / (wall / args.steps) / 1e12
-    peak = PEAK_TFLOPS[c["dtype"]]
-    achieved = flops / (avg_kern_ms * 1e-3) / 1e12
-    log("step %.4f ms wall, %.4f ms per launch between stream events: %.2f TFLOP/s = %.1f%% of %.1f"
-        % (ms_per_step, avg_kern_ms, achieved, 100 * achieved / peak, peak))
+    hbm_bound = c["op"] == "reduce_sum"
+    if hbm_bound:
+        # bound by HBM: algorithmic bytes = every element read once (the 4-byte result is noise)
+        nbytes = c["rows"] * c["cols"] * 4
+        unit, peak = "GB/s", PEAK_HBM_GBS
+        value = nbytes / (wall / args.steps) / 1e9
+        achieved = nbytes / (avg_kern_ms * 1e-3) / 1e9
+    else:
+        unit, peak = "TFLOP/s", PEAK_TFLOPS[c["dtype"]]
+        value = flops / (wall / args.steps) / 1e12
+        achieved = flops / (avg_kern_ms * 1e-3) / 1e12
+    log("step %.4f ms wall, %.4f ms per launch between stream events: %.2f %s = %.1f%% of %.1f"
+        % (ms_per_step, avg_kern_ms, achieved, unit, 100 * achieved / peak, peak))
 
     cpu = None
     if not args.no_cpu:
         import oracle
-        if c["op"] == "conv2d_nhwc":
+        if c["op"] == "reduce_sum":
+            sub = a[:min(M, 4096)]
+            t0 = time.perf_counter()
+            oracle.reduce_sum(sub)
+            dtc = time.perf_counter() - t0
+            cpu = {"value": sub.size * 4 / dtc / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+                   "sample": "rows 0..%d (%d elements, fp64 sum)" % (sub.shape[0] - 1, sub.size),
+                   "seconds": round(dtc, 3)}
+        elif c["op"] == "conv2d_nhwc":
             xs = a[:1]
             t0 = time.perf_counter()
             oracle.conv2d_nhwc(xs, b, stride=(c["stride"],) * 2, pad=(c["pad"],) * 2, with_s=False)
@@ -239,23 +272,26 @@ def main() -> int:
             dtc = time.perf_counter() - t0
             sflops, sample = 2 * rows * N * K, "rows 0..%d of C%s (%d x %d x %d triple loop)" % (
                 rows - 1, " of batch 0" if c["op"] == "gemm_batched" else "", rows, N, K)
-        cpu = {"value": sflops / dtc / 1e12, "unit": "TFLOP/s", "cores": oracle.threads(), "kind": "oracle",
-               "sample": sample, "seconds": round(dtc, 3)}
-        log("cpu oracle: %s in %.2f s on %d threads = %.4f TFLOP/s" % (sample, dtc, cpu["cores"], cpu["value"]))
+        if cpu is None:
+            cpu = {"value": sflops / dtc / 1e12, "unit": "TFLOP/s", "cores": oracle.threads(), "kind": "oracle",
+                   "sample": sample, "seconds": round(dtc, 3)}
+        log("cpu oracle: %s in %.2f s on %d threads = %.4f %s" % (cpu["sample"], dtc, cpu["cores"], cpu["value"],
+                                                                  cpu["unit"]))
 
     out = {
-        "metric": METRIC if k == 3 else "TFLOP/s and % of MI355X matrix peak, " + describe(k, c),
-        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "metric": METRIC if k == 3 else ("GB/s and % of MI355X HBM peak, " if hbm_bound else
+                                         "TFLOP/s and % of MI355X matrix peak, ") + describe(k, c),
+        "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": c["dtype"], "data": "synthetic",
         "pct_of_peak": 100.0 * value / peak,
         "config": {"workload": describe(k, c), "M": M, "N": N, "K": K, "flops_per_step": flops,
-                   "tile_config": li.config.as_dict(), "alternative": int(li.alternative),
-                   "tuned": not args.no_tune},
-        "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+                   "tile_config": None if hbm_bound else li.config.as_dict(),
+                   "alternative": None if hbm_bound else int(li.alternative), "tuned": not args.no_tune},
+        "roofline": {"bound": "hbm" if hbm_bound else "mfma", "achieved": achieved, "peak": peak, "unit": unit,
                      "frac": achieved / peak,
-                     "traffic": traffic_bytes(k, c["dtype"], li.config.as_dict()),
-                     "kernel_ms_avg": avg_kern_ms, "kernel_hash": kernel_hash(c["dtype"])},
+                     "traffic": traffic_bytes(k, c["dtype"], {} if hbm_bound else li.config.as_dict(), c["op"]),
+                     "kernel_ms_avg": avg_kern_ms, "kernel_hash": kernel_hash(c["dtype"], c["op"])},
         "cpu_baseline": cpu,
     }
     if tuner_log is not None:

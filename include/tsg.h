@@ -166,6 +166,17 @@ tsg_status tsg_conv2d_nhwc_window(tsg_dtype dtype, int64_t N, int64_t H, int64_t
                                   int64_t y_stride_n, int64_t y_stride_h, int64_t y_stride_w,
                                   uint32_t flags, void *stream);
 
+/* Full additive reduce: out[0] = +-(sum over r < rows, c < cols of x[r*ld + c]) (+ out[0]),
+ * x fp32 or bfloat16 bits, accumulated in fp32 in a fixed order (results are repeatable).
+ * Case Study 3: a full additive reduce may ignore a reshape or transpose of its operand, so
+ * a tensor is passed as it lies in memory, whatever view the program had of it (ld >= cols;
+ * ld == cols means one contiguous run).  x, out: DEVICE pointers.  One workgroup per 16 K
+ * elements, up to 2048; more than one needs the workspace (tsg_workspace_set) for the
+ * workgroup sums: without it the call runs as one workgroup, or fails silenceably under
+ * TSG_STRICT. */
+tsg_status tsg_reduce_sum(tsg_dtype dtype, int64_t rows, int64_t cols, const void *x, int64_t ld,
+                          float *out, uint32_t flags, void *stream);
+
 /* ---- schedule parameters (host only; no GPU needed) --------------------------- */
 
 /* Loop split of Fig. 1 / Fig. 8: main = largest multiple of d <= ub, rest = ub - main

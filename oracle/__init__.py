@@ -155,6 +155,17 @@ def add_of_zero_pad(big, R, lo, sign: int = 1):
     return big + padded
 
 
+def reduce_sum(x):
+    """(sum, sum of magnitudes) of every element, in fp64 (Case Study 3: the full additive
+    reduce, which does not depend on how the tensor is indexed).  x: fp32 array or uint16
+    array of bfloat16 bits, any shape."""
+    x, is_bf16 = _operand(x)
+    if is_bf16:
+        x = (x.astype(np.uint32) << np.uint32(16)).view(np.float32)
+    v = x.astype(np.float64).ravel()
+    return float(np.sum(v)), float(np.sum(np.abs(v)))
+
+
 def split(ub: int, d: int):
     """(main, rest, tiles) of splitting a loop of trip count ub by divisor d (Fig. 1,
     Fig. 8): main % d == 0, rest < d, main + rest == ub."""

@@ -64,6 +64,7 @@ def _load():
         "tsg_gemm_batched": [i32, i32, i64, i64, i64, i64, vp, i64, i64, vp, i64, i64, vp, i64, i64, u32, vp],
         "tsg_conv2d_nhwc": [i32] + [i64] * 11 + [vp, vp, vp, u32, vp],
         "tsg_conv2d_nhwc_window": [i32] + [i64] * 11 + [vp, vp, vp, i64, i64, i64, u32, vp],
+        "tsg_reduce_sum": [i32, i64, i64, vp, i64, vp, u32, vp],
         "tsg_split": [i64, i64, vp, vp, vp],
         "tsg_tile_config_enum": [i32, i32, i32, cfgp],
         "tsg_tile_config_check": [i32, i32, i64, i64, i64, i64, cfgp],
@@ -102,7 +103,7 @@ def _load():
 _lib = _load()
 
 EXPORTS = ("tsg_gemm", "tsg_gemm_transA", "tsg_gemm_batched", "tsg_conv2d_nhwc", "tsg_conv2d_nhwc_window",
-           "tsg_split",
+           "tsg_reduce_sum", "tsg_split",
            "tsg_tile_config_count", "tsg_tile_config_enum", "tsg_tile_config_check",
            "tsg_tile_config_set", "tsg_tile_config_get", "tsg_last_launch", "tsg_workspace_set",
            "tsg_workspace_bytes", "tsg_search_set", "tsg_conv2d_index_map",
@@ -174,6 +175,10 @@ def conv2d_nhwc_window(dtype, N, H, W, Cin, Cout, KH, KW, stride_h, stride_w, pa
     _check(_lib.tsg_conv2d_nhwc_window(dtype, N, H, W, Cin, Cout, KH, KW, stride_h, stride_w, pad_h, pad_w,
                                        _ptr(x), _ptr(w), _ptr(y), y_stride_n, y_stride_h, y_stride_w, flags,
                                        _stream(stream)), "tsg_conv2d_nhwc_window")
+
+
+def reduce_sum(dtype, rows, cols, x, ld, out, flags=0, stream=None):
+    _check(_lib.tsg_reduce_sum(dtype, rows, cols, _ptr(x), ld, _ptr(out), flags, _stream(stream)), "tsg_reduce_sum")
 
 
 # ---- schedule parameters (host only) -----------------------------------------------

@@ -17,7 +17,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtsg.so")
 SOURCES = ["api.cpp", "gemm_f32_row.hip", "gemm_f32_col.hip", "gemm_f32_conv.hip",
-           "gemm_bf16_row.hip", "gemm_bf16_col.hip", "gemm_bf16_conv.hip"]
+           "gemm_bf16_row.hip", "gemm_bf16_col.hip", "gemm_bf16_conv.hip", "reduce.hip"]
 HEADERS = [os.path.join(CSRC, h) for h in ("tsg_internal.h", "gemm_f32_kernel.h", "gemm_bf16_kernel.h")] + \
           [os.path.join(HERE, "..", "include", "tsg.h")]
 

@@ -41,7 +41,8 @@ tsg_tile_config g_pin[kNumOps][kNumDtypes];
 
 // Caller-owned workspace for split k: arrival counters first, partial tiles after them.
 constexpr int64_t kMaxSlots = 16384;                       // (batch x tile) counters
-constexpr int64_t kCounterBytes = kMaxSlots * 4;
+constexpr int64_t kCounterBytes = tsg::kWorkspaceCounterBytes;
+static_assert(kCounterBytes == kMaxSlots * 4, "one counter per slot");
 constexpr int kMaxSplit = 16;
 void* g_ws = nullptr;
 int64_t g_ws_bytes = 0;
@@ -438,6 +439,13 @@ tsg_status autotune(Problem p, hipStream_t s, int iters, tsg_tile_config* best, 
 }
 
 }  // namespace
+
+bool tsg::workspace_get(void** ws, long long* bytes) {
+    std::lock_guard<std::mutex> g(g_mu);
+    *ws = g_ws;
+    *bytes = g_ws_bytes;
+    return g_ws != nullptr;
+}
 
 extern "C" {
 

@@ -51,6 +51,11 @@ struct KernelEntry {
     hipError_t (*launch)(int tile, int amode, int variant, const KArgs& a, int batch, hipStream_t s);
 };
 
+// The caller's workspace (tsg_workspace_set): arrival counters in the first
+// kWorkspaceCounterBytes, partial results after them.  Returns false if none is set.
+constexpr long long kWorkspaceCounterBytes = 16384 * 4;
+bool workspace_get(void** ws, long long* bytes);
+
 const KernelEntry* f32_kernels(int* count);
 const KernelEntry* bf16_kernels(int* count);
 

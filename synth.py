@@ -144,6 +144,8 @@ CONFIGS = {
     5: dict(op="gemm", dtype="bf16", M=8192, N=8192, K=8192, dist="normal", seed=4, flags=("negate",)),
     # Case Study 4 / Fig. 7 of the paper: one ResNet-50 layer's loop nest, batch loop included
     6: dict(op="gemm_batched", dtype="f32", B=6, M=196, N=256, K=2305, dist="uniform", seed=5, flags=()),
+    # the full additive reduce of Case Study 3 on a tensor larger than every cache (1 GiB)
+    7: dict(op="reduce_sum", dtype="f32", rows=16384, cols=16384, dist="uniform", seed=6, flags=()),
 }
 
 PAPER_BATCH_MATMUL = dict(B=6, M=196, N=256, K=2305)
@@ -152,6 +154,8 @@ PAPER_BATCH_MATMUL = dict(B=6, M=196, N=256, K=2305)
 def config_inputs(k: int):
     """Host arrays for workload configuration k (1-based)."""
     c = CONFIGS[k]
+    if c["op"] == "reduce_sum":
+        return c, uniform_pm1(c["seed"], 0, c["rows"] * c["cols"]).reshape(c["rows"], c["cols"]), None
     if c["op"] == "gemm_batched":
         # one stream per tensor: the batch index is the slowest dimension of A and of B
         a, b = gemm_inputs(c["B"] * c["M"], c["N"], c["K"], seed=c["seed"], dist=c["dist"])

@@ -536,3 +536,75 @@ def test_search_budget_and_model_order():
     tsg.gemm(tsg.F32, M, N, K, dA, K, dB, N, dC, N, tsg.STRICT)
     torch.cuda.synchronize()
     assert np.array_equal(dC.cpu().numpy().astype(np.float64), oracle.gemm(A, B, with_s=False))
+
+
+# ------------------------------------------------------------------ full additive reduce
+
+REDUCE_TOL = 1e-5   # of the sum of magnitudes: ~100 sequential fp32 adds per partial sum at most
+
+
+@pytest.mark.parametrize("dtype", [tsg.F32, tsg.BF16_F32ACC])
+@pytest.mark.parametrize("with_ws", [False, True])
+def test_reduce_sum_exact_on_integers_and_views(dtype, with_ws):
+    """Integer inputs (every order exact): whole tensor, ragged sizes, a strided view, the
+    flags; with the workspace (many workgroups) and without (one workgroup)."""
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device=DEV) if with_ws else None
+    tsg.workspace_set(ws)
+    try:
+        for n in (1, 3, 4, 5, 255, 256 * 16 * 4 + 3, 1 << 20, (1 << 21) + 7):
+            x = synth.small_ints(50, 0, n)
+            h = synth.f32_to_bf16_bits(x) if dtype == tsg.BF16_F32ACC else x
+            out = torch.full((1,), 5.0, dtype=torch.float32, device=DEV)
+            tsg.reduce_sum(dtype, 1, n, dev(h), n, out)
+            torch.cuda.synchronize()
+            assert float(out.item()) == oracle.reduce_sum(h)[0], n
+            tsg.reduce_sum(dtype, 1, n, dev(h), n, out, tsg.ACCUMULATE | tsg.NEGATE)
+            torch.cuda.synchronize()
+            assert float(out.item()) == 0.0, n
+        rows, cols, ld = 37, 1001, 1024
+        x = synth.small_ints(51, 0, rows * ld).reshape(rows, ld)
+        h = synth.f32_to_bf16_bits(x) if dtype == tsg.BF16_F32ACC else x
+        out = torch.zeros((1,), dtype=torch.float32, device=DEV)
+        tsg.reduce_sum(dtype, rows, cols, dev(h), ld, out)
+        torch.cuda.synchronize()
+        assert float(out.item()) == oracle.reduce_sum(np.ascontiguousarray(h[:, :cols]))[0]
+    finally:
+        tsg.workspace_set(None)
+
+
+def test_reduce_sum_random_tolerance_repeatable_and_transpose_invariant(workspace):
+    x = synth.normal_scaled(52, 0, 3000 * 1111, 1.0).reshape(3000, 1111)
+    ref, mag = oracle.reduce_sum(x)
+    outs = []
+    for view in (x, np.ascontiguousarray(x.T), x.reshape(1111, 3000)):
+        out = torch.zeros((1,), dtype=torch.float32, device=DEV)
+        d = dev(view)
+        for _ in range(2):
+            tsg.reduce_sum(tsg.F32, view.shape[0], view.shape[1], d, view.shape[1], out)
+            torch.cuda.synchronize()
+            outs.append(float(out.item()))
+        assert abs(outs[-1] - ref) <= REDUCE_TOL * mag
+        assert outs[-1] == outs[-2]                     # repeatable
+    # a reshape of contiguous memory is the same run of bytes: identical bits; the transposed
+    # copy holds the elements in another order and agrees within the tolerance
+    assert outs[0] == outs[4]
+    # without the workspace a strict call has no alternative
+    tsg.workspace_set(None)
+    out = torch.zeros((1,), dtype=torch.float32, device=DEV)
+    with pytest.raises(tsg.SilenceableError):
+        tsg.reduce_sum(tsg.F32, 3000, 1111, dev(x), 1111, out, tsg.STRICT)
+
+
+def test_workload7_full_reduce_one_gib(workspace):
+    """The benchmark's reduce workload at full size, in its launch configuration."""
+    c, x, _ = synth.config_inputs(7)
+    ref, mag = oracle.reduce_sum(x)
+    out = torch.zeros((1,), dtype=torch.float32, device=DEV)
+    d = dev(x)
+    tsg.reduce_sum(tsg.F32, c["rows"], c["cols"], d, c["cols"], out)
+    torch.cuda.synchronize()
+    assert abs(float(out.item()) - ref) <= REDUCE_TOL * mag
+    ones = torch.ones_like(d)
+    tsg.reduce_sum(tsg.F32, c["rows"], c["cols"], ones, c["cols"], out)
+    torch.cuda.synchronize()
+    assert float(out.item()) == float(c["rows"] * c["cols"])     # 2^28: every partial sum is exact

@@ -228,6 +228,15 @@ def test_strict_call_with_failed_precondition_is_silenceable_and_enqueues_nothin
         tsg.tile_config_set(op, dt, None)
 
 
+def test_reduce_sum_invalid_arguments():
+    for kw in (dict(rows=0), dict(cols=0), dict(ld=3), dict(x=None), dict(out=None), dict(flags=64), dict(dtype=5)):
+        a = dict(dtype=tsg.F32, rows=2, cols=4, x=FAKE, ld=4, out=FAKE, flags=0, stream=0)
+        a.update(kw)
+        with pytest.raises(tsg.TsgError) as e:
+            tsg.reduce_sum(**a)
+        assert e.value.status == tsg.E_INVALID, kw
+
+
 def test_search_set_validates():
     for bad in ((-1, 1), (0, 2), (0, -1)):
         with pytest.raises(tsg.TsgError) as e:

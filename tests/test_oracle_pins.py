@@ -344,3 +344,27 @@ def test_add_of_zero_pad_touches_only_the_interior():
             assert out[i, j] == want
     neg = oracle.add_of_zero_pad(big, R, (1, 2), sign=-1)
     assert np.array_equal(neg[1:3, 2:5], big[1:3, 2:5] - R)
+
+
+def test_reduce_sum_pins():
+    """Closed forms (all ones, 1..n), exact rational sum on a small case, and invariance
+    under transpose / reshape, which is the point of the rewrite."""
+    import math
+    from fractions import Fraction
+    assert oracle.reduce_sum(np.ones((7, 13), np.float32)) == (91.0, 91.0)
+    n = 1000
+    s, a = oracle.reduce_sum(np.arange(1, n + 1, dtype=np.float32))
+    assert s == n * (n + 1) / 2 and a == s
+    x = _rand((9, 11), 5)
+    exact = sum(Fraction(float(v)) for v in x.ravel())
+    s, a = oracle.reduce_sum(x)
+    assert abs(Fraction(s) - exact) <= Fraction(a) * Fraction(1, 2 ** 50)
+    assert s == math.fsum(float(v) for v in x.ravel()) or abs(s - math.fsum(float(v) for v in x.ravel())) < 1e-12
+    st, at = oracle.reduce_sum(np.ascontiguousarray(x.T))
+    sr, ar = oracle.reduce_sum(x.reshape(3, 33))
+    assert abs(st - s) <= 1e-12 and abs(sr - s) <= 1e-12 and at == a == ar
+    neg = x.copy(); neg[0, 0] = -abs(neg[0, 0]) - 1
+    assert oracle.reduce_sum(neg)[1] > abs(oracle.reduce_sum(neg)[0])
+    b = synth.f32_to_bf16_bits(x)
+    sb, _ = oracle.reduce_sum(b)
+    assert sb == float(np.sum(synth.bf16_bits_to_f32(b).astype(np.float64)))
