@@ -778,58 +778,128 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
     for (int i = 0; i < MI; ++i) a_row_off[i] = (wm0 + i * 32 + li) * BK;
     const int a_x = lh ^ swz(li);   // wm0 + 32 i is a multiple of 32, so the swizzle depends on li alone
 
-    // Operands are fetched a whole k group (8 values of k = 4 MFMAs per block) ahead of their
-    // use: with one wave per SIMD nothing else covers the LDS latency, and one MFMA does not.
-    auto compute = [&](int stage) {
-        const float* As = smem + stage * L::STAGE;
-        const float* Bs = As + L::A_FLOATS;
-        constexpr int G = BK / 8;
-        f32x4 af[2][MI], bf[2][NI];
-        auto fetch = [&](int g) {
-#pragma unroll
-            for (int i = 0; i < MI; ++i) {
-                if constexpr (A_KMAJ) {
-                    af[g & 1][i] = *(const f32x4*)(As + a_row_off[i] + (((2 * g) ^ a_x) << 2));
-                } else {
-#pragma unroll
-                    for (int t = 0; t < 4; ++t) af[g & 1][i][t] = As[(g * 8 + 4 * lh + t) * BM + wm0 + i * 32 + li];
+    // ---- one direct load: the x-th of the LPT loads that bring a tile in
+    auto load_one = [&](int kt, int stage, int x) {
+        const int k0 = kt * BK;
+        const unsigned as = lds0 + (unsigned)(stage * L::STAGE) * 4u;
+        const unsigned bs = as + (unsigned)L::A_FLOATS * 4u;
+        if (x < PA) {
+            const int q = x;
+            const float* src;
+            if constexpr (AMODE == A_ROW) {
+                const bool in = a_in[q] && (!EDGE || k0 + a_k[q] < p.K);
+                src = in ? a_src[q] + k0 : g_zero_chunk;
+            } else if constexpr (AMODE == A_COL) {
+                const bool in = a_in[q] && (!EDGE || k0 + a_k[q] < p.K);
+                src = in ? a_src[q] + (long long)k0 * p.lda : g_zero_chunk;
+            } else {
+                const int k = k0 + a_k[q];
+                int kh = cs_kh, kw = cs_kw, ci = cs_ci + a_k[q];
+                if (!one_tap) {
+                    const int tap = k / p.Cin;
+                    ci = k - tap * p.Cin;
+                    kh = tap / p.KW;
+                    kw = tap - kh * p.KW;
+                }
+                const int hi = cv_hi0[q] + kh, wi = cv_wi0[q] + kw;
+                const bool in = a_in[q] && k < p.K && hi >= 0 && hi < p.H && wi >= 0 && wi < p.W;
+                src = in ? A + ((long long)(cv_base[q] + hi) * p.W + wi) * p.Cin + ci : g_zero_chunk;
+            }
+            load_to_lds16(src, as + (unsigned)(q * NT) * 16u);
+        } else {
+            const int q = x - PA;
+            const bool in = b_in && (!EDGE || k0 + b_r + q * B_RPP < p.K);
+            const float* src = in ? b_src[q] + (long long)k0 * p.ldb : g_zero_chunk;
+            load_to_lds16(src, bs + (unsigned)(q * NT) * 16u);
+        }
+    };
+    // the x-th part of bringing in tile kt_local: one direct load, or (steps with cut chunks)
+    // the whole masked tile at x = 0; the convolution's tap state moves on after the last part
+    auto issue_part = [&](int kt_local, int stage, int x) {
+        if (!EDGE || kt_local < n_direct) load_one(kb + kt_local, stage, x);
+        else if (x == 0) issue_masked(kb + kt_local, stage);
+        if constexpr (AMODE == A_CONV) {
+            if (x == LPT - 1) {
+                cs_ci += BK;
+                while (cs_ci >= p.Cin) {
+                    cs_ci -= p.Cin;
+                    if (++cs_kw == p.KW) { cs_kw = 0; ++cs_kh; }
                 }
             }
-#pragma unroll
-            for (int j = 0; j < NI; ++j)
-#pragma unroll
-                for (int t = 0; t < 4; ++t) bf[g & 1][j][t] = Bs[(g * 8 + 4 * lh + t) * BN + wn0 + j * 32 + li];
-        };
-        fetch(0);
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-            if (g + 1 < G) fetch(g + 1);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int t = 0; t < 4; ++t)
-#pragma unroll
-                for (int i = 0; i < MI; ++i)
-#pragma unroll
-                    for (int j = 0; j < NI; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[g & 1][i][t], bf[g & 1][j][t], acc[i][j], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
-    // ---- ring: step kt is multiplied from stage kt % STAGES while steps kt+1 .. kt+D-1 are in
-    // flight and step kt+D is issued into the stage that step kt-1 has just left
+    // ---- fragments: a k group (8 values of k = 4 MFMAs per block) is fetched while the group
+    // before it is multiplied, one LDS read after each MFMA
+    constexpr int G = BK / 8;
+    static_assert(G % 2 == 0, "the fragment double buffer alternates per group across steps");
+    constexpr int NFRAG = (A_KMAJ ? MI : 4 * MI) + 4 * NI;   // LDS reads of one group's fragments
+    constexpr int NM = 4 * MI * NI;                            // MFMAs of one group
+    f32x4 af[2][MI], bf[2][NI];
+    auto frag_read = [&](int stage, int g, int x) {
+        const float* As = smem + stage * L::STAGE;
+        const float* Bs = As + L::A_FLOATS;
+        if constexpr (A_KMAJ) {
+            if (x < MI) {
+                af[g & 1][x] = *(const f32x4*)(As + a_row_off[x] + (((2 * g) ^ a_x) << 2));
+                return;
+            }
+            x -= MI;
+        } else {
+            if (x < 4 * MI) {
+                af[g & 1][x >> 2][x & 3] = As[(g * 8 + 4 * lh + (x & 3)) * BM + wm0 + (x >> 2) * 32 + li];
+                return;
+            }
+            x -= 4 * MI;
+        }
+        bf[g & 1][x >> 2][x & 3] = Bs[(g * 8 + 4 * lh + (x & 3)) * BN + wn0 + (x >> 2) * 32 + li];
+    };
+
+    // ---- ring.  Step kt is multiplied from stage kt % STAGES.  The one barrier of a step sits
+    // before its LAST k group: by then tile kt+1 has landed (own loads: the wait; everybody's:
+    // the barrier) and everybody has left step kt-1, so during that last group the loads of
+    // tile kt+D go into the stage step kt-1 used and the first fragments of step kt+1 are
+    // fetched.  No wave ever starts a step, or leaves a barrier, with its MFMA operands missing.
     for (int t = 0; t < D; ++t)
         if (t < nk) issue(t, t);
+    if (D <= n_direct) wait_loads_outstanding<(D - 1) * LPT>();
+    else wait_loads_outstanding<0>();
+    __syncthreads();
+#pragma unroll
+    for (int x = 0; x < NFRAG; ++x) frag_read(0, 0, x);
     int cur = 0;
     for (int kt = 0; kt < nk; ++kt) {
-        // own loads of step kt have landed once no more than the loads of the D-1 later steps
-        // are outstanding; the barrier then covers the other waves' loads and frees stage cur-1
-        if (kt + D <= n_direct) wait_loads_outstanding<(D - 1) * LPT>();
-        else wait_loads_outstanding<0>();
-        __syncthreads();
-        if (kt + D < nk) issue(kt + D, cur == 0 ? STAGES - 1 : cur - 1);
-        compute(cur);
-        cur = cur + 1 == STAGES ? 0 : cur + 1;
+        const int nxt = cur + 1 == STAGES ? 0 : cur + 1;
+        const int fill = cur == 0 ? STAGES - 1 : cur - 1;
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const bool last = g == G - 1;
+            if (last) {
+                // issued so far: tiles up to kt+D-1, so D-2 tiles may stay in flight behind tile kt+1
+                if (D >= 3 && kt + D <= n_direct) wait_loads_outstanding<(D >= 3 ? (D - 2) * LPT : 0)>();
+                else wait_loads_outstanding<0>();
+                __syncthreads();
+            }
+            constexpr int NX = LPT + NFRAG;
+            constexpr int PER = (NX + NM - 1) / NM;
+#pragma unroll
+            for (int m = 0; m < NM; ++m) {
+                const int t = m / (MI * NI), i = (m / NI) % MI, j = m % NI;
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[g & 1][i][t], bf[g & 1][j][t], acc[i][j], 0, 0, 0);
+#pragma unroll
+                for (int e = m * PER; e < (m + 1) * PER && e < NX; ++e) {
+                    if (e < LPT) {
+                        if (last && kt + D < nk) issue_part(kt + D, fill, e);
+                    } else if (last) {
+                        frag_read(nxt, 0, e - LPT);   // after the last step this reads a stage nobody multiplies
+                    } else {
+                        frag_read(cur, g + 1, e - LPT);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        cur = nxt;
     }
 
     finish_tile<T>(p, acc, C, tile, split, tiles, m0, n0, wm0, wn0, interior);
