@@ -135,13 +135,19 @@ def main() -> int:
     # device memory for the split of the k loop (used by shapes whose tiles cannot fill the chip)
     workspace = torch.empty(64 << 20, dtype=torch.uint8, device=dev)
     tsg.workspace_set(workspace)
+    # raw addresses and the stream handle are taken once: the timed loop then costs one
+    # foreign call per step, which matters for the kernels that run a few microseconds
+    st = torch.cuda.current_stream().cuda_stream
+    pA = dA.data_ptr()
+    pB = dB.data_ptr() if dB is not None else 0
     if c["op"] == "reduce_sum":
         M, N, K = c["rows"], c["cols"], 1
         op = None
         dC = torch.zeros((1,), dtype=torch.float32, device=dev)
+        pC = dC.data_ptr()
 
         def step():
-            tsg.reduce_sum(dt, M, N, dA, N, dC, flags)
+            tsg.reduce_sum(dt, M, N, pA, N, pC, flags, st)
 
         args.no_tune = True      # one kernel form, nothing to search
     elif c["op"] == "conv2d_nhwc":
@@ -152,8 +158,10 @@ def main() -> int:
         op = tsg.OP_CONV2D_NHWC
         M, N, K = c["N"] * Ho * Ho, c["Cout"], c["KH"] * c["KW"] * c["Cin"]
 
+        pC = dC.data_ptr()
+
         def step():
-            tsg.conv2d_nhwc(dt, *geom, dA, dB, dC, flags)
+            tsg.conv2d_nhwc(dt, *geom, pA, pB, pC, flags, st)
 
         def tune():
             return tsg.autotune_conv2d_nhwc(dt, *geom, dA, dB, dC, flags, iters=5)
@@ -162,8 +170,10 @@ def main() -> int:
         op = tsg.OP_GEMM
         dC = torch.zeros((nb, M, N), dtype=torch.float32, device=dev)
 
+        pC = dC.data_ptr()
+
         def step():
-            tsg.gemm_batched(dt, False, nb, M, N, K, dA, K, M * K, dB, N, K * N, dC, N, M * N, flags)
+            tsg.gemm_batched(dt, False, nb, M, N, K, pA, K, M * K, pB, N, K * N, pC, N, M * N, flags, st)
 
         def tune():
             return tsg.autotune_gemm_batched(dt, False, nb, M, N, K, dA, K, M * K, dB, N, K * N, dC, N, M * N,
@@ -176,8 +186,10 @@ def main() -> int:
         lda = M if trans else K
         fn = tsg.gemm_transA if trans else tsg.gemm
 
+        pC = dC.data_ptr()
+
         def step():
-            fn(dt, M, N, K, dA, lda, dB, N, dC, N, flags)
+            fn(dt, M, N, K, pA, lda, pB, N, pC, N, flags, st)
 
         def tune():
             return tsg.autotune_gemm(dt, trans, M, N, K, dA, lda, dB, N, dC, N, flags, iters=5)
