@@ -641,45 +641,132 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
         return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     };
 
-    // fragments of k step g+1 are fetched while the MFMAs of step g run
-    auto compute = [&](int stage) {
-        const u16* As = smem16 + stage * L::STAGE;
-        const u16* Bs = As + L::A_ELEMS;
-        constexpr int G = BK / 16;
-        bf16x8 af[2][MI], bf[2][NI];
-        auto fetch = [&](int g) {
-#pragma unroll
-            for (int i = 0; i < MI; ++i) {
-                if constexpr (A_KMAJ) af[g & 1][i] = *(const bf16x8*)(As + a_row_off[i] + (((2 * g) ^ a_x) << 3));
-                else af[g & 1][i] = read_tr(As, BM, g * 16, wm0 + i * 32);
+    // ---- one direct load: the x-th of the LPT loads that bring a tile in
+    auto load_one = [&](int kt, int stage, int x) {
+        const int k0 = kt * BK;
+        const unsigned as = lds0 + (unsigned)(stage * L::STAGE) * 2u;
+        const unsigned bs = as + (unsigned)L::A_ELEMS * 2u;
+        if (x < PA) {
+            const int q = x;
+            const u16* src;
+            if constexpr (AMODE == A_ROW) {
+                const bool in = a_in[q] && (!EDGE || k0 + a_k[q] < p.K);
+                src = in ? a_src[q] + k0 : g_zero_chunk;
+            } else if constexpr (AMODE == A_COL) {
+                const bool in = a_in[q] && (!EDGE || k0 + a_k[q] < p.K);
+                src = in ? a_src[q] + (long long)k0 * p.lda : g_zero_chunk;
+            } else {
+                const int k = k0 + a_k[q];
+                int kh = cs_kh, kw = cs_kw, ci = cs_ci + a_k[q];
+                if (!one_tap) {
+                    const int tap = k / p.Cin;
+                    ci = k - tap * p.Cin;
+                    kh = tap / p.KW;
+                    kw = tap - kh * p.KW;
+                }
+                const int hi = cv_hi0[q] + kh, wi = cv_wi0[q] + kw;
+                const bool in = a_in[q] && k < p.K && hi >= 0 && hi < p.H && wi >= 0 && wi < p.W;
+                src = in ? A + ((long long)(cv_base[q] + hi) * p.W + wi) * p.Cin + ci : g_zero_chunk;
             }
-#pragma unroll
-            for (int j = 0; j < NI; ++j) bf[g & 1][j] = read_tr(Bs, BN, g * 16, wn0 + j * 32);
-        };
-        fetch(0);
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-            if (g + 1 < G) fetch(g + 1);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int i = 0; i < MI; ++i)
-#pragma unroll
-                for (int j = 0; j < NI; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[g & 1][i], bf[g & 1][j], acc[i][j], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
+            load_to_lds16(src, as + (unsigned)(q * NT) * 16u);
+        } else {
+            const int q = x - PA;
+            const bool in = b_in[q] && (!EDGE || k0 + b_r + q * B_RPP < p.K);
+            const u16* src = in ? b_src[q] + (long long)k0 * p.ldb : g_zero_chunk;
+            load_to_lds16(src, bs + (unsigned)(q * NT) * 16u);
+        }
+    };
+    auto issue_part = [&](int kt_local, int stage, int x) {
+        if (!EDGE || kt_local < n_direct) load_one(kb + kt_local, stage, x);
+        else if (x == 0) issue_masked(kb + kt_local, stage);
+        if constexpr (AMODE == A_CONV) {
+            if (x == LPT - 1) {
+                cs_ci += BK;
+                while (cs_ci >= p.Cin) {
+                    cs_ci -= p.Cin;
+                    if (++cs_kw == p.KW) { cs_kw = 0; ++cs_kh; }
+                }
+            }
         }
     };
 
+    // ---- fragments: a k group (16 values of k = one MFMA per block) is fetched while the group
+    // before it is multiplied, its LDS reads spread over that group's MFMAs.  A transposing
+    // read returns half a fragment (4 values of k), so those operands are kept as two halves.
+    constexpr int G = BK / 16;
+    static_assert(G % 2 == 0, "the fragment double buffer alternates per group across steps");
+    constexpr int NFRAG = (A_KMAJ ? MI : 2 * MI) + 2 * NI;
+    constexpr int NM = MI * NI;
+    bf16x8 af[2][MI];
+    bf16x4 ah[2][MI][2], bh[2][NI][2];
+    auto read_half = [&](const u16* t, int ld, int k, int col, int h) -> bf16x4 {
+        const int c = col + tr_col;
+        const u16* p0 = t + (k + tr_row + 4 * h) * ld + (((c >> 3) ^ tr_x) << 3) + (c & 7);
+        return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p0));
+    };
+    auto frag_read = [&](int stage, int g, int x) {
+        const u16* As = smem16 + stage * L::STAGE;
+        const u16* Bs = As + L::A_ELEMS;
+        if constexpr (A_KMAJ) {
+            if (x < MI) {
+                af[g & 1][x] = *(const bf16x8*)(As + a_row_off[x] + (((2 * g) ^ a_x) << 3));
+                return;
+            }
+            x -= MI;
+        } else {
+            if (x < 2 * MI) {
+                ah[g & 1][x >> 1][x & 1] = read_half(As, BM, g * 16, wm0 + (x >> 1) * 32, x & 1);
+                return;
+            }
+            x -= 2 * MI;
+        }
+        bh[g & 1][x >> 1][x & 1] = read_half(Bs, BN, g * 16, wn0 + (x >> 1) * 32, x & 1);
+    };
+
+    // ---- ring, as in the fp32 kernels: the one barrier of a step sits before its last k group
     for (int t = 0; t < D; ++t)
         if (t < nk) issue(t, t);
+    if (D <= n_direct) wait_loads_outstanding<(D - 1) * LPT>();
+    else wait_loads_outstanding<0>();
+    __syncthreads();
+#pragma unroll
+    for (int x = 0; x < NFRAG; ++x) frag_read(0, 0, x);
     int cur = 0;
     for (int kt = 0; kt < nk; ++kt) {
-        if (kt + D <= n_direct) wait_loads_outstanding<(D - 1) * LPT>();
-        else wait_loads_outstanding<0>();
-        __syncthreads();
-        if (kt + D < nk) issue(kt + D, cur == 0 ? STAGES - 1 : cur - 1);
-        compute(cur);
-        cur = cur + 1 == STAGES ? 0 : cur + 1;
+        const int nxt = cur + 1 == STAGES ? 0 : cur + 1;
+        const int fill = cur == 0 ? STAGES - 1 : cur - 1;
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const bool last = g == G - 1;
+            if (last) {
+                if (D >= 3 && kt + D <= n_direct) wait_loads_outstanding<(D >= 3 ? (D - 2) * LPT : 0)>();
+                else wait_loads_outstanding<0>();
+                __syncthreads();
+            }
+            constexpr int NX = LPT + NFRAG;
+            constexpr int PER = (NX + NM - 1) / NM;
+#pragma unroll
+            for (int m = 0; m < NM; ++m) {
+                const int i = m / NI, j = m % NI;
+                bf16x8 a;
+                if constexpr (A_KMAJ) a = af[g & 1][i];
+                else a = __builtin_shufflevector(ah[g & 1][i][0], ah[g & 1][i][1], 0, 1, 2, 3, 4, 5, 6, 7);
+                const bf16x8 b = __builtin_shufflevector(bh[g & 1][j][0], bh[g & 1][j][1], 0, 1, 2, 3, 4, 5, 6, 7);
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i][j], 0, 0, 0);
+#pragma unroll
+                for (int e = m * PER; e < (m + 1) * PER && e < NX; ++e) {
+                    if (e < LPT) {
+                        if (last && kt + D < nk) issue_part(kt + D, fill, e);
+                    } else if (last) {
+                        frag_read(nxt, 0, e - LPT);
+                    } else {
+                        frag_read(cur, g + 1, e - LPT);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        cur = nxt;
     }
 
     finish_tile<T>(p, acc, C, tile, split, tiles, m0, n0, wm0, wn0, interior);
