@@ -608,3 +608,38 @@ def test_workload7_full_reduce_one_gib(workspace):
     tsg.reduce_sum(tsg.F32, c["rows"], c["cols"], ones, c["cols"], out)
     torch.cuda.synchronize()
     assert float(out.item()) == float(c["rows"] * c["cols"])     # 2^28: every partial sum is exact
+
+
+# ------------------------------------------------------------------ seeded sweep of shapes
+
+def test_seeded_sweep_of_ragged_shapes_all_entry_points(workspace):
+    """Forty shapes drawn from a seeded generator (odd extents, odd leading dimensions, tiny
+    and long k), each through a random entry point, dtype, flag set and, for half of them, a
+    random pinned point of the search space: integer inputs, so every result must match the
+    oracle bit for bit whatever tile, form or split served the call."""
+    rng = np.random.default_rng(20240903)
+    for case in range(40):
+        dtype = tsg.F32 if rng.integers(2) == 0 else tsg.BF16_F32ACC
+        trans = bool(rng.integers(2))
+        M, N = int(rng.integers(1, 300)), int(rng.integers(1, 300))
+        K = int(rng.choice([1, 2, 7, 33, 64, 100, 257, 1000, 2305]))
+        flags = int(rng.choice([0, tsg.NEGATE, tsg.ACCUMULATE, tsg.NEGATE | tsg.ACCUMULATE]))
+        op = tsg.OP_GEMM_TRANSA if trans else tsg.OP_GEMM
+        A, B = inputs(M, N, K, 1000 + case, "ints", trans, dtype)
+        C0 = synth.small_ints(2000 + case, 2, M * N).reshape(M, N)
+        pinned = None
+        if case % 2:
+            for _ in range(50):
+                c = tsg.tile_config_enum(op, dtype, int(rng.integers(tsg.tile_config_count(op, dtype))))
+                if tsg.tile_config_check(op, dtype, M, N, K, c) == tsg.OK:
+                    pinned = c
+                    tsg.tile_config_set(op, dtype, c)
+                    break
+        acols = A.shape[1]
+        C = run_gemm(dtype, A, B, trans_a=trans, flags=flags | (tsg.STRICT if pinned is not None else 0), C0=C0,
+                     lda=acols + int(rng.integers(0, 4)), ldb=N + int(rng.integers(0, 4)),
+                     ldc=N + int(rng.integers(0, 4)))
+        R = oracle.gemm(A, B, trans_a=trans, with_s=False)
+        want = oracle.epilogue(R, flags & 3, C0) if flags & tsg.ACCUMULATE else oracle.epilogue(R, flags & 3)
+        assert np.array_equal(C.astype(np.float64), want), (case, dtype, trans, M, N, K, flags, pinned)
+        tsg.tile_config_set(op, dtype, None)
