@@ -96,6 +96,8 @@ def main() -> int:
     ap.add_argument("--workload", type=int, default=3, choices=[1, 2, 3, 4, 5, 6, 7])
     ap.add_argument("--no-tune", action="store_true", help="use the shape heuristic instead of the tuner")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--graph", action="store_true",
+                    help="record the K steps once into a HIP graph and time one replay (launch-bound workloads)")
     ap.add_argument("--evals", type=int, default=0, help="tuner budget: timed points, in cost-model order (0 = all)")
     ap.add_argument("--cpu-rows", type=int, default=4096, help="rows of the product the oracle is timed on")
     ap.add_argument("--pin", default="", help="bm,bn,bk,wm,wn,vec,raster,sched[,split_k]: pin this tile config instead of tuning")
@@ -164,7 +166,7 @@ def main() -> int:
             tsg.conv2d_nhwc(dt, *geom, pA, pB, pC, flags, st)
 
         def tune():
-            return tsg.autotune_conv2d_nhwc(dt, *geom, dA, dB, dC, flags, iters=5)
+            return tsg.autotune_conv2d_nhwc(dt, *geom, dA, dB, dC, flags, iters=tune_iters)
     elif c["op"] == "gemm_batched":
         nb, M, N, K = c["B"], c["M"], c["N"], c["K"]
         op = tsg.OP_GEMM
@@ -177,7 +179,7 @@ def main() -> int:
 
         def tune():
             return tsg.autotune_gemm_batched(dt, False, nb, M, N, K, dA, K, M * K, dB, N, K * N, dC, N, M * N,
-                                             flags, iters=5)
+                                             flags, iters=tune_iters)
     else:
         M, N, K = c["M"], c["N"], c["K"]
         trans = c["op"] == "gemm_transA"
@@ -192,7 +194,7 @@ def main() -> int:
             fn(dt, M, N, K, pA, lda, pB, N, pC, N, flags, st)
 
         def tune():
-            return tsg.autotune_gemm(dt, trans, M, N, K, dA, lda, dB, N, dC, N, flags, iters=5)
+            return tsg.autotune_gemm(dt, trans, M, N, K, dA, lda, dB, N, dC, N, flags, iters=tune_iters)
 
     if args.copy_calibration:
         n = args.copy_calibration * (1 << 20) // 4
@@ -204,6 +206,8 @@ def main() -> int:
         log("copy calibration: one device copy of %d MiB (reads and writes that many bytes)" % args.copy_calibration)
         del src, dst
 
+    # enough back-to-back calls per timed batch that a batch lasts about a millisecond
+    tune_iters = 5 if workload_flops(c) >= 1e11 else 50
     tuner_log = None
     search = None
     if args.pin:
@@ -232,13 +236,33 @@ def main() -> int:
     # on the stream the kernels are launched on
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    e0.record()
-    for _ in range(args.steps):
-        step()
-    e1.record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
+    if args.graph:
+        # the library only enqueues kernels on the stream it is given, so a call can be recorded;
+        # the K steps become one graph and the timed region is one replay of it
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        st = side.cuda_stream
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                for _ in range(args.steps):
+                    step()
+            graph.replay()            # untimed first replay
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        with torch.cuda.stream(side):
+            e0.record()
+            graph.replay()
+            e1.record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+    else:
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(args.steps):
+            step()
+        e1.record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
     li = tsg.last_launch()
     avg_kern_ms = e0.elapsed_time(e1) / args.steps
 
@@ -299,7 +323,8 @@ def main() -> int:
         "pct_of_peak": 100.0 * value / peak,
         "config": {"workload": describe(k, c), "M": M, "N": N, "K": K, "flops_per_step": flops,
                    "tile_config": None if hbm_bound else li.config.as_dict(),
-                   "alternative": None if hbm_bound else int(li.alternative), "tuned": not args.no_tune},
+                   "alternative": None if hbm_bound else int(li.alternative), "tuned": not args.no_tune,
+                   "hip_graph": bool(args.graph)},
         "roofline": {"bound": "hbm" if hbm_bound else "mfma", "achieved": achieved, "peak": peak, "unit": unit,
                      "frac": achieved / peak,
                      "traffic": traffic_bytes(k, c["dtype"], {} if hbm_bound else li.config.as_dict(), c["op"]),

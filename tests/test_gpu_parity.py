@@ -643,3 +643,41 @@ def test_seeded_sweep_of_ragged_shapes_all_entry_points(workspace):
         want = oracle.epilogue(R, flags & 3, C0) if flags & tsg.ACCUMULATE else oracle.epilogue(R, flags & 3)
         assert np.array_equal(C.astype(np.float64), want), (case, dtype, trans, M, N, K, flags, pinned)
         tsg.tile_config_set(op, dtype, None)
+
+
+def test_calls_recorded_into_a_hip_graph_replay_correctly(workspace):
+    """Compute calls only enqueue kernels on the given stream (no memset, no synchronisation),
+    so they can be recorded into a HIP graph: a graph of a plain GEMM, a split-k GEMM (arrival
+    counters reset themselves) and a reduce is replayed several times, with eager work and
+    synchronisations in between, and every replay must reproduce the eager result bit for bit."""
+    M, N, K = 196, 256, 2305
+    A, B = inputs(M, N, K, 61, "uniform", False, tsg.F32)
+    dA, dB = dev(A), dev(B)
+    tsg.tile_config_set(tsg.OP_GEMM, tsg.F32, tsg.TileConfig(bm=64, bn=64, bk=64, wm=32, wn=32, vec=4, raster=0,
+                                                               sched=4, split_k=4))
+    eager = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+    esum = torch.zeros((1,), dtype=torch.float32, device=DEV)
+    tsg.gemm(tsg.F32, M, N, K, dA, K, dB, N, eager, N, tsg.STRICT)
+    tsg.reduce_sum(tsg.F32, M, N, eager, N, esum)
+    torch.cuda.synchronize()
+    out = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+    osum = torch.zeros((1,), dtype=torch.float32, device=DEV)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            tsg.gemm(tsg.F32, M, N, K, dA, K, dB, N, out, N, tsg.STRICT, side.cuda_stream)
+            tsg.reduce_sum(tsg.F32, M, N, out, N, osum, 0, side.cuda_stream)
+    for rep in range(4):
+        out.fill_(-1.0)
+        osum.fill_(-1.0)
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager) and torch.equal(osum, esum), rep
+        # eager work of the program's own between replays, on the same workspace
+        tmp = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+        tsg.gemm(tsg.F32, M, N, K, dA, K, dB, N, tmp, N, tsg.STRICT)
+        torch.cuda.synchronize()
+        assert torch.equal(tmp, eager)
