@@ -47,6 +47,8 @@ def _c():
         lib.ref_threads.restype = ci
         lib.ref_gemm.argtypes = [ci, ci, i64, i64, i64, vp, i64, vp, i64, vp, vp]
         lib.ref_gemm.restype = None
+        lib.ref_gemm_transB.argtypes = [ci, ci, i64, i64, i64, vp, i64, vp, i64, vp, vp]
+        lib.ref_gemm_transB.restype = None
         lib.ref_conv2d_nhwc.argtypes = [ci] + [i64] * 11 + [vp, vp, vp, vp]
         lib.ref_conv2d_nhwc.restype = None
         lib.ref_conv2d_index_map.argtypes = [i64] * 10 + [vp]
@@ -70,12 +72,13 @@ def _operand(a):
     raise TypeError("operands are fp32 arrays or uint16 arrays of bfloat16 bit patterns")
 
 
-def gemm(A, B, *, trans_a: bool = False, with_s: bool = True):
-    """R = op(A).B in fp64 and S = |op(A)|.|B| (Fig. 7 with the batch index dropped).
+def gemm(A, B, *, trans_a: bool = False, trans_b: bool = False, with_s: bool = True):
+    """R = op(A).op(B) in fp64 and S = |op(A)|.|op(B)| (Fig. 7 with the batch index dropped).
 
     A is M x K row-major, or K x M when trans_a (the left operand is stored
-    transposed and read in place, Case Study 3).  B is K x N.  Both fp32, or both
-    bfloat16 bit patterns (uint16) whose exact values are multiplied in fp64.
+    transposed and read in place, Case Study 3).  B is K x N, or N x K when trans_b.
+    Both fp32, or both bfloat16 bit patterns (uint16) whose exact values are
+    multiplied in fp64.
     """
     A, ta = _operand(A)
     B, tb = _operand(B)
@@ -85,13 +88,14 @@ def gemm(A, B, *, trans_a: bool = False, with_s: bool = True):
         K, M = A.shape
     else:
         M, K = A.shape
-    if B.shape[0] != K:
+    if B.shape[1 if trans_b else 0] != K:
         raise ValueError("inner dimensions differ")
-    N = B.shape[1]
+    N = B.shape[0 if trans_b else 1]
     R = np.empty((M, N), dtype=np.float64)
     S = np.empty((M, N), dtype=np.float64) if with_s else None
-    _c().ref_gemm(ta, int(trans_a), M, N, K, A.ctypes.data, A.shape[1], B.ctypes.data, N,
-                  R.ctypes.data, S.ctypes.data if with_s else None)
+    fn = _c().ref_gemm_transB if trans_b else _c().ref_gemm
+    fn(ta, int(trans_a), M, N, K, A.ctypes.data, A.shape[1], B.ctypes.data, B.shape[1],
+       R.ctypes.data, S.ctypes.data if with_s else None)
     return (R, S) if with_s else R
 
 

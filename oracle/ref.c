@@ -81,6 +81,29 @@ void ref_gemm(int is_bf16, int trans_a, int64_t M, int64_t N, int64_t K,
 }
 
 /*
+ * The same product with the right operand stored transposed as well (B is N x K,
+ * row-major, and op(B)(k,j) = B[j*ldb + k] is read in place): the plain i, j, k loop.
+ */
+void ref_gemm_transB(int is_bf16, int trans_a, int64_t M, int64_t N, int64_t K,
+                     const void *A, int64_t lda, const void *B, int64_t ldb,
+                     double *R, double *S) {
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < M; ++i) {
+        for (int64_t j = 0; j < N; ++j) {
+            double acc = 0.0, mag = 0.0;
+            for (int64_t k = 0; k < K; ++k) {
+                const double a = load_a(A, is_bf16, trans_a ? k * lda + i : i * lda + k);
+                const double b = load_a(B, is_bf16, j * ldb + k);
+                acc += a * b;
+                mag += fabs(a) * fabs(b);
+            }
+            R[i * N + j] = acc;
+            if (S) S[i * N + j] = mag;
+        }
+    }
+}
+
+/*
  * Direct NHWC convolution.  x [N][H][W][Cin], w [KH][KW][Cin][Cout],
  * R,S [N][Ho][Wo][Cout] with Ho = (H + 2*ph - KH)/sh + 1 (floor), same for Wo.
  * A tap whose input coordinate falls in the zero padding is skipped: the padded

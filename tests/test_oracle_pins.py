@@ -368,3 +368,30 @@ def test_reduce_sum_pins():
     b = synth.f32_to_bf16_bits(x)
     sb, _ = oracle.reduce_sum(b)
     assert sb == float(np.sum(synth.bf16_bits_to_f32(b).astype(np.float64)))
+
+
+def test_transposed_right_operand_pins():
+    """op(B) = B^T read in place: against numpy's fp64 matmul of the explicit transpose,
+    the identities A.B^T = (B.A^T)^T and A^T.B^T = (B.A)^T, a one-hot probe that tells B^T from
+    B, and exact rationals on a tiny case."""
+    from fractions import Fraction
+    M, N, K = 13, 9, 21
+    A = _rand((M, K), 71)
+    Bt = _rand((N, K), 72, tid=1)
+    R, S = oracle.gemm(A, Bt, trans_b=True)
+    ref = A.astype(np.float64) @ Bt.astype(np.float64).T
+    assert np.max(np.abs(R - ref)) <= K * 2.0 ** -52 * np.max(S)
+    R2 = oracle.gemm(Bt, A, trans_b=True, with_s=False)            # B.A^T, N x M
+    assert np.max(np.abs(R - R2.T)) <= K * 2.0 ** -52 * np.max(S)
+    At = np.ascontiguousarray(A.T)                                   # K x M
+    R3 = oracle.gemm(At, Bt, trans_a=True, trans_b=True, with_s=False)
+    assert np.array_equal(R3, R)                                     # same products, same order
+    R4 = oracle.gemm(Bt, At, with_s=False)                           # B.A with B = Bt (N x K), A = At (K x M)
+    assert np.max(np.abs(R3 - R4.T)) <= K * 2.0 ** -52 * np.max(S)
+    hot = np.zeros((4, 5), np.float32); hot[2, 3] = 1.0              # op(B)(k=3, j=2) = 1
+    X = _rand((6, 5), 73)
+    assert np.array_equal(oracle.gemm(X, hot, trans_b=True, with_s=False)[:, 2], X[:, 3].astype(np.float64))
+    a = np.array([[1, 2], [3, 4]], np.float32); b = np.array([[5, 6], [7, 8]], np.float32)
+    want = [[sum(Fraction(int(a[i, k])) * Fraction(int(b[j, k])) for k in range(2)) for j in range(2)] for i in range(2)]
+    got = oracle.gemm(a, b, trans_b=True, with_s=False)
+    assert all(Fraction(got[i, j]) == want[i][j] for i in range(2) for j in range(2))
