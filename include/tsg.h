@@ -144,6 +144,18 @@ tsg_status tsg_gemm_batched(tsg_dtype dtype, int32_t trans_a, int64_t batch,
                             float *C, int64_t ldc, int64_t stride_c,
                             uint32_t flags, void *stream);
 
+/* The general form: either operand, or both, stored transposed and read in place (Case
+ * Study 3: transposes folded into a matmul that takes transposed operands).  trans_a: A is
+ * K x M (lda >= M); trans_b: B is N x K (ldb >= K).  Batched like tsg_gemm_batched.  A
+ * transposed B is served by the direct-to-LDS kernel forms only (sched 4, 5): a pinned config
+ * of another form is a silenceable failure and the library's default for the shape is used. */
+tsg_status tsg_gemm_trans(tsg_dtype dtype, int32_t trans_a, int32_t trans_b, int64_t batch,
+                          int64_t M, int64_t N, int64_t K,
+                          const void *A, int64_t lda, int64_t stride_a,
+                          const void *B, int64_t ldb, int64_t stride_b,
+                          float *C, int64_t ldc, int64_t stride_c,
+                          uint32_t flags, void *stream);
+
 /* y[N][Ho][Wo][Cout] = +-conv(x[N][H][W][Cin], w[KH][KW][Cin][Cout]) (+ y), zero
  * padding (pad_h, pad_w) never materialised; Ho = (H + 2*pad_h - KH)/stride_h + 1. */
 tsg_status tsg_conv2d_nhwc(tsg_dtype dtype, int64_t N, int64_t H, int64_t W, int64_t Cin,
@@ -262,6 +274,16 @@ tsg_status tsg_autotune_gemm_batched(tsg_dtype dtype, int32_t trans_a, int64_t b
                                      uint32_t flags, void *stream, int32_t iters,
                                      tsg_tile_config *best, float *best_ms,
                                      tsg_tune_record *log, int32_t log_cap, int32_t *n_log);
+
+/* The same search for the general form (tsg_gemm_trans). */
+tsg_status tsg_autotune_gemm_trans(tsg_dtype dtype, int32_t trans_a, int32_t trans_b, int64_t batch,
+                                   int64_t M, int64_t N, int64_t K,
+                                   const void *A, int64_t lda, int64_t stride_a,
+                                   const void *B, int64_t ldb, int64_t stride_b,
+                                   float *C, int64_t ldc, int64_t stride_c,
+                                   uint32_t flags, void *stream, int32_t iters,
+                                   tsg_tile_config *best, float *best_ms,
+                                   tsg_tune_record *log, int32_t log_cap, int32_t *n_log);
 
 tsg_status tsg_autotune_conv2d_nhwc(tsg_dtype dtype, int64_t N, int64_t H, int64_t W, int64_t Cin,
                                     int64_t Cout, int64_t KH, int64_t KW,

@@ -62,6 +62,7 @@ def _load():
         "tsg_gemm": [i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, u32, vp],
         "tsg_gemm_transA": [i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, u32, vp],
         "tsg_gemm_batched": [i32, i32, i64, i64, i64, i64, vp, i64, i64, vp, i64, i64, vp, i64, i64, u32, vp],
+        "tsg_gemm_trans": [i32, i32, i32, i64, i64, i64, i64, vp, i64, i64, vp, i64, i64, vp, i64, i64, u32, vp],
         "tsg_conv2d_nhwc": [i32] + [i64] * 11 + [vp, vp, vp, u32, vp],
         "tsg_conv2d_nhwc_window": [i32] + [i64] * 11 + [vp, vp, vp, i64, i64, i64, u32, vp],
         "tsg_reduce_sum": [i32, i64, i64, vp, i64, vp, u32, vp],
@@ -81,6 +82,9 @@ def _load():
         "tsg_autotune_gemm_batched": [i32, i32, i64, i64, i64, i64, vp, i64, i64, vp, i64, i64, vp, i64, i64, u32,
                                       vp, i32, cfgp, ctypes.POINTER(ctypes.c_float),
                                       ctypes.POINTER(TuneRecord), i32, ctypes.POINTER(i32)],
+        "tsg_autotune_gemm_trans": [i32, i32, i32, i64, i64, i64, i64, vp, i64, i64, vp, i64, i64, vp, i64, i64, u32,
+                                    vp, i32, cfgp, ctypes.POINTER(ctypes.c_float),
+                                    ctypes.POINTER(TuneRecord), i32, ctypes.POINTER(i32)],
         "tsg_autotune_conv2d_nhwc": [i32] + [i64] * 11 + [vp, vp, vp, u32, vp, i32,
                                                           cfgp, ctypes.POINTER(ctypes.c_float),
                                                           ctypes.POINTER(TuneRecord), i32, ctypes.POINTER(i32)],
@@ -102,7 +106,7 @@ def _load():
 
 _lib = _load()
 
-EXPORTS = ("tsg_gemm", "tsg_gemm_transA", "tsg_gemm_batched", "tsg_conv2d_nhwc", "tsg_conv2d_nhwc_window",
+EXPORTS = ("tsg_gemm", "tsg_gemm_transA", "tsg_gemm_batched", "tsg_gemm_trans", "tsg_autotune_gemm_trans", "tsg_conv2d_nhwc", "tsg_conv2d_nhwc_window",
            "tsg_reduce_sum", "tsg_split",
            "tsg_tile_config_count", "tsg_tile_config_enum", "tsg_tile_config_check",
            "tsg_tile_config_set", "tsg_tile_config_get", "tsg_last_launch", "tsg_workspace_set",
@@ -162,6 +166,13 @@ def gemm_batched(dtype, trans_a, batch, M, N, K, A, lda, stride_a, B, ldb, strid
     _check(_lib.tsg_gemm_batched(dtype, int(bool(trans_a)), batch, M, N, K, _ptr(A), lda, stride_a,
                                  _ptr(B), ldb, stride_b, _ptr(C), ldc, stride_c, flags, _stream(stream)),
            "tsg_gemm_batched")
+
+
+def gemm_trans(dtype, trans_a, trans_b, batch, M, N, K, A, lda, stride_a, B, ldb, stride_b, C, ldc, stride_c,
+               flags=0, stream=None):
+    _check(_lib.tsg_gemm_trans(dtype, int(bool(trans_a)), int(bool(trans_b)), batch, M, N, K, _ptr(A), lda, stride_a,
+                               _ptr(B), ldb, stride_b, _ptr(C), ldc, stride_c, flags, _stream(stream)),
+           "tsg_gemm_trans")
 
 
 def conv2d_nhwc(dtype, N, H, W, Cin, Cout, KH, KW, stride_h, stride_w, pad_h, pad_w, x, w, y,
@@ -273,6 +284,16 @@ def autotune_gemm_batched(dtype, trans_a, batch, M, N, K, A, lda, stride_a, B, l
                                           _ptr(B), ldb, stride_b, _ptr(C), ldc, stride_c, flags, _stream(stream),
                                           iters, ctypes.byref(best), ctypes.byref(ms), log, log_cap,
                                           ctypes.byref(n)), "tsg_autotune_gemm_batched")
+    return best, float(ms.value), [log[i] for i in range(n.value)]
+
+
+def autotune_gemm_trans(dtype, trans_a, trans_b, batch, M, N, K, A, lda, stride_a, B, ldb, stride_b, C, ldc,
+                        stride_c, flags=0, stream=None, iters=5, log_cap=512):
+    best, ms, log, n = _tune_out(log_cap)
+    _check(_lib.tsg_autotune_gemm_trans(dtype, int(bool(trans_a)), int(bool(trans_b)), batch, M, N, K, _ptr(A), lda,
+                                        stride_a, _ptr(B), ldb, stride_b, _ptr(C), ldc, stride_c, flags,
+                                        _stream(stream), iters, ctypes.byref(best), ctypes.byref(ms), log, log_cap,
+                                        ctypes.byref(n)), "tsg_autotune_gemm_trans")
     return best, float(ms.value), [log[i] for i in range(n.value)]
 
 

@@ -17,6 +17,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtsg.so")
 SOURCES = ["api.cpp", "gemm_f32_row.hip", "gemm_f32_col.hip", "gemm_f32_conv.hip",
+           "gemm_f32_row_bt.hip", "gemm_f32_col_bt.hip", "gemm_bf16_row_bt.hip", "gemm_bf16_col_bt.hip",
            "gemm_bf16_row.hip", "gemm_bf16_col.hip", "gemm_bf16_conv.hip", "reduce.hip"]
 HEADERS = [os.path.join(CSRC, h) for h in ("tsg_internal.h", "gemm_f32_kernel.h", "gemm_bf16_kernel.h")] + \
           [os.path.join(HERE, "..", "include", "tsg.h")]
@@ -54,7 +55,7 @@ def _compile(src: str, force: bool) -> str:
 
 def build(force: bool = False) -> str:
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
+    with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         objs = list(ex.map(lambda s: _compile(s, force), SOURCES))
     if force or _stale(LIB, objs):
         cmd = [_hipcc(), "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs

@@ -27,6 +27,7 @@ struct Problem {
     float* C;
     int64_t lda, ldb, ldc;
     int64_t stride_a = 0, stride_b = 0, stride_c = 0;
+    bool trans_b = false;   // B stored N x K (direct-to-LDS kernel forms only)
     uint32_t flags;
     // convolution geometry
     int64_t H = 0, W = 0, Cin = 0, Ho = 0, Wo = 0, KH = 0, KW = 0, sh = 1, sw = 1, ph = 0, pw = 0;
@@ -127,7 +128,8 @@ bool split_allowed(const KernelEntry& e, int split, int64_t batch, int64_t M, in
 }
 
 // The default config of a shape: the model's minimum over instantiated tiles and splits.
-tsg_tile_config heuristic(tsg_dtype dt, int64_t batch, int64_t M, int64_t N, int64_t K, int64_t ws_bytes) {
+tsg_tile_config heuristic(tsg_dtype dt, int64_t batch, int64_t M, int64_t N, int64_t K, int64_t ws_bytes,
+                          bool direct_only = false) {
     int n = 0;
     const KernelEntry* t = kernels(dt, &n);
     double best = 0;
@@ -135,6 +137,7 @@ tsg_tile_config heuristic(tsg_dtype dt, int64_t batch, int64_t M, int64_t N, int
     bool first = true;
     for (int i = 0; i < n; ++i)
         for (int split = 1; split <= kMaxSplit; split *= 2) {
+            if (direct_only && t[i].sched < 4) break;
             if (!split_allowed(t[i], split, batch, M, N, K, ws_bytes)) break;
             const double est = model_cycles(dt, t[i], split, batch, M, N, K);
             if (first || est < best * 0.999) { best = est; best_i = i; best_split = split; first = false; }
@@ -187,6 +190,7 @@ tsg_status make_plan(const Problem& p, const tsg_tile_config& cfg, int alternati
     if (!e) return TSG_E_SILENCEABLE;
     if (!vec_legal(p, cfg.vec)) return TSG_E_SILENCEABLE;
     if (e->sched >= 4 && cfg.vec == 1) return TSG_E_SILENCEABLE;   // direct-to-LDS forms move 16-byte chunks
+    if (p.trans_b && e->sched < 4) return TSG_E_SILENCEABLE;       // a transposed B exists in those forms only
     if (cfg.raster != 0 && cfg.raster != 1) return TSG_E_SILENCEABLE;
     if (cfg.split_k < 1 || cfg.split_k > kMaxSplit) return TSG_E_SILENCEABLE;
 
@@ -240,7 +244,8 @@ tsg_status make_plan(const Problem& p, const tsg_tile_config& cfg, int alternati
 }
 
 tsg_status enqueue(const Problem& p, const Plan& pl, hipStream_t s) {
-    const int amode = p.op == TSG_OP_GEMM ? tsg::A_ROW : p.op == TSG_OP_GEMM_TRANSA ? tsg::A_COL : tsg::A_CONV;
+    const int amode = p.op == TSG_OP_GEMM ? (p.trans_b ? tsg::A_ROW_BT : tsg::A_ROW)
+                      : p.op == TSG_OP_GEMM_TRANSA ? (p.trans_b ? tsg::A_COL_BT : tsg::A_COL) : tsg::A_CONV;
     int n = 0;
     const int tile = (int)(pl.entry - kernels(p.dtype, &n));
     const hipError_t e = pl.entry->launch(tile, amode, pl.variant, pl.args, (int)p.batch, s);
@@ -265,14 +270,14 @@ tsg_status run(const Problem& p, hipStream_t s) {
         std::lock_guard<std::mutex> g(g_mu);
         ws_bytes = g_ws ? g_ws_bytes : 0;
     }
-    const tsg_tile_config heur = heuristic(p.dtype, p.batch, p.M, p.N, p.K, ws_bytes);
+    const tsg_tile_config heur = heuristic(p.dtype, p.batch, p.M, p.N, p.K, ws_bytes, p.trans_b);
     Plan pl;
     if (pinned) {
         if (make_plan(p, pin, 0, &pl) == TSG_OK) return enqueue(p, pl, s);
         if (p.flags & TSG_STRICT) return TSG_E_SILENCEABLE;
     }
     if (make_plan(p, heur, 1, &pl) == TSG_OK) return enqueue(p, pl, s);
-    if (p.flags & TSG_STRICT) return TSG_E_SILENCEABLE;
+    if ((p.flags & TSG_STRICT) || p.trans_b) return TSG_E_SILENCEABLE;   // no scalar form with a transposed B
     // last alternative: scalar accesses, which have no precondition.  The direct-to-LDS forms
     // have no scalar variant, so the same tile is taken in a register-staged form (or, if
     // that one is not instantiated, the smallest tile of the table).
@@ -298,12 +303,13 @@ tsg_status run(const Problem& p, hipStream_t s) {
 bool fits_i32(int64_t v) { return v >= 0 && v <= 0x7fffffff; }
 
 tsg_status check_gemm(int dtype, int64_t batch, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
-                      const void* B, int64_t ldb, const float* C, int64_t ldc, bool trans_a, uint32_t flags) {
+                      const void* B, int64_t ldb, const float* C, int64_t ldc, bool trans_a, uint32_t flags,
+                      bool trans_b = false) {
     if (!valid_dtype(dtype)) return TSG_E_INVALID;
     if (!A || !B || !C) return TSG_E_INVALID;
     if (M <= 0 || N <= 0 || K <= 0 || batch <= 0) return TSG_E_INVALID;
     if (!fits_i32(M) || !fits_i32(N) || !fits_i32(K)) return TSG_E_INVALID;
-    if (lda < (trans_a ? M : K) || ldb < N || ldc < N) return TSG_E_INVALID;
+    if (lda < (trans_a ? M : K) || ldb < (trans_b ? K : N) || ldc < N) return TSG_E_INVALID;
     if (flags & ~(uint32_t)(TSG_NEGATE | TSG_ACCUMULATE | TSG_STRICT)) return TSG_E_INVALID;
     return TSG_OK;
 }
@@ -470,11 +476,10 @@ tsg_status tsg_split(int64_t ub, int64_t d, int64_t* main_part, int64_t* rest, i
     return TSG_OK;
 }
 
-tsg_status tsg_gemm_batched(tsg_dtype dtype, int32_t trans_a, int64_t batch, int64_t M, int64_t N, int64_t K,
-                            const void* A, int64_t lda, int64_t stride_a, const void* B, int64_t ldb,
-                            int64_t stride_b, float* C, int64_t ldc, int64_t stride_c, uint32_t flags,
-                            void* stream) {
-    const tsg_status v = check_gemm(dtype, batch, M, N, K, A, lda, B, ldb, C, ldc, trans_a != 0, flags);
+tsg_status tsg_gemm_trans(tsg_dtype dtype, int32_t trans_a, int32_t trans_b, int64_t batch, int64_t M, int64_t N,
+                          int64_t K, const void* A, int64_t lda, int64_t stride_a, const void* B, int64_t ldb,
+                          int64_t stride_b, float* C, int64_t ldc, int64_t stride_c, uint32_t flags, void* stream) {
+    const tsg_status v = check_gemm(dtype, batch, M, N, K, A, lda, B, ldb, C, ldc, trans_a != 0, flags, trans_b != 0);
     if (v != TSG_OK) return v;
     if (stride_a < 0 || stride_b < 0 || stride_c < 0) return TSG_E_INVALID;
     if (batch > 1 && stride_c < (M - 1) * ldc + N) return TSG_E_INVALID;   // outputs must not overlap
@@ -486,8 +491,17 @@ tsg_status tsg_gemm_batched(tsg_dtype dtype, int32_t trans_a, int64_t batch, int
     p.A = A; p.B = B; p.C = C;
     p.lda = lda; p.ldb = ldb; p.ldc = ldc;
     p.stride_a = stride_a; p.stride_b = stride_b; p.stride_c = stride_c;
+    p.trans_b = trans_b != 0;
     p.flags = flags;
     return run(p, (hipStream_t)stream);
+}
+
+tsg_status tsg_gemm_batched(tsg_dtype dtype, int32_t trans_a, int64_t batch, int64_t M, int64_t N, int64_t K,
+                            const void* A, int64_t lda, int64_t stride_a, const void* B, int64_t ldb,
+                            int64_t stride_b, float* C, int64_t ldc, int64_t stride_c, uint32_t flags,
+                            void* stream) {
+    return tsg_gemm_trans(dtype, trans_a, 0, batch, M, N, K, A, lda, stride_a, B, ldb, stride_b, C, ldc, stride_c,
+                          flags, stream);
 }
 
 tsg_status tsg_gemm(tsg_dtype dtype, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda, const void* B,
@@ -647,16 +661,17 @@ tsg_status tsg_gemm_index_map(int32_t trans_a, int64_t M, int64_t K, int64_t lda
     return TSG_OK;
 }
 
-tsg_status tsg_autotune_gemm_batched(tsg_dtype dtype, int32_t trans_a, int64_t batch, int64_t M, int64_t N,
-                                     int64_t K, const void* A, int64_t lda, int64_t stride_a, const void* B,
+tsg_status tsg_autotune_gemm_trans(tsg_dtype dtype, int32_t trans_a, int32_t trans_b, int64_t batch, int64_t M,
+                                   int64_t N, int64_t K, const void* A, int64_t lda, int64_t stride_a, const void* B,
                                      int64_t ldb, int64_t stride_b, float* C, int64_t ldc, int64_t stride_c,
                                      uint32_t flags, void* stream, int32_t iters, tsg_tile_config* best,
                                      float* best_ms, tsg_tune_record* log, int32_t log_cap, int32_t* n_log) {
-    const tsg_status v = check_gemm(dtype, batch, M, N, K, A, lda, B, ldb, C, ldc, trans_a != 0, flags);
+    const tsg_status v = check_gemm(dtype, batch, M, N, K, A, lda, B, ldb, C, ldc, trans_a != 0, flags, trans_b != 0);
     if (v != TSG_OK) return v;
     if (stride_a < 0 || stride_b < 0 || stride_c < 0) return TSG_E_INVALID;
     if (batch > 1 && stride_c < (M - 1) * ldc + N) return TSG_E_INVALID;
     Problem p;
+    p.trans_b = trans_b != 0;
     p.op = trans_a ? TSG_OP_GEMM_TRANSA : TSG_OP_GEMM;
     p.dtype = dtype;
     p.batch = batch;
@@ -672,8 +687,17 @@ tsg_status tsg_autotune_gemm(tsg_dtype dtype, int32_t trans_a, int64_t M, int64_
                              int64_t lda, const void* B, int64_t ldb, float* C, int64_t ldc, uint32_t flags,
                              void* stream, int32_t iters, tsg_tile_config* best, float* best_ms,
                              tsg_tune_record* log, int32_t log_cap, int32_t* n_log) {
-    return tsg_autotune_gemm_batched(dtype, trans_a, 1, M, N, K, A, lda, 0, B, ldb, 0, C, ldc, 0, flags, stream,
-                                     iters, best, best_ms, log, log_cap, n_log);
+    return tsg_autotune_gemm_trans(dtype, trans_a, 0, 1, M, N, K, A, lda, 0, B, ldb, 0, C, ldc, 0, flags, stream,
+                                   iters, best, best_ms, log, log_cap, n_log);
+}
+
+tsg_status tsg_autotune_gemm_batched(tsg_dtype dtype, int32_t trans_a, int64_t batch, int64_t M, int64_t N,
+                                     int64_t K, const void* A, int64_t lda, int64_t stride_a, const void* B,
+                                     int64_t ldb, int64_t stride_b, float* C, int64_t ldc, int64_t stride_c,
+                                     uint32_t flags, void* stream, int32_t iters, tsg_tile_config* best,
+                                     float* best_ms, tsg_tune_record* log, int32_t log_cap, int32_t* n_log) {
+    return tsg_autotune_gemm_trans(dtype, trans_a, 0, batch, M, N, K, A, lda, stride_a, B, ldb, stride_b, C, ldc,
+                                   stride_c, flags, stream, iters, best, best_ms, log, log_cap, n_log);
 }
 
 tsg_status tsg_autotune_conv2d_nhwc(tsg_dtype dtype, int64_t N, int64_t H, int64_t W, int64_t Cin, int64_t Cout,

@@ -429,8 +429,11 @@ struct LdsDirect {
     static constexpr int BYTES = STAGES * STAGE * 2;
 };
 
-template <class T, int AMODE, bool EDGE>
+template <class T, int MODE, bool EDGE>
 __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const KArgs p) {
+    // address mode of the left operand, and whether the right one is stored transposed (N x K)
+    constexpr int AMODE = MODE == A_ROW_BT ? A_ROW : MODE == A_COL_BT ? A_COL : MODE;
+    constexpr bool B_KMAJ = MODE == A_ROW_BT || MODE == A_COL_BT;
     constexpr int BM = T::BM, BN = T::BN, BK = T::BK, NT = T::NT, MI = T::MI, NI = T::NI;
     using L = LdsDirect<T>;
     constexpr int STAGES = L::STAGES, D = STAGES - 1;
@@ -438,13 +441,16 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
     constexpr int A_CPR = A_KMAJ ? BK / 8 : BM / 8;   // 16-byte chunks per stored row of A
     constexpr int A_ROWS = A_KMAJ ? BM : BK;
     constexpr int A_RPP = NT / A_CPR, PA = A_ROWS / A_RPP;
-    constexpr int B_CPR = BN / 8, B_RPP = NT / B_CPR, PB = BK / B_RPP;
+    constexpr int B_CPR = B_KMAJ ? BK / 8 : BN / 8;
+    constexpr int B_ROWS = B_KMAJ ? BN : BK;
+    constexpr int B_RPP = NT / B_CPR, PB = B_ROWS / B_RPP;
     constexpr int LPT = PA + PB;
     static_assert(NT % A_CPR == 0 && A_ROWS % A_RPP == 0 && PA >= 1, "A staging shape");
-    static_assert(NT % B_CPR == 0 && BK % B_RPP == 0 && PB >= 1, "B staging shape");
+    static_assert(NT % B_CPR == 0 && B_ROWS % B_RPP == 0 && PB >= 1, "B staging shape");
     static_assert((D - 1) * LPT <= 63, "outstanding-load counter range");
-    static_assert(B_CPR >= 8 && (A_KMAJ || A_CPR >= 8), "the [k][j] swizzle permutes chunks in groups of eight");
-    constexpr int SW_MOD = A_CPR < 16 ? A_CPR : 16, SW_DIV = 16 / SW_MOD;
+    static_assert((B_KMAJ || B_CPR >= 8) && (A_KMAJ || A_CPR >= 8), "the [k][j] swizzle permutes chunks in groups of eight");
+    constexpr int K_CPR = BK / 8;   // chunks per row of a [row][k] tile
+    constexpr int SW_MOD = K_CPR < 16 ? K_CPR : 16, SW_DIV = 16 / SW_MOD;
     extern __shared__ __attribute__((aligned(16))) u16 smem16[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -468,10 +474,10 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
     // leading steps of this workgroup whose chunks are all whole (inside or outside)
     int n_direct = nk;
     if constexpr (EDGE) {
-        bool whole_tile = !((p.N & 7) && n0 + BN > p.N);
+        bool whole_tile = !(!B_KMAJ && (p.N & 7) && n0 + BN > p.N);
         if (AMODE == A_COL && (p.M & 7) && m0 + BM > p.M) whole_tile = false;
         if (!whole_tile) n_direct = 0;
-        else if (AMODE == A_ROW && (p.K & 7)) n_direct = max(0, min(nk, p.k_full - kb));
+        else if ((AMODE == A_ROW || B_KMAJ) && (p.K & 7)) n_direct = max(0, min(nk, p.k_full - kb));
     }
 
     const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) u16*)smem16 +
@@ -519,13 +525,21 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
         cs_kw = tap - cs_kh * p.KW;
     }
     const u16* b_src[PB];
+    int b_k[PB];          // k offset of the chunk inside a step
     bool b_in[PB];
 #pragma unroll
     for (int q = 0; q < PB; ++q) {
-        const int krow = b_r + q * B_RPP;
-        const int nc = (b_cp ^ swz_j(krow)) * 8;
-        b_in[q] = !EDGE || n0 + nc < p.N;
-        b_src[q] = B + (long long)krow * p.ldb + n0 + nc;
+        const int row = b_r + q * B_RPP;
+        if constexpr (B_KMAJ) {
+            b_k[q] = (b_cp ^ swz_k(row)) * 8;
+            b_in[q] = !EDGE || n0 + row < p.N;
+            b_src[q] = B + (long long)(n0 + row) * p.ldb + b_k[q];
+        } else {
+            const int nc = (b_cp ^ swz_j(row)) * 8;
+            b_k[q] = row;
+            b_in[q] = !EDGE || n0 + nc < p.N;
+            b_src[q] = B + (long long)row * p.ldb + n0 + nc;
+        }
     }
 
     auto issue_direct = [&](int kt, int stage) {
@@ -558,8 +572,8 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
         }
 #pragma unroll
         for (int q = 0; q < PB; ++q) {
-            const bool in = b_in[q] && (!EDGE || k0 + b_r + q * B_RPP < p.K);
-            const u16* src = in ? b_src[q] + (long long)k0 * p.ldb : g_zero_chunk;
+            const bool in = b_in[q] && (!EDGE || k0 + b_k[q] < p.K);
+            const u16* src = in ? b_src[q] + (B_KMAJ ? (long long)k0 : (long long)k0 * p.ldb) : g_zero_chunk;
             load_to_lds16(src, bs + (unsigned)(q * NT) * 16u);
         }
     };
@@ -593,12 +607,17 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
         }
 #pragma unroll
         for (int q = 0; q < PB; ++q) {
-            const int krow = b_r + q * B_RPP, k = k0 + krow;
+            const int row = b_r + q * B_RPP;
             u16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const int n = n0 + (b_cp ^ swz_j(krow)) * 8 + e;
-                if (k < p.K && n < p.N) v[e] = B[(long long)k * p.ldb + n];
+                if constexpr (B_KMAJ) {
+                    const int n = n0 + row, k = k0 + b_k[q] + e;
+                    if (n < p.N && k < p.K) v[e] = B[(long long)n * p.ldb + k];
+                } else {
+                    const int k = k0 + row, n = n0 + (b_cp ^ swz_j(row)) * 8 + e;
+                    if (k < p.K && n < p.N) v[e] = B[(long long)k * p.ldb + n];
+                }
             }
             *(u16x8*)(Bs + (q * NT + tid) * 8) = v;
         }
@@ -627,6 +646,9 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
     int a_row_off[MI];
 #pragma unroll
     for (int i = 0; i < MI; ++i) a_row_off[i] = (wm0 + i * 32 + li) * BK;
+    int b_row_off[NI];   // the same for a k-contiguous B, whose rows are columns of C
+#pragma unroll
+    for (int j = 0; j < NI; ++j) b_row_off[j] = (wn0 + j * 32 + li) * BK;
     const int a_x = lh ^ swz_k(li);
     // [k][j] fragment by transposing reads: lane s of a 16-lane group points at row
     // 8 lh + s / 4 (and that row + 4) of the k step, columns 16 (lane / 16 % 2) + 4 (s % 4) of the block
@@ -671,8 +693,8 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
             load_to_lds16(src, as + (unsigned)(q * NT) * 16u);
         } else {
             const int q = x - PA;
-            const bool in = b_in[q] && (!EDGE || k0 + b_r + q * B_RPP < p.K);
-            const u16* src = in ? b_src[q] + (long long)k0 * p.ldb : g_zero_chunk;
+            const bool in = b_in[q] && (!EDGE || k0 + b_k[q] < p.K);
+            const u16* src = in ? b_src[q] + (B_KMAJ ? (long long)k0 : (long long)k0 * p.ldb) : g_zero_chunk;
             load_to_lds16(src, bs + (unsigned)(q * NT) * 16u);
         }
     };
@@ -695,9 +717,9 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
     // read returns half a fragment (4 values of k), so those operands are kept as two halves.
     constexpr int G = BK / 16;
     static_assert(G % 2 == 0, "the fragment double buffer alternates per group across steps");
-    constexpr int NFRAG = (A_KMAJ ? MI : 2 * MI) + 2 * NI;
+    constexpr int NFRAG = (A_KMAJ ? MI : 2 * MI) + (B_KMAJ ? NI : 2 * NI);
     constexpr int NM = MI * NI;
-    bf16x8 af[2][MI];
+    bf16x8 af[2][MI], bfull[2][NI];
     bf16x4 ah[2][MI][2], bh[2][NI][2];
     auto read_half = [&](const u16* t, int ld, int k, int col, int h) -> bf16x4 {
         const int c = col + tr_col;
@@ -720,7 +742,8 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
             }
             x -= 2 * MI;
         }
-        bh[g & 1][x >> 1][x & 1] = read_half(Bs, BN, g * 16, wn0 + (x >> 1) * 32, x & 1);
+        if constexpr (B_KMAJ) bfull[g & 1][x] = *(const bf16x8*)(Bs + b_row_off[x] + (((2 * g) ^ a_x) << 3));
+        else bh[g & 1][x >> 1][x & 1] = read_half(Bs, BN, g * 16, wn0 + (x >> 1) * 32, x & 1);
     };
 
     // ---- ring, as in the fp32 kernels: the one barrier of a step sits before its last k group
@@ -751,7 +774,9 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
                 bf16x8 a;
                 if constexpr (A_KMAJ) a = af[g & 1][i];
                 else a = __builtin_shufflevector(ah[g & 1][i][0], ah[g & 1][i][1], 0, 1, 2, 3, 4, 5, 6, 7);
-                const bf16x8 b = __builtin_shufflevector(bh[g & 1][j][0], bh[g & 1][j][1], 0, 1, 2, 3, 4, 5, 6, 7);
+                bf16x8 b;
+                if constexpr (B_KMAJ) b = bfull[g & 1][j];
+                else b = __builtin_shufflevector(bh[g & 1][j][0], bh[g & 1][j][1], 0, 1, 2, 3, 4, 5, 6, 7);
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i][j], 0, 0, 0);
 #pragma unroll
                 for (int e = m * PER; e < (m + 1) * PER && e < NX; ++e) {
@@ -777,7 +802,9 @@ hipError_t launch_mode(int variant, const KArgs& a, int batch, hipStream_t s) {
     const dim3 grid(a.tiles_m * a.tiles_n * a.split_k, batch, 1), block(T::NT, 1, 1);
     void (*fn)(const KArgs) = nullptr;
     int bytes;
-    if constexpr (T::SCHED >= 4) {
+    if constexpr ((AMODE == A_ROW_BT || AMODE == A_COL_BT) && T::SCHED < 4) {
+        return hipErrorInvalidValue;   // a transposed right operand exists in the direct-to-LDS forms only
+    } else if constexpr (T::SCHED >= 4) {
         if (variant == 2) return hipErrorInvalidValue;   // whole 16-byte chunks only
         bytes = LdsDirect<T>::BYTES;
         fn = variant == 0 ? gemm_bf16_direct_kernel<T, AMODE, false> : gemm_bf16_direct_kernel<T, AMODE, true>;
@@ -838,3 +865,7 @@ hipError_t launch_mode(int variant, const KArgs& a, int batch, hipStream_t s) {
     if (tile == idx++) return launch_mode<Tile<bm, bn, bk, wm, wn, mw, sc>, A_COL>(variant, a, batch, s);
 #define TSG_BF16_CASE_A_CONV(bm, bn, bk, wm, wn, mw, sc) \
     if (tile == idx++) return launch_mode<Tile<bm, bn, bk, wm, wn, mw, sc>, A_CONV>(variant, a, batch, s);
+#define TSG_BF16_CASE_A_ROW_BT(bm, bn, bk, wm, wn, mw, sc) \
+    if (tile == idx++) return launch_mode<Tile<bm, bn, bk, wm, wn, mw, sc>, A_ROW_BT>(variant, a, batch, s);
+#define TSG_BF16_CASE_A_COL_BT(bm, bn, bk, wm, wn, mw, sc) \
+    if (tile == idx++) return launch_mode<Tile<bm, bn, bk, wm, wn, mw, sc>, A_COL_BT>(variant, a, batch, s);

@@ -6,12 +6,16 @@ TSG_BF16_DEFINE_MODE(launch_bf16_row, A_ROW)
 namespace tsg {
 hipError_t launch_bf16_col(int tile, int variant, const KArgs& a, int batch, hipStream_t s);
 hipError_t launch_bf16_conv(int tile, int variant, const KArgs& a, int batch, hipStream_t s);
+hipError_t launch_bf16_row_bt(int tile, int variant, const KArgs& a, int batch, hipStream_t s);
+hipError_t launch_bf16_col_bt(int tile, int variant, const KArgs& a, int batch, hipStream_t s);
 
 namespace {
 hipError_t launch_any(int tile, int amode, int variant, const KArgs& a, int batch, hipStream_t s) {
     switch (amode) {
         case A_ROW: return launch_bf16_row(tile, variant, a, batch, s);
         case A_COL: return launch_bf16_col(tile, variant, a, batch, s);
+        case A_ROW_BT: return launch_bf16_row_bt(tile, variant, a, batch, s);
+        case A_COL_BT: return launch_bf16_col_bt(tile, variant, a, batch, s);
         default: return launch_bf16_conv(tile, variant, a, batch, s);
     }
 }

@@ -580,8 +580,11 @@ struct LdsDirect {
     static constexpr int BYTES = STAGES * STAGE * (int)sizeof(float);
 };
 
-template <class T, int AMODE, bool EDGE>
+template <class T, int MODE, bool EDGE>
 __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const KArgs p) {
+    // address mode of the left operand, and whether the right one is stored transposed (N x K)
+    constexpr int AMODE = MODE == A_ROW_BT ? A_ROW : MODE == A_COL_BT ? A_COL : MODE;
+    constexpr bool B_KMAJ = MODE == A_ROW_BT || MODE == A_COL_BT;
     constexpr int BM = T::BM, BN = T::BN, BK = T::BK, NT = T::NT, MI = T::MI, NI = T::NI;
     using L = LdsDirect<T, AMODE>;
     constexpr int STAGES = L::STAGES, D = STAGES - 1;
@@ -589,12 +592,15 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
     constexpr int A_CPR = A_KMAJ ? BK / 4 : BM / 4;   // 16-byte chunks per stored row of A
     constexpr int A_ROWS = A_KMAJ ? BM : BK;
     constexpr int A_RPP = NT / A_CPR, PA = A_ROWS / A_RPP;
-    constexpr int B_CPR = BN / 4, B_RPP = NT / B_CPR, PB = BK / B_RPP;
+    constexpr int B_CPR = B_KMAJ ? BK / 4 : BN / 4;   // and of B
+    constexpr int B_ROWS = B_KMAJ ? BN : BK;
+    constexpr int B_RPP = NT / B_CPR, PB = B_ROWS / B_RPP;
     constexpr int LPT = PA + PB;                       // direct loads per thread and step
     static_assert(NT % A_CPR == 0 && A_ROWS % A_RPP == 0 && PA >= 1, "A staging shape");
-    static_assert(NT % B_CPR == 0 && BK % B_RPP == 0 && PB >= 1, "B staging shape");
+    static_assert(NT % B_CPR == 0 && B_ROWS % B_RPP == 0 && PB >= 1, "B staging shape");
     static_assert((D - 1) * LPT <= 63, "outstanding-load counter range");
-    constexpr int SW_MOD = A_CPR < 16 ? A_CPR : 16, SW_DIV = 16 / SW_MOD;
+    constexpr int K_CPR = BK / 4;   // chunks per row of a k-contiguous tile
+    constexpr int SW_MOD = K_CPR < 16 ? K_CPR : 16, SW_DIV = 16 / SW_MOD;
     extern __shared__ __attribute__((aligned(16))) float smem[];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -618,10 +624,10 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
     // Leading steps of this workgroup whose chunks are all whole (inside or outside).
     int n_direct = nk;
     if constexpr (EDGE) {
-        bool whole_tile = !((p.N & 3) && n0 + BN > p.N);                       // rows of B are cut mid-chunk
+        bool whole_tile = !(!B_KMAJ && (p.N & 3) && n0 + BN > p.N);            // rows of B are cut mid-chunk
         if (AMODE == A_COL && (p.M & 3) && m0 + BM > p.M) whole_tile = false;  // so are rows of A^T
         if (!whole_tile) n_direct = 0;
-        else if (AMODE == A_ROW && (p.K & 3)) n_direct = max(0, min(nk, p.k_full - kb));
+        else if ((AMODE == A_ROW || B_KMAJ) && (p.K & 3)) n_direct = max(0, min(nk, p.k_full - kb));
     }
 
     // LDS byte address of this wave's 1 KiB slice of pass 0 of stage 0 (wave-uniform)
@@ -629,7 +635,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
                           (unsigned)__builtin_amdgcn_readfirstlane(tid & ~63) * 16u;
     const int a_r = tid / A_CPR, a_cp = tid % A_CPR;
     const int b_r = tid / B_CPR, b_cp = tid % B_CPR;
-    auto swz = [](int row) -> int { return A_KMAJ ? (row / SW_DIV) % SW_MOD : 0; };
+    auto swz = [](int row) -> int { return (row / SW_DIV) % SW_MOD; };   // k-contiguous tiles only
 
     // per-thread source of each of its chunks at k0 = 0
     const float* a_src[PA];
@@ -671,9 +677,21 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
         cs_kw = tap - cs_kh * p.KW;
     }
     const float* b_src[PB];
-    const bool b_in = !EDGE || n0 + b_cp * 4 < p.N;
+    int b_k[PB];          // k offset of the chunk inside a step: its row (B as K x N) or its swizzled chunk (N x K)
+    bool b_in[PB];        // the chunk's n range lies inside the operand
 #pragma unroll
-    for (int q = 0; q < PB; ++q) b_src[q] = B + (long long)(b_r + q * B_RPP) * p.ldb + n0 + b_cp * 4;
+    for (int q = 0; q < PB; ++q) {
+        const int row = b_r + q * B_RPP;
+        if constexpr (B_KMAJ) {
+            b_k[q] = (b_cp ^ swz(row)) * 4;
+            b_in[q] = !EDGE || n0 + row < p.N;
+            b_src[q] = B + (long long)(n0 + row) * p.ldb + b_k[q];
+        } else {
+            b_k[q] = row;
+            b_in[q] = !EDGE || n0 + b_cp * 4 < p.N;
+            b_src[q] = B + (long long)row * p.ldb + n0 + b_cp * 4;
+        }
+    }
 
     // ---- one tile into one stage, direct
     auto issue_direct = [&](int kt, int stage) {
@@ -706,8 +724,8 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
         }
 #pragma unroll
         for (int q = 0; q < PB; ++q) {
-            const bool in = b_in && (!EDGE || k0 + b_r + q * B_RPP < p.K);
-            const float* src = in ? b_src[q] + (long long)k0 * p.ldb : g_zero_chunk;
+            const bool in = b_in[q] && (!EDGE || k0 + b_k[q] < p.K);
+            const float* src = in ? b_src[q] + (B_KMAJ ? (long long)k0 : (long long)k0 * p.ldb) : g_zero_chunk;
             load_to_lds16(src, bs + (unsigned)(q * NT) * 16u);
         }
     };
@@ -742,12 +760,17 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
         }
 #pragma unroll
         for (int q = 0; q < PB; ++q) {
-            const int k = k0 + b_r + q * B_RPP;
+            const int row = b_r + q * B_RPP;
             f32x4 v = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                const int n = n0 + b_cp * 4 + e;
-                if (k < p.K && n < p.N) v[e] = B[(long long)k * p.ldb + n];
+                if constexpr (B_KMAJ) {
+                    const int n = n0 + row, k = k0 + b_k[q] + e;
+                    if (n < p.N && k < p.K) v[e] = B[(long long)n * p.ldb + k];
+                } else {
+                    const int k = k0 + row, n = n0 + b_cp * 4 + e;
+                    if (k < p.K && n < p.N) v[e] = B[(long long)k * p.ldb + n];
+                }
             }
             *(f32x4*)(Bs + (q * NT + tid) * 4) = v;
         }
@@ -776,6 +799,9 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
     int a_row_off[MI];   // float offset of the lane's row (k-contiguous A)
 #pragma unroll
     for (int i = 0; i < MI; ++i) a_row_off[i] = (wm0 + i * 32 + li) * BK;
+    int b_row_off[NI];   // the same for a k-contiguous B, whose rows are columns of C
+#pragma unroll
+    for (int j = 0; j < NI; ++j) b_row_off[j] = (wn0 + j * 32 + li) * BK;
     const int a_x = lh ^ swz(li);   // wm0 + 32 i is a multiple of 32, so the swizzle depends on li alone
 
     // ---- one direct load: the x-th of the LPT loads that bring a tile in
@@ -808,8 +834,8 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
             load_to_lds16(src, as + (unsigned)(q * NT) * 16u);
         } else {
             const int q = x - PA;
-            const bool in = b_in && (!EDGE || k0 + b_r + q * B_RPP < p.K);
-            const float* src = in ? b_src[q] + (long long)k0 * p.ldb : g_zero_chunk;
+            const bool in = b_in[q] && (!EDGE || k0 + b_k[q] < p.K);
+            const float* src = in ? b_src[q] + (B_KMAJ ? (long long)k0 : (long long)k0 * p.ldb) : g_zero_chunk;
             load_to_lds16(src, bs + (unsigned)(q * NT) * 16u);
         }
     };
@@ -833,7 +859,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
     // before it is multiplied, one LDS read after each MFMA
     constexpr int G = BK / 8;
     static_assert(G % 2 == 0, "the fragment double buffer alternates per group across steps");
-    constexpr int NFRAG = (A_KMAJ ? MI : 4 * MI) + 4 * NI;   // LDS reads of one group's fragments
+    constexpr int NFRAG = (A_KMAJ ? MI : 4 * MI) + (B_KMAJ ? NI : 4 * NI);   // LDS reads of one group's fragments
     constexpr int NM = 4 * MI * NI;                            // MFMAs of one group
     f32x4 af[2][MI], bf[2][NI];
     auto frag_read = [&](int stage, int g, int x) {
@@ -852,7 +878,8 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
             }
             x -= 4 * MI;
         }
-        bf[g & 1][x >> 2][x & 3] = Bs[(g * 8 + 4 * lh + (x & 3)) * BN + wn0 + (x >> 2) * 32 + li];
+        if constexpr (B_KMAJ) bf[g & 1][x] = *(const f32x4*)(Bs + b_row_off[x] + (((2 * g) ^ a_x) << 2));
+        else bf[g & 1][x >> 2][x & 3] = Bs[(g * 8 + 4 * lh + (x & 3)) * BN + wn0 + (x >> 2) * 32 + li];
     };
 
     // ---- ring.  Step kt is multiplied from stage kt % STAGES.  The one barrier of a step sits
@@ -910,7 +937,9 @@ hipError_t launch_mode(int variant, const KArgs& a, int batch, hipStream_t s) {
     const dim3 grid(a.tiles_m * a.tiles_n * a.split_k, batch, 1), block(T::NT, 1, 1);
     void (*fn)(const KArgs) = nullptr;
     int bytes;
-    if constexpr (T::SCHED >= 4) {
+    if constexpr ((AMODE == A_ROW_BT || AMODE == A_COL_BT) && T::SCHED < 4) {
+        return hipErrorInvalidValue;   // a transposed right operand exists in the direct-to-LDS forms only
+    } else if constexpr (T::SCHED >= 4) {
         // the direct-to-LDS forms move whole 16-byte chunks only
         if (variant == 2) return hipErrorInvalidValue;
         bytes = LdsDirect<T, AMODE>::BYTES;
@@ -990,3 +1019,7 @@ hipError_t launch_mode(int variant, const KArgs& a, int batch, hipStream_t s) {
     if (tile == idx++) return launch_mode<Tile<bm, bn, bk, wm, wn, mw, sc>, A_COL>(variant, a, batch, s);
 #define TSG_F32_CASE_A_CONV(bm, bn, bk, wm, wn, mw, sc) \
     if (tile == idx++) return launch_mode<Tile<bm, bn, bk, wm, wn, mw, sc>, A_CONV>(variant, a, batch, s);
+#define TSG_F32_CASE_A_ROW_BT(bm, bn, bk, wm, wn, mw, sc) \
+    if (tile == idx++) return launch_mode<Tile<bm, bn, bk, wm, wn, mw, sc>, A_ROW_BT>(variant, a, batch, s);
+#define TSG_F32_CASE_A_COL_BT(bm, bn, bk, wm, wn, mw, sc) \
+    if (tile == idx++) return launch_mode<Tile<bm, bn, bk, wm, wn, mw, sc>, A_COL_BT>(variant, a, batch, s);

@@ -6,12 +6,16 @@ TSG_F32_DEFINE_MODE(launch_f32_row, A_ROW)
 namespace tsg {
 hipError_t launch_f32_col(int tile, int variant, const KArgs& a, int batch, hipStream_t s);
 hipError_t launch_f32_conv(int tile, int variant, const KArgs& a, int batch, hipStream_t s);
+hipError_t launch_f32_row_bt(int tile, int variant, const KArgs& a, int batch, hipStream_t s);
+hipError_t launch_f32_col_bt(int tile, int variant, const KArgs& a, int batch, hipStream_t s);
 
 namespace {
 hipError_t launch_any(int tile, int amode, int variant, const KArgs& a, int batch, hipStream_t s) {
     switch (amode) {
         case A_ROW: return launch_f32_row(tile, variant, a, batch, s);
         case A_COL: return launch_f32_col(tile, variant, a, batch, s);
+        case A_ROW_BT: return launch_f32_row_bt(tile, variant, a, batch, s);
+        case A_COL_BT: return launch_f32_col_bt(tile, variant, a, batch, s);
         default: return launch_f32_conv(tile, variant, a, batch, s);
     }
 }

@@ -9,7 +9,11 @@ namespace tsg {
 enum AMode : int {
     A_ROW = 0,   // A stored M x K, k contiguous
     A_COL = 1,   // A stored K x M, i contiguous (transposed left operand read in place)
-    A_CONV = 2   // A is the implicit im2col matrix of an NHWC tensor, never materialised
+    A_CONV = 2,  // A is the implicit im2col matrix of an NHWC tensor, never materialised
+    // the same two GEMM forms with the right operand stored transposed too (B is N x K,
+    // k contiguous, read in place); only the direct-to-LDS kernel forms take these
+    A_ROW_BT = 3,
+    A_COL_BT = 4
 };
 
 // Kernel arguments, passed by value.

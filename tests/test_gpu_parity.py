@@ -421,6 +421,79 @@ def test_conv_into_window_of_larger_nhwc_tensor(dtype):
     assert e.value.status == tsg.E_INVALID
 
 
+@pytest.mark.parametrize("dtype", [tsg.F32, tsg.BF16_F32ACC])
+@pytest.mark.parametrize("trans_a", [False, True])
+def test_transposed_right_operand_bit_exact(dtype, trans_a, workspace):
+    """op(B) = B^T read in place (B stored N x K), alone and with a transposed A: integer
+    inputs on ragged shapes and odd leading dimensions, the library's default config, every
+    direct-to-LDS config pinned (with and without a split of k), and the flags."""
+    op = tsg.OP_GEMM_TRANSA if trans_a else tsg.OP_GEMM
+    for (M, N, K) in [(1, 1, 1), (5, 3, 2), (65, 63, 33), (196, 130, 461), (256, 384, 512), (130, 70, 2305)]:
+        A, _ = inputs(M, N, K, 81, "ints", trans_a, dtype)
+        Bt = inputs(N, 1, K, 82, "ints", False, dtype)[0]           # N x K
+        R = oracle.gemm(A, Bt, trans_a=trans_a, trans_b=True, with_s=False)
+        C0 = synth.small_ints(83, 2, M * N).reshape(M, N)
+        acols = A.shape[1]
+        for pad in (0, 1):
+            lda, ldb, ldc = acols + pad, K + 3 * pad, N + pad
+            Ah = np.zeros((A.shape[0], lda), A.dtype); Ah[:, :acols] = A
+            Bh = np.zeros((N, ldb), Bt.dtype); Bh[:, :K] = Bt
+            Ch = np.full((M, ldc), np.float32(-9.0)); Ch[:, :N] = C0
+            dC = dev(Ch)
+            tsg.gemm_trans(dtype, trans_a, True, 1, M, N, K, dev(Ah), lda, 0, dev(Bh), ldb, 0, dC, ldc, 0,
+                           tsg.ACCUMULATE | tsg.NEGATE)
+            torch.cuda.synchronize()
+            out = dC.cpu().numpy()
+            assert np.array_equal(out[:, :N].astype(np.float64), C0 - R), (M, N, K, pad)
+            assert np.all(out[:, N:] == np.float32(-9.0))
+            assert tsg.last_launch().config.sched >= 4
+    M, N, K = 196, 130, 461
+    A, _ = inputs(M, N, K, 84, "ints", trans_a, dtype)
+    Bt = inputs(N, 1, K, 85, "ints", False, dtype)[0]
+    R = oracle.gemm(A, Bt, trans_a=trans_a, trans_b=True, with_s=False)
+    dA, dB = dev(A), dev(Bt)
+    seen = 0
+    for i in range(tsg.tile_config_count(op, dtype)):
+        c = tsg.tile_config_enum(op, dtype, i)
+        if c.sched < 4 or c.vec == 1 or tsg.tile_config_check(op, dtype, M, N, K, c) != tsg.OK:
+            continue
+        tsg.tile_config_set(op, dtype, c)
+        dC = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+        tsg.gemm_trans(dtype, trans_a, True, 1, M, N, K, dA, A.shape[1], 0, dB, K, 0, dC, N, 0, tsg.STRICT)
+        torch.cuda.synchronize()
+        assert tsg.last_launch().config.as_dict() == c.as_dict()
+        assert np.array_equal(dC.cpu().numpy().astype(np.float64), R), c
+        seen += 1
+    assert seen >= 8
+    # a pinned register-staged config cannot serve a transposed B: silenceable under STRICT,
+    # the library's own choice otherwise
+    tsg.tile_config_set(op, dtype, tsg.TileConfig(bm=64, bn=64, bk=64, wm=32, wn=32, vec=(4 if dtype == tsg.F32 else 8),
+                                                  raster=0, sched=0, split_k=1))
+    dC = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+    with pytest.raises(tsg.SilenceableError):
+        tsg.gemm_trans(dtype, trans_a, True, 1, M, N, K, dA, A.shape[1], 0, dB, K, 0, dC, N, 0, tsg.STRICT)
+    tsg.gemm_trans(dtype, trans_a, True, 1, M, N, K, dA, A.shape[1], 0, dB, K, 0, dC, N, 0, 0)
+    torch.cuda.synchronize()
+    assert tsg.last_launch().alternative == 1
+    assert np.array_equal(dC.cpu().numpy().astype(np.float64), R)
+
+
+def test_transposed_right_operand_random_and_batched():
+    M, N, K, nb = 300, 200, 700, 3
+    for dtype in (tsg.F32, tsg.BF16_F32ACC):
+        a = [inputs(M, 1, K, 90 + b, "uniform", False, dtype)[0] for b in range(nb)]
+        bt = [inputs(N, 1, K, 95 + b, "uniform", False, dtype)[0] for b in range(nb)]
+        dA, dB = dev(np.stack(a)), dev(np.stack(bt))
+        dC = torch.zeros((nb, M, N), dtype=torch.float32, device=DEV)
+        tsg.gemm_trans(dtype, False, True, nb, M, N, K, dA, K, M * K, dB, K, N * K, dC, N, M * N, 0)
+        torch.cuda.synchronize()
+        out = dC.cpu().numpy()
+        for b in range(nb):
+            R, S = oracle.gemm(a[b], bt[b], trans_b=True)
+            nw, cw = oracle.errors(out[b], R, S)
+            assert nw <= TOL[dtype] and cw <= TOL[dtype], (dtype, b, nw, cw)
+
+
 # ------------------------------------------------------------------ the five workloads
 
 def test_config1_gemm_256():
