@@ -31,9 +31,13 @@ METRIC = "TFLOP/s and % of MI355X matrix peak, fp32 GEMM 4096^3 (1 GPU)"
 # An entry is reported only while the kernel sources still hash to the value it was taken
 # with and the launch uses the same tile config; otherwise `traffic` is null.
 TRAFFIC = {
-    3: [{"kernel_hash": "dbbcaf246699b5d0", "tile": {"bm": 256, "bn": 256, "bk": 16, "wm": 128, "wn": 64, "vec": 4, "raster": 1, "sched": 4, "split_k": 1}, "bytes": 470776061}],
-    5: [{"kernel_hash": "d19b3516f28975c8", "tile": {"bm": 256, "bn": 256, "bk": 32, "wm": 128, "wn": 64, "vec": 8, "raster": 0, "sched": 1, "split_k": 1}, "bytes": 1880929774}],
-    6: [{"kernel_hash": "dbbcaf246699b5d0", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 4}, "bytes": 87988647}],
+    1: [{"kernel_hash": "861e6eee1aef5252", "tile": {"bm": 64, "bn": 64, "bk": 64, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 4}, "bytes": 4156884}],
+    2: [{"kernel_hash": "861e6eee1aef5252", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 1}, "bytes": 42136441}],
+    3: [{"kernel_hash": "861e6eee1aef5252", "tile": {"bm": 256, "bn": 256, "bk": 16, "wm": 128, "wn": 64, "vec": 4, "raster": 1, "sched": 4, "split_k": 1}, "bytes": 472246403}],
+    4: [{"kernel_hash": "861e6eee1aef5252", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 1}, "bytes": 25449699}],
+    5: [{"kernel_hash": "4c90405d170f97e3", "tile": {"bm": 256, "bn": 256, "bk": 32, "wm": 128, "wn": 64, "vec": 8, "raster": 0, "sched": 4, "split_k": 1}, "bytes": 1880735990}],
+    6: [{"kernel_hash": "861e6eee1aef5252", "tile": {"bm": 64, "bn": 64, "bk": 64, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 2}, "bytes": 83849645}],
+    7: [{"kernel_hash": "6f639f7d1747716d", "tile": {}, "bytes": 1073772916}],
 }
 
 
