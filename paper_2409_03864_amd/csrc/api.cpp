@@ -112,9 +112,12 @@ double model_cycles(tsg_dtype dt, const KernelEntry& e, int split, int64_t batch
     // re-read LDS more often per MFMA; the finely pipelined forms pay a little for their order
     double ineff = (1.0 + 0.16 / (conc * wg_wps)) * (1.0 + 17.7 / (e.wm + e.wn));
     if (e.sched == 2 || e.sched == 3) ineff *= 1.0275;
+    if (e.sched >= 4) ineff *= 0.95;   // the LDS rings keep the barrier and the loads off the MFMA chain
     // k steps in flight ahead of the one being multiplied: register staging 1, the LDS rings 2 / 3
     const double depth = e.sched == 5 ? 3.0 : e.sched == 4 ? 2.0 : 1.0;
-    const double step_cost = std::max(conc * wg_mfma * ineff, kLatency / depth + 0.91 * wg_mfma);
+    // how much of a step's MFMA time is added to its exposed latency rather than overlapped
+    const double serial = (e.sched >= 4 && dt == TSG_BF16_F32ACC) ? 0.3 : 0.91;
+    const double step_cost = std::max(conc * wg_mfma * ineff, kLatency / depth + serial * wg_mfma);
     // split k: every partial tile goes through to memory and back (about 48 bytes per cycle)
     const double reduce = split > 1 ? 2.0 * e.bm * e.bn * 4.0 / 48.5 * split + 3814.0 : 0.0;
     return rounds * (steps * step_cost + reduce) + kLaunch;
