@@ -655,13 +655,6 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
     const int tr_row = 8 * lh + ((lane & 15) >> 2);
     const int tr_col = (lane & 16) + 4 * (lane & 3);
     const int tr_x = swz_j(tr_row);   // (row + 4) % 4 == row % 4: both reads share the mask
-    auto read_tr = [&](const u16* t, int ld, int k, int col) -> bf16x8 {
-        const int c = col + tr_col;
-        const u16* p0 = t + (k + tr_row) * ld + (((c >> 3) ^ tr_x) << 3) + (c & 7);
-        const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p0));
-        const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p0 + 4 * ld));
-        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    };
 
     // ---- one direct load: the x-th of the LPT loads that bring a tile in
     auto load_one = [&](int kt, int stage, int x) {
@@ -845,7 +838,6 @@ hipError_t launch_mode(int variant, const KArgs& a, int batch, hipStream_t s) {
     X(64, 64, 64, 32, 32, 2, 0)     \
     X(256, 256, 32, 128, 64, 2, 4)  \
     X(256, 256, 32, 128, 64, 2, 5)  \
-    X(256, 256, 32, 128, 128, 1, 5) \
     X(256, 128, 64, 64, 64, 2, 4)   \
     X(128, 128, 64, 64, 64, 2, 4)   \
     X(128, 128, 32, 64, 64, 2, 5)   \
