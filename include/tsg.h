@@ -209,7 +209,7 @@ tsg_status tsg_tile_config_enum(tsg_op op, tsg_dtype dtype, int32_t idx, tsg_til
 tsg_status tsg_tile_config_check(tsg_op op, tsg_dtype dtype, int64_t M, int64_t N, int64_t K,
                                  int64_t contig, const tsg_tile_config *cfg);
 
-/* Pin the config used by later calls of (op, dtype); NULL clears the pin.
+/* Pin the config used by later calls of (op, dtype), whatever their extents; NULL clears the pin.
  * Zero fields are filled from the default.  Validates instantiation first:
  * on TSG_E_SILENCEABLE the registry is unchanged. */
 tsg_status tsg_tile_config_set(tsg_op op, tsg_dtype dtype, const tsg_tile_config *cfg);
@@ -256,7 +256,9 @@ tsg_status tsg_gemm_index_map(int32_t trans_a, int64_t M, int64_t K, int64_t lda
 tsg_status tsg_search_set(int32_t max_evals, int32_t model_order);
 
 /* Time every legal instantiated config on the caller's buffers (three batches of `iters`
- * back-to-back calls each, after one warm-up), keep the fastest and pin it with tsg_tile_config_set.  This
+ * back-to-back calls each, after one warm-up) and remember the fastest for THIS problem (op,
+ * dtype, transposition, batch, extents): later calls with the same problem use it like a
+ * pinned config, unless tsg_tile_config_set has pinned another.  This
  * call SYNCHRONISES the stream and overwrites C / y.  `log` (host, may be NULL)
  * receives up to log_cap records in evaluation order; *n_log the number written. */
 tsg_status tsg_autotune_gemm(tsg_dtype dtype, int32_t trans_a, int64_t M, int64_t N, int64_t K,
@@ -292,6 +294,15 @@ tsg_status tsg_autotune_conv2d_nhwc(tsg_dtype dtype, int64_t N, int64_t H, int64
                                     uint32_t flags, void *stream, int32_t iters,
                                     tsg_tile_config *best, float *best_ms,
                                     tsg_tune_record *log, int32_t log_cap, int32_t *n_log);
+
+/* The tuner's results (host only).  save writes one text line per tuned problem; load adds
+ * the lines of such a file to the cache (entries whose config is not instantiated in this
+ * build, or malformed lines, are counted in *rejected and skipped; both counters may be
+ * NULL).  TSG_E_RUNTIME if the file cannot be opened or written. */
+int32_t    tsg_tune_cache_size(void);
+tsg_status tsg_tune_cache_clear(void);
+tsg_status tsg_tune_cache_save(const char *path);
+tsg_status tsg_tune_cache_load(const char *path, int32_t *loaded, int32_t *rejected);
 
 const char *tsg_status_string(tsg_status s);
 int32_t tsg_version(void);

@@ -74,6 +74,9 @@ def _load():
         "tsg_last_launch": [ctypes.POINTER(LaunchInfo)],
         "tsg_workspace_set": [vp, i64],
         "tsg_search_set": [i32, i32],
+        "tsg_tune_cache_clear": [],
+        "tsg_tune_cache_save": [ctypes.c_char_p],
+        "tsg_tune_cache_load": [ctypes.c_char_p, ctypes.POINTER(i32), ctypes.POINTER(i32)],
         "tsg_conv2d_index_map": [i64] * 10 + [vp],
         "tsg_gemm_index_map": [i32, i64, i64, i64, vp],
         "tsg_autotune_gemm": [i32, i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, u32, vp, i32,
@@ -97,6 +100,8 @@ def _load():
     lib.tsg_tile_config_count.restype = i32
     lib.tsg_workspace_bytes.argtypes = [i32, i64, i64, i64, cfgp]
     lib.tsg_workspace_bytes.restype = i64
+    lib.tsg_tune_cache_size.argtypes = []
+    lib.tsg_tune_cache_size.restype = i32
     lib.tsg_status_string.argtypes = [ctypes.c_int]
     lib.tsg_status_string.restype = ctypes.c_char_p
     lib.tsg_version.argtypes = []
@@ -110,7 +115,8 @@ EXPORTS = ("tsg_gemm", "tsg_gemm_transA", "tsg_gemm_batched", "tsg_gemm_trans", 
            "tsg_reduce_sum", "tsg_split",
            "tsg_tile_config_count", "tsg_tile_config_enum", "tsg_tile_config_check",
            "tsg_tile_config_set", "tsg_tile_config_get", "tsg_last_launch", "tsg_workspace_set",
-           "tsg_workspace_bytes", "tsg_search_set", "tsg_conv2d_index_map",
+           "tsg_workspace_bytes", "tsg_search_set", "tsg_tune_cache_size", "tsg_tune_cache_clear",
+           "tsg_tune_cache_save", "tsg_tune_cache_load", "tsg_conv2d_index_map",
            "tsg_gemm_index_map", "tsg_autotune_gemm", "tsg_autotune_gemm_batched", "tsg_autotune_conv2d_nhwc",
            "tsg_status_string", "tsg_version")
 
@@ -262,6 +268,25 @@ def gemm_index_map(trans_a, M, K, lda, off):
 
 def search_set(max_evals=0, model_order=True):
     _check(_lib.tsg_search_set(max_evals, int(bool(model_order))), "tsg_search_set")
+
+
+def tune_cache_size() -> int:
+    return int(_lib.tsg_tune_cache_size())
+
+
+def tune_cache_clear():
+    _check(_lib.tsg_tune_cache_clear(), "tsg_tune_cache_clear")
+
+
+def tune_cache_save(path):
+    _check(_lib.tsg_tune_cache_save(os.fsencode(path)), "tsg_tune_cache_save")
+
+
+def tune_cache_load(path):
+    """Returns (entries loaded, lines rejected)."""
+    ok, bad = ctypes.c_int32(), ctypes.c_int32()
+    _check(_lib.tsg_tune_cache_load(os.fsencode(path), ctypes.byref(ok), ctypes.byref(bad)), "tsg_tune_cache_load")
+    return ok.value, bad.value
 
 
 def _tune_out(cap):

@@ -2,6 +2,9 @@
 // legality rules, the chain of alternatives, launch planning and the tuner.
 // Host code only; the kernels live in gemm_f32_*.hip and gemm_bf16_*.hip.
 #include <algorithm>
+#include <array>
+#include <cstdio>
+#include <map>
 #include <cstring>
 #include <mutex>
 #include <vector>
@@ -39,6 +42,13 @@ struct Problem {
 std::mutex g_mu;
 bool g_pinned[kNumOps][kNumDtypes];
 tsg_tile_config g_pin[kNumOps][kNumDtypes];
+
+// Results of the tuner, per problem: (op, dtype, B transposed, batch, M, N, K, contiguous run
+// of the gathered operand) -> (config, time).  A call whose problem has an entry uses it
+// like a pinned config; tsg_tune_cache_save / _load carry the entries across processes.
+using TuneKey = std::array<int64_t, 8>;
+struct TuneVal { tsg_tile_config cfg; float ms; };
+std::map<TuneKey, TuneVal> g_tuned;
 
 // Caller-owned workspace for split k: arrival counters first, partial tiles after them.
 constexpr int64_t kMaxSlots = 16384;                       // (batch x tile) counters
@@ -179,6 +189,11 @@ bool vec_legal(const Problem& p, int vec) {
     return true;
 }
 
+TuneKey tune_key(const Problem& p) {
+    return TuneKey{(int64_t)p.op, (int64_t)p.dtype, p.trans_b ? 1 : 0, p.batch, p.M, p.N, p.K,
+                   p.op == TSG_OP_CONV2D_NHWC ? p.Cin : 0};
+}
+
 struct Plan {
     const KernelEntry* entry;
     tsg_tile_config cfg;
@@ -258,19 +273,21 @@ tsg_status enqueue(const Problem& p, const Plan& pl, hipStream_t s) {
 }
 
 // The chain of alternatives (Case Study 4: try, and on a silenceable failure fall through
-// to the next region): caller's pinned config -> shape heuristic -> the heuristic's tile
-// with scalar accesses, which has no precondition beyond a valid problem.
+// to the next region): the caller's pinned config, else the tuner's result for this problem
+// -> the cost model's default -> that tile with scalar accesses, which has no precondition
+// beyond a valid problem.
 tsg_status run(const Problem& p, hipStream_t s) {
     bool pinned;
     tsg_tile_config pin;
+    int64_t ws_bytes;
     {
         std::lock_guard<std::mutex> g(g_mu);
         pinned = g_pinned[p.op][p.dtype];
         pin = g_pin[p.op][p.dtype];
-    }
-    int64_t ws_bytes;
-    {
-        std::lock_guard<std::mutex> g(g_mu);
+        if (!pinned) {   // no config pinned by the caller: the tuner's result for this very problem, if any
+            const auto it = g_tuned.find(tune_key(p));
+            if (it != g_tuned.end()) { pinned = true; pin = it->second.cfg; }
+        }
         ws_bytes = g_ws ? g_ws_bytes : 0;
     }
     const tsg_tile_config heur = heuristic(p.dtype, p.batch, p.M, p.N, p.K, ws_bytes, p.trans_b);
@@ -444,7 +461,9 @@ tsg_status autotune(Problem p, hipStream_t s, int iters, tsg_tile_config* best, 
     if (bms < 0) return TSG_E_SILENCEABLE;
     if (best) *best = bcfg;
     if (best_ms) *best_ms = bms;
-    return tsg_tile_config_set(p.op, p.dtype, &bcfg);
+    std::lock_guard<std::mutex> g(g_mu);
+    g_tuned[tune_key(p)] = TuneVal{bcfg, bms};
+    return TSG_OK;
 }
 
 }  // namespace
@@ -599,7 +618,16 @@ tsg_status tsg_tile_config_get(tsg_op op, tsg_dtype dtype, int64_t M, int64_t N,
     if (!valid_op(op) || !valid_dtype(dtype) || !out) return TSG_E_INVALID;
     if (M <= 0 || N <= 0 || K <= 0) return TSG_E_INVALID;
     std::lock_guard<std::mutex> g(g_mu);
-    *out = g_pinned[op][dtype] ? g_pin[op][dtype] : heuristic(dtype, 1, M, N, K, g_ws ? g_ws_bytes : 0);
+    if (g_pinned[op][dtype]) { *out = g_pin[op][dtype]; return TSG_OK; }
+    // the tuner's result for an unbatched problem of these extents (any contiguous run), else the default
+    for (const auto& kv : g_tuned) {
+        const TuneKey& k = kv.first;
+        if (k[0] == op && k[1] == dtype && k[2] == 0 && k[3] == 1 && k[4] == M && k[5] == N && k[6] == K) {
+            *out = kv.second.cfg;
+            return TSG_OK;
+        }
+    }
+    *out = heuristic(dtype, 1, M, N, K, g_ws ? g_ws_bytes : 0);
     return TSG_OK;
 }
 
@@ -625,6 +653,64 @@ tsg_status tsg_search_set(int32_t max_evals, int32_t model_order) {
     std::lock_guard<std::mutex> g(g_mu);
     g_search_max_evals = max_evals;
     g_search_model_order = model_order;
+    return TSG_OK;
+}
+
+int32_t tsg_tune_cache_size(void) {
+    std::lock_guard<std::mutex> g(g_mu);
+    return (int32_t)g_tuned.size();
+}
+
+tsg_status tsg_tune_cache_clear(void) {
+    std::lock_guard<std::mutex> g(g_mu);
+    g_tuned.clear();
+    return TSG_OK;
+}
+
+tsg_status tsg_tune_cache_save(const char* path) {
+    if (!path) return TSG_E_INVALID;
+    std::FILE* f = std::fopen(path, "w");
+    if (!f) return TSG_E_RUNTIME;
+    std::lock_guard<std::mutex> g(g_mu);
+    std::fprintf(f, "# tsg tuner results: op dtype trans_b batch M N K contig  bm bn bk wm wn vec raster sched split_k  ms\n");
+    for (const auto& kv : g_tuned) {
+        const TuneKey& k = kv.first;
+        const tsg_tile_config& c = kv.second.cfg;
+        std::fprintf(f, "%lld %lld %lld %lld %lld %lld %lld %lld  %d %d %d %d %d %d %d %d %d  %.6f\n", (long long)k[0],
+                     (long long)k[1], (long long)k[2], (long long)k[3], (long long)k[4], (long long)k[5],
+                     (long long)k[6], (long long)k[7], c.bm, c.bn, c.bk, c.wm, c.wn, c.vec, c.raster, c.sched,
+                     c.split_k, kv.second.ms);
+    }
+    return std::fclose(f) == 0 ? TSG_OK : TSG_E_RUNTIME;
+}
+
+tsg_status tsg_tune_cache_load(const char* path, int32_t* loaded, int32_t* rejected) {
+    if (!path) return TSG_E_INVALID;
+    std::FILE* f = std::fopen(path, "r");
+    if (!f) return TSG_E_RUNTIME;
+    int ok = 0, bad = 0;
+    char line[512];
+    while (std::fgets(line, sizeof line, f)) {
+        if (line[0] == '#' || line[0] == '\n') continue;
+        long long k[8];
+        tsg_tile_config c;
+        float ms = 0.f;
+        const int n = std::sscanf(line, "%lld %lld %lld %lld %lld %lld %lld %lld %d %d %d %d %d %d %d %d %d %f", &k[0],
+                                  &k[1], &k[2], &k[3], &k[4], &k[5], &k[6], &k[7], &c.bm, &c.bn, &c.bk, &c.wm, &c.wn,
+                                  &c.vec, &c.raster, &c.sched, &c.split_k, &ms);
+        // an entry is taken only if it names an instantiated, well-formed config of a valid problem
+        const bool good = n == 18 && valid_op((int)k[0]) && valid_dtype((int)k[1]) && (k[2] == 0 || k[2] == 1) &&
+                          k[3] >= 1 && k[4] >= 1 && k[5] >= 1 && k[6] >= 1 && find_entry((tsg_dtype)k[1], c) &&
+                          (c.vec == 1 || c.vec == vec_max((tsg_dtype)k[1])) && (c.raster == 0 || c.raster == 1) &&
+                          c.split_k >= 1 && c.split_k <= kMaxSplit;
+        if (!good) { ++bad; continue; }
+        std::lock_guard<std::mutex> g(g_mu);
+        g_tuned[TuneKey{k[0], k[1], k[2], k[3], k[4], k[5], k[6], k[7]}] = TuneVal{c, ms};
+        ++ok;
+    }
+    std::fclose(f);
+    if (loaded) *loaded = ok;
+    if (rejected) *rejected = bad;
     return TSG_OK;
 }
 

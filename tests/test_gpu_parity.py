@@ -66,6 +66,7 @@ def _clear_pins():
     for op in (tsg.OP_GEMM, tsg.OP_GEMM_TRANSA, tsg.OP_CONV2D_NHWC):
         for dt in (tsg.F32, tsg.BF16_F32ACC):
             tsg.tile_config_set(op, dt, None)
+    tsg.tune_cache_clear()
 
 
 # shapes spanning several tiles with ragged tails in every dimension, plus degenerate ones
@@ -578,9 +579,15 @@ def test_autotune_pins_the_fastest_legal_config():
     assert timed and min(r.ms for r in timed) <= ms <= min(r.ms for r in timed) / 0.995 + 1e-6
     bests = [r.best_ms for r in log if r.best_ms >= 0]
     assert all(a >= b for a, b in zip(bests, bests[1:]))          # best-so-far curve (Fig. 11)
+    # the result is remembered for this problem only: other extents still get the default
     assert tsg.tile_config_get(tsg.OP_GEMM, tsg.F32, M, N, K).as_dict() == best.as_dict()
+    other = tsg.tile_config_get(tsg.OP_GEMM, tsg.F32, M + 1, N, K)
+    tsg.tune_cache_clear()
+    assert tsg.tile_config_get(tsg.OP_GEMM, tsg.F32, M + 1, N, K).as_dict() == other.as_dict()
+    tsg.autotune_gemm(tsg.F32, False, M, N, K, dA, K, dB, N, dC, N, iters=3)
     tsg.gemm(tsg.F32, M, N, K, dA, K, dB, N, dC, N, tsg.STRICT)
     torch.cuda.synchronize()
+    assert tsg.last_launch().alternative == 0
     assert np.array_equal(dC.cpu().numpy().astype(np.float64), oracle.gemm(A, B, with_s=False))
 
 

@@ -237,6 +237,42 @@ def test_reduce_sum_invalid_arguments():
         assert e.value.status == tsg.E_INVALID, kw
 
 
+def test_tune_cache_save_load_roundtrip(tmp_path):
+    """Tuner results are kept per problem and travel through a text file: well-formed lines
+    naming instantiated configs are taken, the rest is counted and skipped; a cached problem
+    answers tsg_tile_config_get, any other extents still get the default; a pin wins."""
+    op, dt = tsg.OP_GEMM, tsg.F32
+    tsg.tune_cache_clear()
+    assert tsg.tune_cache_size() == 0
+    default = tsg.tile_config_get(op, dt, 1000, 900, 800).as_dict()
+    f = tmp_path / "tuned.txt"
+    f.write_text("# comment\n"
+                 "0 0 0 1 1000 900 800 0  128 128 32 64 64 4 0 0 1  0.5\n"     # instantiated
+                 "0 0 0 1 1000 900 801 0  96 96 32 32 32 4 0 0 1  0.5\n"       # not instantiated
+                 "0 0 0 1 1000 900 802 0  128 128 32 64 64 3 0 0 1  0.5\n"     # no such access width
+                 "garbage line\n"
+                 "1 1 1 6 196 256 2305 0  64 64 64 32 32 8 1 4 2  0.03\n")
+    assert tsg.tune_cache_load(str(f)) == (2, 3)
+    assert tsg.tune_cache_size() == 2
+    got = tsg.tile_config_get(op, dt, 1000, 900, 800).as_dict()
+    assert (got["bm"], got["bn"], got["bk"], got["sched"], got["raster"]) == (128, 128, 32, 0, 0)
+    assert tsg.tile_config_get(op, dt, 1000, 900, 801).as_dict() != got          # other extents: the default
+    pin = tsg.tile_config_enum(op, dt, 5)
+    tsg.tile_config_set(op, dt, pin)
+    assert tsg.tile_config_get(op, dt, 1000, 900, 800).as_dict() == pin.as_dict()
+    tsg.tile_config_set(op, dt, None)
+    g = tmp_path / "again.txt"
+    tsg.tune_cache_save(str(g))
+    tsg.tune_cache_clear()
+    assert tsg.tile_config_get(op, dt, 1000, 900, 800).as_dict() == default
+    assert tsg.tune_cache_load(str(g)) == (2, 0)
+    assert tsg.tile_config_get(op, dt, 1000, 900, 800).as_dict() == got
+    tsg.tune_cache_clear()
+    with pytest.raises(tsg.TsgError) as e:
+        tsg.tune_cache_load(str(tmp_path / "missing.txt"))
+    assert e.value.status == tsg.E_RUNTIME
+
+
 def test_search_set_validates():
     for bad in ((-1, 1), (0, 2), (0, -1)):
         with pytest.raises(tsg.TsgError) as e:
