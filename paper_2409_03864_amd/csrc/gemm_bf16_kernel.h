@@ -93,25 +93,24 @@ __device__ __forceinline__ void finish_tile(const KArgs& p, f32x16 (&acc)[T::MI]
         if (tid == 0) arrived = __hip_atomic_fetch_add(p.counters + slot, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __syncthreads();
         if (arrived != p.split_k - 1) return;
-        // acc = ((P0 + P1) + P2) + ...: one partial tile at a time, all of its loads in flight together
-        for (int sp = 0; sp < p.split_k; ++sp) {
-            const float* part = ws + (long long)sp * (BM * BN);
-            float t[MI][NI][16];
+        // acc = ((P0 + P1) + P2) + ...: a row of MFMA blocks of one partial tile at a time, all of
+        // its loads in flight together
 #pragma unroll
-            for (int i = 0; i < MI; ++i)
+        for (int i = 0; i < MI; ++i)
+            for (int sp = 0; sp < p.split_k; ++sp) {
+                const float* part = ws + (long long)sp * (BM * BN);
+                float t[NI][16];
 #pragma unroll
                 for (int j = 0; j < NI; ++j)
 #pragma unroll
                     for (int r = 0; r < 16; ++r)
-                        t[i][j][r] = __hip_atomic_load(part + ((i * NI + j) * 16 + r) * NT + tid, __ATOMIC_RELAXED,
-                                                       __HIP_MEMORY_SCOPE_AGENT);
-#pragma unroll
-            for (int i = 0; i < MI; ++i)
+                        t[j][r] = __hip_atomic_load(part + ((i * NI + j) * 16 + r) * NT + tid, __ATOMIC_RELAXED,
+                                                    __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
                 for (int j = 0; j < NI; ++j)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[i][j][r] = sp == 0 ? t[i][j][r] : acc[i][j][r] + t[i][j][r];
-        }
+                    for (int r = 0; r < 16; ++r) acc[i][j][r] = sp == 0 ? t[j][r] : acc[i][j][r] + t[j][r];
+            }
         if (tid == 0) p.counters[slot] = 0;   // ready for the next launch on this workspace
     }
 
@@ -772,7 +771,9 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
                 else b = __builtin_shufflevector(bh[g & 1][j][0], bh[g & 1][j][1], 0, 1, 2, 3, 4, 5, 6, 7);
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i][j], 0, 0, 0);
 #pragma unroll
-                for (int e = m * PER; e < (m + 1) * PER && e < NX; ++e) {
+                for (int u = 0; u < PER; ++u) {
+                    const int e = m * PER + u;
+                    if (e >= NX) continue;
                     if (e < LPT) {
                         if (last && kt + D < nk) issue_part(kt + D, fill, e);
                     } else if (last) {
