@@ -110,7 +110,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU; --gpus %d is not supported "
-            "(the contraction shards by rows of C with no exchange, see DESIGN.md)." % args.gpus)
+            "(rows of C are independent, so more GPUs would each take a panel of A with no exchange)." % args.gpus)
         return 2
 
     import numpy as np
