@@ -158,7 +158,7 @@ tsg_tile_config heuristic(tsg_dtype dt, int64_t batch, int64_t M, int64_t N, int
     return config_of(t[best_i], vec_max(dt), 1, best_split);   // XCD-aware raster: same time, fewer bytes fetched
 }
 
-// Fill zero fields ("tiling by 0 is a no-op": the library default stands) from `def`.
+// Fill zero fields from `def` (Sec. 3.4: a tile size of 0 changes nothing, so the library default stands).
 tsg_tile_config fill_defaults(tsg_tile_config c, const tsg_tile_config& def) {
     const bool tile_given = c.bm > 0 || c.bn > 0 || c.bk > 0 || c.wm > 0 || c.wn > 0;
     if (c.bm <= 0) c.bm = def.bm;
