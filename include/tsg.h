@@ -4,13 +4,16 @@
  * The library computes the loop nest that the paper's schedules optimise
  * (Case Study 4, Fig. 7):
  *
- *        C[i][j] (+)= sum_k op(A)[i][k] * B[k][j]
+ *        C[i][j] (+)= sum_k op(A)[i][k] * op(B)[k][j]
  *
  * with the rewrites of Case Study 3 folded into addressing instead of being
- * materialised: a transposed left operand is read in place (tsg_gemm_transA), a
- * negate is applied in the store epilogue (TSG_NEGATE), and elements produced by
- * zero padding are never formed, read or added (tsg_conv2d_nhwc, an implicit
- * GEMM over M = N*Ho*Wo, N = Cout, K = KH*KW*Cin with k ordered (kh, kw, ci)).
+ * materialised: a transposed operand is read in place (tsg_gemm_transA,
+ * tsg_gemm_trans), a negate is applied in the store epilogue (TSG_NEGATE), elements
+ * produced by zero padding are never formed, read or added (tsg_conv2d_nhwc, an
+ * implicit GEMM over M = N*Ho*Wo, N = Cout, K = KH*KW*Cin with k ordered (kh, kw,
+ * ci); tsg_conv2d_nhwc_window adds a result into the interior of a padded tensor),
+ * and the full additive reduce reads its operand as it lies in memory
+ * (tsg_reduce_sum).
  * The knobs of the schedule -- tile sizes per loop, the vectorise flag and their
  * legality constraints (Case Study 5, Fig. 9 and Fig. 10), the split of a loop
  * into a divisible main part and a remainder (Fig. 1, Fig. 8) -- are data:
@@ -28,11 +31,14 @@
  *    schedule failed; NOTHING was enqueued and no output byte was touched, so the
  *    caller may try another alternative.  TSG_E_INVALID and TSG_E_RUNTIME are
  *    definite.  Without TSG_STRICT a compute call walks its own chain of
- *    alternatives (config set by the caller -> shape heuristic -> scalar-access
- *    fallback of the same tile) and only fails definitely.
+ *    alternatives (the config pinned by the caller, else the tuner's result for
+ *    this very problem -> the library's default for the shape -> that tile with
+ *    scalar accesses) and only fails definitely.
  *  - Extents must fit in int32 (each of M, N, K, and every tensor's element count
  *    for convolution); larger values are TSG_E_INVALID.
- *  - The config registry is guarded by a mutex; compute calls are re-entrant.
+ *  - The config registry, the tuner's results and the workspace pointer are guarded
+ *    by a mutex; compute calls are re-entrant, except that calls which use the
+ *    workspace must be ordered on one stream.
  */
 #ifndef TSG_H
 #define TSG_H
