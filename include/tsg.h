@@ -99,6 +99,12 @@ enum {
  *                alone cannot fill the chip).  1 = none; 0 = library default.  Values
  *                above 1 need a workspace (tsg_workspace_set) and at most 16; the partial
  *                tiles are added in split order, so the result does not depend on timing.
+ *   split_tail : 0 = split_k applies to every tile.  1 = only the tiles left over after
+ *                the last full round of one tile per compute unit (256) are split, the
+ *                earlier ones stay whole, all in one launch: the peeled remainder of the
+ *                tile loop itself (Fig. 8 applied at the grid level), for tile counts just
+ *                above a multiple of 256.  Needs split_k > 1 and a tile count (per batch
+ *                entry) that is not a multiple of 256, else silenceable.
  */
 typedef struct {
     int32_t bm, bn, bk;
@@ -107,6 +113,7 @@ typedef struct {
     int32_t raster;
     int32_t sched;
     int32_t split_k;
+    int32_t split_tail;
 } tsg_tile_config;
 
 /* What the most recent compute call on the calling thread enqueued. */
@@ -210,7 +217,8 @@ tsg_status tsg_tile_config_enum(tsg_op op, tsg_dtype dtype, int32_t idx, tsg_til
  * pointers.  For convolution pass the implicit extents and Cin as `contig`
  * (the contiguous run of the gathered operand); for GEMM contig is ignored.
  * TSG_E_SILENCEABLE if the tile is not instantiated, `vec` violates Fig. 10's
- * divisibility rule, or split_k exceeds 16 or the number of k steps; TSG_E_INVALID for
+ * divisibility rule, split_k exceeds 16 or the number of k steps, or split_tail is set with
+ * split_k = 1 or a tile count that leaves no tail; TSG_E_INVALID for
  * malformed arguments. */
 tsg_status tsg_tile_config_check(tsg_op op, tsg_dtype dtype, int64_t M, int64_t N, int64_t K,
                                  int64_t contig, const tsg_tile_config *cfg);

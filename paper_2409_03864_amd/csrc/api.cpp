@@ -79,17 +79,25 @@ const KernelEntry* find_entry(tsg_dtype dt, const tsg_tile_config& c) {
     return nullptr;
 }
 
-tsg_tile_config config_of(const KernelEntry& e, int vec, int raster, int split_k = 1) {
+tsg_tile_config config_of(const KernelEntry& e, int vec, int raster, int split_k = 1, int split_tail = 0) {
     tsg_tile_config c;
     c.bm = e.bm; c.bn = e.bn; c.bk = e.bk; c.wm = e.wm; c.wn = e.wn;
-    c.vec = vec; c.raster = raster; c.sched = e.sched; c.split_k = split_k;
+    c.vec = vec; c.raster = raster; c.sched = e.sched; c.split_k = split_k; c.split_tail = split_tail;
     return c;
 }
 
-int64_t ws_bytes_needed(const KernelEntry& e, int64_t batch, int64_t M, int64_t N, int split_k) {
+// Tiles that a split applies to: all of them, or (split_tail) those beyond the last full
+// round of one tile per CU -- the tail that would otherwise leave most of the chip idle.
+int64_t split_tiles(int64_t tiles, int split_k, int split_tail) {
     if (split_k <= 1) return 0;
+    return split_tail ? tiles % kCUs : tiles;
+}
+
+int64_t ws_bytes_needed(const KernelEntry& e, int64_t batch, int64_t M, int64_t N, int split_k, int split_tail = 0) {
     const int64_t tiles = ((M + e.bm - 1) / e.bm) * ((N + e.bn - 1) / e.bn);
-    return kCounterBytes + batch * tiles * split_k * (int64_t)e.bm * e.bn * 4;
+    const int64_t st = split_tiles(tiles, split_k, split_tail);
+    if (st == 0) return 0;
+    return kCounterBytes + batch * st * split_k * (int64_t)e.bm * e.bn * 4;
 }
 
 // Cost model of one launch, in cycles of a CU.  A workgroup step costs its MFMA cycles on
@@ -101,12 +109,14 @@ int64_t ws_bytes_needed(const KernelEntry& e, int64_t batch, int64_t M, int64_t 
 // covers the likely winners.  Constants are fitted to the tuner's own measurements on six
 // shapes (256^3, 1024^3 transposed, 4096^3, the 3x3 convolution, bf16 8192^3, and the batched
 // 196 x 256 x 2305); on those the model's pick is within 12 % of the measured optimum.
-double model_cycles(tsg_dtype dt, const KernelEntry& e, int split, int64_t batch, int64_t M, int64_t N, int64_t K) {
+constexpr double kModelLaunch = 7682.0;      // launch, first loads and epilogue of a kernel
+
+// `ntiles` tiles of C (all batch entries together), each split `split` ways; no launch cost
+double model_core(tsg_dtype dt, const KernelEntry& e, double ntiles, int split, int64_t K) {
     const double kLatency = 2324.0;     // cycles from issuing a tile's loads to LDS-ready
-    const double kLaunch = 7682.0;      // launch, first loads and epilogue of a kernel
     const double kLds = 160.0 * 1024;
     const int64_t nk_all = (K + e.bk - 1) / e.bk;
-    const double tiles = (double)((M + e.bm - 1) / e.bm) * (double)((N + e.bn - 1) / e.bn) * (double)batch * split;
+    const double tiles = ntiles * split;
     const double blocks = (e.wm / 32) * (e.wn / 32);
     const double wg_wps = e.threads / 256.0;                        // waves per SIMD of one workgroup
     const double wps_cap = (double)(int)(512.0 / (blocks * 16.0 + 64.0));   // register-file limit
@@ -130,14 +140,29 @@ double model_cycles(tsg_dtype dt, const KernelEntry& e, int split, int64_t batch
     const double step_cost = std::max(conc * wg_mfma * ineff, kLatency / depth + serial * wg_mfma);
     // split k: every partial tile goes through to memory and back (about 48 bytes per cycle)
     const double reduce = split > 1 ? 2.0 * e.bm * e.bn * 4.0 / 48.5 * split + 3814.0 : 0.0;
-    return rounds * (steps * step_cost + reduce) + kLaunch;
+    return rounds * (steps * step_cost + reduce);
 }
 
-bool split_allowed(const KernelEntry& e, int split, int64_t batch, int64_t M, int64_t N, int64_t K, int64_t ws_bytes) {
-    if (split == 1) return true;
+double model_cycles(tsg_dtype dt, const KernelEntry& e, int split, int split_tail, int64_t batch, int64_t M,
+                    int64_t N, int64_t K) {
+    const int64_t tiles = ((M + e.bm - 1) / e.bm) * ((N + e.bn - 1) / e.bn);
+    if (split > 1 && split_tail) {
+        // full rounds of one tile per CU unsplit, then the tail split so that it fills the chip
+        const int64_t rem = tiles % kCUs, full = tiles - rem;
+        if (rem == 0) return model_core(dt, e, (double)(tiles * batch), 1, K) + kModelLaunch;
+        return (full ? model_core(dt, e, (double)(full * batch), 1, K) : 0.0) +
+               model_core(dt, e, (double)(rem * batch), split, K) + kModelLaunch;
+    }
+    return model_core(dt, e, (double)(tiles * batch), split, K) + kModelLaunch;
+}
+
+bool split_allowed(const KernelEntry& e, int split, int split_tail, int64_t batch, int64_t M, int64_t N, int64_t K,
+                   int64_t ws_bytes) {
+    if (split == 1) return !split_tail;
     const int64_t nk_all = (K + e.bk - 1) / e.bk;
-    return split * 2 <= nk_all && ws_bytes_needed(e, batch, M, N, split) <= ws_bytes &&
-           batch * ((M + e.bm - 1) / e.bm) * ((N + e.bn - 1) / e.bn) <= kMaxSlots;
+    const int64_t n_split = split_tiles(((M + e.bm - 1) / e.bm) * ((N + e.bn - 1) / e.bn), split, split_tail);
+    return n_split > 0 && split * 2 <= nk_all && ws_bytes_needed(e, batch, M, N, split, split_tail) <= ws_bytes &&
+           batch * n_split <= kMaxSlots;
 }
 
 // The default config of a shape: the model's minimum over instantiated tiles and splits.
@@ -146,16 +171,21 @@ tsg_tile_config heuristic(tsg_dtype dt, int64_t batch, int64_t M, int64_t N, int
     int n = 0;
     const KernelEntry* t = kernels(dt, &n);
     double best = 0;
-    int best_i = 0, best_split = 1;
+    int best_i = 0, best_split = 1, best_tail = 0;
     bool first = true;
     for (int i = 0; i < n; ++i)
-        for (int split = 1; split <= kMaxSplit; split *= 2) {
-            if (direct_only && t[i].sched < 4) break;
-            if (!split_allowed(t[i], split, batch, M, N, K, ws_bytes)) break;
-            const double est = model_cycles(dt, t[i], split, batch, M, N, K);
-            if (first || est < best * 0.999) { best = est; best_i = i; best_split = split; first = false; }
-        }
-    return config_of(t[best_i], vec_max(dt), 1, best_split);   // XCD-aware raster: same time, fewer bytes fetched
+        for (int tail = 0; tail < 2; ++tail)
+            for (int split = 1; split <= kMaxSplit; split *= 2) {
+                if (direct_only && t[i].sched < 4) break;
+                if (!split_allowed(t[i], split, tail, batch, M, N, K, ws_bytes)) {
+                    if (split == 1) continue;   // tail = 1 starts at split 2
+                    break;
+                }
+                const double est = model_cycles(dt, t[i], split, tail, batch, M, N, K);
+                if (first || est < best * 0.999) { best = est; best_i = i; best_split = split; best_tail = tail; first = false; }
+            }
+    // XCD-aware raster: same time, fewer bytes fetched
+    return config_of(t[best_i], vec_max(dt), 1, best_split, best_tail);
 }
 
 // Fill zero fields from `def` (Sec. 3.4: a tile size of 0 changes nothing, so the library default stands).
@@ -170,7 +200,7 @@ tsg_tile_config fill_defaults(tsg_tile_config c, const tsg_tile_config& def) {
     if (c.vec <= 0) c.vec = def.vec;
     if (c.raster < 0) c.raster = def.raster;
     if (c.sched < 0) c.sched = def.sched;
-    if (c.split_k <= 0) c.split_k = tile_given ? 1 : def.split_k;
+    if (c.split_k <= 0) { c.split_k = tile_given ? 1 : def.split_k; c.split_tail = tile_given ? 0 : def.split_tail; }
     return c;
 }
 
@@ -211,6 +241,7 @@ tsg_status make_plan(const Problem& p, const tsg_tile_config& cfg, int alternati
     if (p.trans_b && e->sched < 4) return TSG_E_SILENCEABLE;       // a transposed B exists in those forms only
     if (cfg.raster != 0 && cfg.raster != 1) return TSG_E_SILENCEABLE;
     if (cfg.split_k < 1 || cfg.split_k > kMaxSplit) return TSG_E_SILENCEABLE;
+    if ((cfg.split_tail != 0 && cfg.split_tail != 1) || (cfg.split_tail && cfg.split_k == 1)) return TSG_E_SILENCEABLE;
 
     int64_t m_main, m_rest, n_main, n_rest, k_main, k_rest, t;
     tsg_split(p.M, e->bm, &m_main, &m_rest, &t);
@@ -219,12 +250,16 @@ tsg_status make_plan(const Problem& p, const tsg_tile_config& cfg, int alternati
     const int64_t tiles_m = (p.M + e->bm - 1) / e->bm, tiles_n = (p.N + e->bn - 1) / e->bn;
     if (tiles_m * tiles_n * cfg.split_k > 0x7fffffff / 2 || p.batch > 65535) return TSG_E_SILENCEABLE;
     void* ws = nullptr;
+    const int64_t n_split = split_tiles(tiles_m * tiles_n, cfg.split_k, cfg.split_tail);
     if (cfg.split_k > 1) {
-        // every split needs at least one k step, and the partial tiles need the workspace
+        // every split needs at least one k step, a tail to split if only the tail is split, and
+        // the partial tiles need the workspace
         if (cfg.split_k > (p.K + e->bk - 1) / e->bk) return TSG_E_SILENCEABLE;
-        if (p.batch * tiles_m * tiles_n > kMaxSlots) return TSG_E_SILENCEABLE;
+        if (n_split == 0) return TSG_E_SILENCEABLE;
+        if (p.batch * n_split > kMaxSlots) return TSG_E_SILENCEABLE;
         std::lock_guard<std::mutex> g(g_mu);
-        if (!g_ws || ws_bytes_needed(*e, p.batch, p.M, p.N, cfg.split_k) > g_ws_bytes) return TSG_E_SILENCEABLE;
+        if (!g_ws || ws_bytes_needed(*e, p.batch, p.M, p.N, cfg.split_k, cfg.split_tail) > g_ws_bytes)
+            return TSG_E_SILENCEABLE;
         ws = g_ws;
     }
 
@@ -244,6 +279,7 @@ tsg_status make_plan(const Problem& p, const tsg_tile_config& cfg, int alternati
     a.flags = p.flags & (TSG_NEGATE | TSG_ACCUMULATE);
     a.raster = cfg.raster;
     a.split_k = cfg.split_k;
+    a.split_first = (int)(tiles_m * tiles_n - n_split);
     a.counters = (int*)ws;
     a.ws = ws ? (float*)((char*)ws + kCounterBytes) : nullptr;
     a.H = (int)p.H; a.W = (int)p.W; a.Cin = (int)p.Cin; a.Ho = (int)p.Ho; a.Wo = (int)p.Wo;
@@ -304,6 +340,7 @@ tsg_status run(const Problem& p, hipStream_t s) {
     tsg_tile_config scalar = heur;
     scalar.vec = 1;
     scalar.split_k = 1;
+    scalar.split_tail = 0;
     if (scalar.sched >= 4) {
         scalar.sched = 0;
         if (!find_entry(p.dtype, scalar)) {
@@ -360,8 +397,9 @@ tsg_status conv_problem(int dtype, int64_t N, int64_t H, int64_t W, int64_t Cin,
 }
 
 // Enumerated search space: every instantiated tile x {wide access with either raster order,
-// scalar access, wide access with the k loop split 2, 4, 8 or 16 ways}.
-constexpr int kPointsPerTile = 7;
+// scalar access, wide access with the k loop split 2, 4, 8 or 16 ways, or with only the tail
+// tiles split 2, 4 or 8 ways}.
+constexpr int kPointsPerTile = 10;
 int space_size(tsg_dtype dt) {
     int n = 0;
     kernels(dt, &n);
@@ -377,7 +415,8 @@ tsg_tile_config space_point(tsg_dtype dt, int idx) {
         case 0: return config_of(e, vec_max(dt), 1);
         case 1: return config_of(e, vec_max(dt), 0);
         case 2: return config_of(e, 1, 1);
-        default: return config_of(e, vec_max(dt), 0, 1 << (k - 2));
+        case 3: case 4: case 5: case 6: return config_of(e, vec_max(dt), 0, 1 << (k - 2));
+        default: return config_of(e, vec_max(dt), 1, 1 << (k - 6), 1);   // tail only, split 2, 4, 8
     }
 }
 
@@ -409,7 +448,7 @@ tsg_status autotune(Problem p, hipStream_t s, int iters, tsg_tile_config* best, 
     for (int i = 0; i < n; ++i) {
         const tsg_tile_config c = space_point(p.dtype, i);
         const KernelEntry* e = find_entry(p.dtype, c);
-        double pred = model_cycles(p.dtype, *e, c.split_k, p.batch, p.M, p.N, p.K) / 2.4e6;
+        double pred = model_cycles(p.dtype, *e, c.split_k, c.split_tail, p.batch, p.M, p.N, p.K) / 2.4e6;
         if (c.vec == 1) pred *= 4.0;
         cand.push_back(Cand{c, pred, i});
     }
@@ -426,7 +465,7 @@ tsg_status autotune(Problem p, hipStream_t s, int iters, tsg_tile_config* best, 
         Plan pl;
         float med = -1.f;
         // splitting k only pays while the unsplit tiles cannot fill the chip twice over
-        const bool worth = c.split_k == 1 ||
+        const bool worth = c.split_k == 1 || c.split_tail ||
                            p.batch * ((p.M + c.bm - 1) / c.bm) * ((p.N + c.bn - 1) / c.bn) < 2 * kCUs;
         if (worth && make_plan(p, c, 0, &pl) == TSG_OK) {
             st = enqueue(p, pl, s);   // warm-up
@@ -580,7 +619,8 @@ tsg_status tsg_tile_config_check(tsg_op op, tsg_dtype dtype, int64_t M, int64_t 
                                  const tsg_tile_config* cfg) {
     if (!valid_op(op) || !valid_dtype(dtype) || !cfg) return TSG_E_INVALID;
     if (M <= 0 || N <= 0 || K <= 0) return TSG_E_INVALID;
-    if (cfg->bm < 0 || cfg->bn < 0 || cfg->bk < 0 || cfg->wm < 0 || cfg->wn < 0 || cfg->vec < 0 || cfg->split_k < 0)
+    if (cfg->bm < 0 || cfg->bn < 0 || cfg->bk < 0 || cfg->wm < 0 || cfg->wn < 0 || cfg->vec < 0 || cfg->split_k < 0 ||
+        (cfg->split_tail != 0 && cfg->split_tail != 1))
         return TSG_E_INVALID;
     if (op == TSG_OP_CONV2D_NHWC && contig <= 0) return TSG_E_INVALID;
     const tsg_tile_config c = fill_defaults(*cfg, heuristic(dtype, 1, M, N, K, 0));
@@ -588,6 +628,9 @@ tsg_status tsg_tile_config_check(tsg_op op, tsg_dtype dtype, int64_t M, int64_t 
     if (!e) return TSG_E_SILENCEABLE;
     if (c.raster != 0 && c.raster != 1) return TSG_E_SILENCEABLE;
     if (c.split_k < 1 || c.split_k > kMaxSplit || c.split_k > (K + e->bk - 1) / e->bk) return TSG_E_SILENCEABLE;
+    if (c.split_tail && c.split_k == 1) return TSG_E_SILENCEABLE;
+    if (c.split_k > 1 && split_tiles(((M + e->bm - 1) / e->bm) * ((N + e->bn - 1) / e->bn), c.split_k, c.split_tail) == 0)
+        return TSG_E_SILENCEABLE;   // no tail to split
     if (c.vec == 1) return e->sched >= 4 ? TSG_E_SILENCEABLE : TSG_OK;
     if (c.vec != vec_max(dtype)) return TSG_E_SILENCEABLE;
     // the innermost contiguous extent of the gathered operand is Cin; matrix rows are
@@ -600,13 +643,14 @@ tsg_status tsg_tile_config_set(tsg_op op, tsg_dtype dtype, const tsg_tile_config
     if (!valid_op(op) || !valid_dtype(dtype)) return TSG_E_INVALID;
     std::lock_guard<std::mutex> g(g_mu);
     if (!cfg) { g_pinned[op][dtype] = false; return TSG_OK; }
-    if (cfg->bm < 0 || cfg->bn < 0 || cfg->bk < 0 || cfg->wm < 0 || cfg->wn < 0 || cfg->vec < 0 || cfg->split_k < 0)
+    if (cfg->bm < 0 || cfg->bn < 0 || cfg->bk < 0 || cfg->wm < 0 || cfg->wn < 0 || cfg->vec < 0 || cfg->split_k < 0 ||
+        (cfg->split_tail != 0 && cfg->split_tail != 1))
         return TSG_E_INVALID;
     int n = 0;
     const KernelEntry* t = kernels(dtype, &n);
     const tsg_tile_config c = fill_defaults(*cfg, config_of(t[0], vec_max(dtype), 1));
     if (!find_entry(dtype, c)) return TSG_E_SILENCEABLE;
-    if (c.split_k > kMaxSplit) return TSG_E_SILENCEABLE;
+    if (c.split_k > kMaxSplit || (c.split_tail && c.split_k == 1)) return TSG_E_SILENCEABLE;
     if (c.vec != 1 && c.vec != vec_max(dtype)) return TSG_E_SILENCEABLE;
     if (c.raster != 0 && c.raster != 1) return TSG_E_SILENCEABLE;
     g_pin[op][dtype] = c;
@@ -645,7 +689,7 @@ int64_t tsg_workspace_bytes(tsg_dtype dtype, int64_t batch, int64_t M, int64_t N
     if (!valid_dtype(dtype) || !cfg || batch <= 0 || M <= 0 || N <= 0) return -1;
     const KernelEntry* e = find_entry(dtype, *cfg);
     if (!e || cfg->split_k < 1 || cfg->split_k > kMaxSplit) return -1;
-    return ws_bytes_needed(*e, batch, M, N, cfg->split_k);
+    return ws_bytes_needed(*e, batch, M, N, cfg->split_k, cfg->split_tail);
 }
 
 tsg_status tsg_search_set(int32_t max_evals, int32_t model_order) {
@@ -672,14 +716,14 @@ tsg_status tsg_tune_cache_save(const char* path) {
     std::FILE* f = std::fopen(path, "w");
     if (!f) return TSG_E_RUNTIME;
     std::lock_guard<std::mutex> g(g_mu);
-    std::fprintf(f, "# tsg tuner results: op dtype trans_b batch M N K contig  bm bn bk wm wn vec raster sched split_k  ms\n");
+    std::fprintf(f, "# tsg tuner results: op dtype trans_b batch M N K contig  bm bn bk wm wn vec raster sched split_k split_tail  ms\n");
     for (const auto& kv : g_tuned) {
         const TuneKey& k = kv.first;
         const tsg_tile_config& c = kv.second.cfg;
-        std::fprintf(f, "%lld %lld %lld %lld %lld %lld %lld %lld  %d %d %d %d %d %d %d %d %d  %.6f\n", (long long)k[0],
+        std::fprintf(f, "%lld %lld %lld %lld %lld %lld %lld %lld  %d %d %d %d %d %d %d %d %d %d  %.6f\n", (long long)k[0],
                      (long long)k[1], (long long)k[2], (long long)k[3], (long long)k[4], (long long)k[5],
                      (long long)k[6], (long long)k[7], c.bm, c.bn, c.bk, c.wm, c.wn, c.vec, c.raster, c.sched,
-                     c.split_k, kv.second.ms);
+                     c.split_k, c.split_tail, kv.second.ms);
     }
     return std::fclose(f) == 0 ? TSG_OK : TSG_E_RUNTIME;
 }
@@ -695,14 +739,15 @@ tsg_status tsg_tune_cache_load(const char* path, int32_t* loaded, int32_t* rejec
         long long k[8];
         tsg_tile_config c;
         float ms = 0.f;
-        const int n = std::sscanf(line, "%lld %lld %lld %lld %lld %lld %lld %lld %d %d %d %d %d %d %d %d %d %f", &k[0],
+        const int n = std::sscanf(line, "%lld %lld %lld %lld %lld %lld %lld %lld %d %d %d %d %d %d %d %d %d %d %f", &k[0],
                                   &k[1], &k[2], &k[3], &k[4], &k[5], &k[6], &k[7], &c.bm, &c.bn, &c.bk, &c.wm, &c.wn,
-                                  &c.vec, &c.raster, &c.sched, &c.split_k, &ms);
+                                  &c.vec, &c.raster, &c.sched, &c.split_k, &c.split_tail, &ms);
         // an entry is taken only if it names an instantiated, well-formed config of a valid problem
-        const bool good = n == 18 && valid_op((int)k[0]) && valid_dtype((int)k[1]) && (k[2] == 0 || k[2] == 1) &&
+        const bool good = n == 19 && valid_op((int)k[0]) && valid_dtype((int)k[1]) && (k[2] == 0 || k[2] == 1) &&
                           k[3] >= 1 && k[4] >= 1 && k[5] >= 1 && k[6] >= 1 && find_entry((tsg_dtype)k[1], c) &&
                           (c.vec == 1 || c.vec == vec_max((tsg_dtype)k[1])) && (c.raster == 0 || c.raster == 1) &&
-                          c.split_k >= 1 && c.split_k <= kMaxSplit;
+                          c.split_k >= 1 && c.split_k <= kMaxSplit &&
+                          (c.split_tail == 0 || (c.split_tail == 1 && c.split_k > 1));
         if (!good) { ++bad; continue; }
         std::lock_guard<std::mutex> g(g_mu);
         g_tuned[TuneKey{k[0], k[1], k[2], k[3], k[4], k[5], k[6], k[7]}] = TuneVal{c, ms};

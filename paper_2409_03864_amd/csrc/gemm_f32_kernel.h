@@ -93,19 +93,35 @@ __device__ __forceinline__ void tile_coords(const KArgs& p, int bid, int& tm, in
     tn = id - tm * p.tiles_n;
 }
 
+// Which tile, and which part of its k loop, a workgroup takes: ids below split_first are
+// whole tiles; after them come the split tiles, split index slow, so the parts of one tile
+// are dispatched a whole round apart and no part ever waits for another.
+__device__ __forceinline__ void decode_block(const KArgs& p, int tiles, int& tile, int& split, int& nsplit, int& slot) {
+    const int bid = blockIdx.x;
+    if (bid < p.split_first) {
+        tile = bid; split = 0; nsplit = 1; slot = 0;
+        return;
+    }
+    const int r = bid - p.split_first, rem = tiles - p.split_first;
+    split = r / rem;
+    const int t = r - split * rem;
+    tile = p.split_first + t;
+    nsplit = p.split_k;
+    slot = blockIdx.y * rem + t;
+}
+
 // What follows the k loop.  Split k: park the partial tile, count the arrival, and let the
 // last arrival add the partials in split order.  Epilogue: sign, optional accumulate, masked
 // at the remainder.
 template <class T>
 __device__ __forceinline__ void finish_tile(const KArgs& p, f32x16 (&acc)[T::MI][T::NI], float* __restrict__ C,
-                                            int tile, int split, int tiles, int m0, int n0, int wm0, int wn0,
+                                            int slot, int split, int nsplit, int m0, int n0, int wm0, int wn0,
                                             bool interior) {
     constexpr int BM = T::BM, BN = T::BN, NT = T::NT, MI = T::MI, NI = T::NI;
     const int tid = threadIdx.x, lane = tid & 63, li = lane & 31, lh = lane >> 5;
-    if (p.split_k > 1) {
+    if (nsplit > 1) {
         __shared__ int arrived;
-        const long long slot = (long long)blockIdx.y * tiles + tile;
-        float* ws = p.ws + slot * p.split_k * (BM * BN);
+        float* ws = p.ws + (long long)slot * nsplit * (BM * BN);
         // A partial tile is kept in register order.  Partials cross between L2 domains, so
         // they are written and read with device-scope accesses that go through to memory; once
         // a wave's stores are acknowledged (the wait) and all waves are at the barrier, the
@@ -124,12 +140,12 @@ __device__ __forceinline__ void finish_tile(const KArgs& p, f32x16 (&acc)[T::MI]
         __syncthreads();
         if (tid == 0) arrived = __hip_atomic_fetch_add(p.counters + slot, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __syncthreads();
-        if (arrived != p.split_k - 1) return;
+        if (arrived != nsplit - 1) return;
         // acc = ((P0 + P1) + P2) + ...: a row of MFMA blocks of one partial tile at a time, all of
         // its loads in flight together
 #pragma unroll
         for (int i = 0; i < MI; ++i)
-            for (int sp = 0; sp < p.split_k; ++sp) {
+            for (int sp = 0; sp < nsplit; ++sp) {
                 const float* part = ws + (long long)sp * (BM * BN);
                 float t[NI][16];
 #pragma unroll
@@ -182,7 +198,8 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_kernel(const KArgs p)
     const int li = lane & 31, lh = lane >> 5;
 
     const int tiles = p.tiles_m * p.tiles_n;
-    const int split = blockIdx.x / tiles, tile = blockIdx.x - split * tiles;   // split is the slow index
+    int tile, split, nsplit, slot;
+    decode_block(p, tiles, tile, split, nsplit, slot);
     int tm, tn;
     tile_coords(p, tile, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
@@ -194,8 +211,8 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_kernel(const KArgs p)
     const bool interior = !EDGE || (m0 + BM <= p.m_main && n0 + BN <= p.n_main);
     // this workgroup's k steps: [kb, kb + nk) of the (K + BK - 1) / BK steps of the whole loop
     const int nk_all = (p.K + BK - 1) / BK;
-    const int kb = (int)((long long)nk_all * split / p.split_k);
-    const int nk = (int)((long long)nk_all * (split + 1) / p.split_k) - kb;
+    const int kb = (int)((long long)nk_all * split / nsplit);
+    const int nk = (int)((long long)nk_all * (split + 1) / nsplit) - kb;
 
     // ---- per-thread global->LDS assignment: 4-element chunks along the contiguous dim
     constexpr int A_CPR = (AMODE == A_COL) ? BM / 4 : BK / 4;   // chunks per stored row
@@ -539,7 +556,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_kernel(const KArgs p)
         __syncthreads();
     }
 
-    finish_tile<T>(p, acc, C, tile, split, tiles, m0, n0, wm0, wn0, interior);
+    finish_tile<T>(p, acc, C, slot, split, nsplit, m0, n0, wm0, wn0, interior);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -607,7 +624,8 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
     const int li = lane & 31, lh = lane >> 5;
 
     const int tiles = p.tiles_m * p.tiles_n;
-    const int split = blockIdx.x / tiles, tile = blockIdx.x - split * tiles;
+    int tile, split, nsplit, slot;
+    decode_block(p, tiles, tile, split, nsplit, slot);
     int tm, tn;
     tile_coords(p, tile, tm, tn);
     const int m0 = tm * BM, n0 = tn * BN;
@@ -617,8 +635,8 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
 
     const bool interior = !EDGE || (m0 + BM <= p.m_main && n0 + BN <= p.n_main);
     const int nk_all = (p.K + BK - 1) / BK;
-    const int kb = (int)((long long)nk_all * split / p.split_k);
-    const int nk = (int)((long long)nk_all * (split + 1) / p.split_k) - kb;
+    const int kb = (int)((long long)nk_all * split / nsplit);
+    const int nk = (int)((long long)nk_all * (split + 1) / nsplit) - kb;
 
     // Leading steps of this workgroup whose chunks are all whole (inside or outside).
     int n_direct = nk;
@@ -930,12 +948,12 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
         cur = nxt;
     }
 
-    finish_tile<T>(p, acc, C, tile, split, tiles, m0, n0, wm0, wn0, interior);
+    finish_tile<T>(p, acc, C, slot, split, nsplit, m0, n0, wm0, wn0, interior);
 }
 
 template <class T, int AMODE>
 hipError_t launch_mode(int variant, const KArgs& a, int batch, hipStream_t s) {
-    const dim3 grid(a.tiles_m * a.tiles_n * a.split_k, batch, 1), block(T::NT, 1, 1);
+    const dim3 grid(a.split_first + (a.tiles_m * a.tiles_n - a.split_first) * a.split_k, batch, 1), block(T::NT, 1, 1);
     void (*fn)(const KArgs) = nullptr;
     int bytes;
     if constexpr ((AMODE == A_ROW_BT || AMODE == A_COL_BT) && T::SCHED < 4) {

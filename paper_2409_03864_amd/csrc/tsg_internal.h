@@ -29,10 +29,13 @@ struct KArgs {
     int k_full;              // number of complete BK steps (the rest of k is masked)
     unsigned flags;
     int raster;
-    // split of the k loop over `split_k` workgroups per tile (1 = none); partial tiles meet in
-    // `ws` ([batch][tile][split][BM*BN] floats, register order) and `counters` ([batch][tile])
-    // counts the arrivals: the last workgroup to arrive sums the partials in split order
+    // split of the k loop over `split_k` workgroups per tile (1 = none) for the tiles from
+    // `split_first` on; partial tiles meet in `ws` ([batch][split tile][split][BM*BN] floats,
+    // register order) and `counters` ([batch][split tile]) counts the arrivals: the last
+    // workgroup to arrive sums the partials in split order.  Workgroup ids below split_first
+    // are whole tiles; the rest are (split index, split tile) with the split index slow.
     int split_k;
+    int split_first;   // tiles below this index are not split (0: the split applies to every tile)
     float* ws;
     int* counters;
     // convolution geometry (A_CONV only)

@@ -256,6 +256,52 @@ def test_split_k_batched_paper_loop_nest(workspace):
         assert nw <= TOL[dt] and cw <= TOL[dt], (i, nw, cw)
 
 
+@pytest.mark.parametrize("dtype", [tsg.F32, tsg.BF16_F32ACC])
+@pytest.mark.parametrize("trans_a", [False, True])
+def test_split_tail_only_bit_exact(dtype, trans_a, workspace):
+    """Only the tiles past the last full round of 256 are split: 17 x 16 tiles of 64 x 64
+    (ragged in M, a k remainder), so 256 whole tiles and 16 split ones in one launch, in the
+    register-staged and the direct-to-LDS form, both rasters, twice on the same workspace;
+    then the same with two batch entries.  Integer data: bit for bit against the oracle."""
+    op = tsg.OP_GEMM_TRANSA if trans_a else tsg.OP_GEMM
+    vmax = 4 if dtype == tsg.F32 else 8
+    M, N, K = 17 * 64 - 10, 1024, 330
+    A, B = inputs(M, N, K, 77, "ints", trans_a, dtype)
+    R = oracle.gemm(A, B, trans_a=trans_a, with_s=False)
+    C0 = synth.small_ints(8, 2, M * N).reshape(M, N)
+    for sched, raster in ((0 if dtype == tsg.F32 else 1, 0), (4, 1)):
+        for split in (2, 4):
+            c = tsg.TileConfig(bm=64, bn=64, bk=64, wm=32, wn=32, vec=vmax, raster=raster, sched=sched,
+                               split_k=split, split_tail=1)
+            assert tsg.tile_config_check(op, dtype, M, N, K, c) == tsg.OK
+            assert tsg.workspace_bytes(dtype, 1, M, N, c) == 65536 + 16 * split * 64 * 64 * 4
+            tsg.tile_config_set(op, dtype, c)
+            for rep in range(2):
+                C = run_gemm(dtype, A, B, trans_a=trans_a, flags=tsg.STRICT)
+                li = tsg.last_launch()
+                assert li.alternative == 0 and li.config.split_k == split and li.config.split_tail == 1
+                assert np.array_equal(C.astype(np.float64), R), (sched, split, rep)
+            fl = tsg.STRICT | tsg.NEGATE | tsg.ACCUMULATE
+            C = run_gemm(dtype, A, B, trans_a=trans_a, flags=fl, C0=C0)
+            assert np.array_equal(C.astype(np.float64), C0 - R), (sched, split)
+    # batched: each entry has its own 16 split tiles, counters and partials
+    nb = 2
+    A2 = np.stack([A, A[::-1].copy()])
+    B2 = np.stack([B, B[:, ::-1].copy()])
+    dA, dB = dev(A2), dev(B2)
+    dC = torch.full((nb, M, N), 7.0, dtype=torch.float32, device=DEV)
+    ar, ac = A.shape
+    tsg.gemm_batched(dtype, trans_a, nb, M, N, K, dA, ac, ar * ac, dB, N, K * N, dC, N, M * N, tsg.STRICT)
+    torch.cuda.synchronize()
+    assert tsg.last_launch().config.split_tail == 1
+    out = dC.cpu().numpy()
+    for i in range(nb):
+        assert np.array_equal(out[i].astype(np.float64), oracle.gemm(A2[i], B2[i], trans_a=trans_a, with_s=False)), i
+    # a shape whose tile count is a multiple of 256 has no tail: silenceable, output untouched
+    with pytest.raises(tsg.SilenceableError):
+        tsg.gemm_batched(dtype, trans_a, nb, 1024, N, K, dA, ac, ar * ac, dB, N, K * N, dC, N, M * N, tsg.STRICT)
+
+
 def test_one_hot_and_identity_on_device():
     M, N, K = 150, 140, 130
     B = synth.uniform_pm1(2, 1, K * N).reshape(K, N)

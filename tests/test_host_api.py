@@ -55,8 +55,13 @@ def test_search_space_enumeration():
                 assert key not in seen
                 seen.add(key)
                 # the direct-to-LDS forms (sched 4, 5) have no scalar-access variant
-                want = tsg.E_SILENCEABLE if (c.vec == 1 and c.sched >= 4) else tsg.OK
-                assert tsg.tile_config_check(op, dt, 4096, 4096, 4096, c, contig=64) == want
+                # and a tail-only split needs a tile count that leaves a tail after rounds of 256
+                assert c.split_tail in (0, 1) and (c.split_k > 1 or not c.split_tail)
+                for ext in (4096, 4000 + 96 * 3):
+                    tiles = -(-ext // c.bm) * -(-ext // c.bn)
+                    bad = (c.vec == 1 and c.sched >= 4) or (c.split_tail and tiles % 256 == 0)
+                    want = tsg.E_SILENCEABLE if bad else tsg.OK
+                    assert tsg.tile_config_check(op, dt, ext, ext, 4096, c, contig=64) == want
             with pytest.raises(tsg.TsgError):
                 tsg.tile_config_enum(op, dt, n)
     assert tsg.tile_config_count(7, 0) == 0
@@ -109,6 +114,17 @@ def test_split_k_legality_and_workspace_size():
     assert tsg.workspace_bytes(dt, 6, 196, 256, c) == 65536 + 6 * tiles * 4 * 64 * 64 * 4
     c.split_k = 1
     assert tsg.workspace_bytes(dt, 6, 196, 256, c) == 0
+    # tail-only split: only the tiles past the last full round of 256 take workspace
+    c.split_k, c.split_tail = 4, 1
+    assert tsg.tile_config_check(op, dt, 196, 256, 2305, c) == tsg.OK          # 16 tiles, all tail
+    assert tsg.workspace_bytes(dt, 6, 196, 256, c) == 65536 + 6 * tiles * 4 * 64 * 64 * 4
+    assert tsg.tile_config_check(op, dt, 1024, 1024, 2305, c) == tsg.E_SILENCEABLE   # 256 tiles, no tail
+    assert tsg.tile_config_check(op, dt, 1024 + 64, 1024, 2305, c) == tsg.OK         # 272 tiles
+    assert tsg.workspace_bytes(dt, 2, 1024 + 64, 1024, c) == 65536 + 2 * 16 * 4 * 64 * 64 * 4
+    c.split_k = 1
+    assert tsg.tile_config_check(op, dt, 1024 + 64, 1024, 2305, c) == tsg.E_SILENCEABLE
+    c.split_k, c.split_tail = 4, 2
+    assert tsg.tile_config_check(op, dt, 1024 + 64, 1024, 2305, c) == tsg.E_INVALID
     # a workspace must be a 256-byte aligned device buffer larger than the counter area
     for ws, nbytes in ((FAKE + 4, 1 << 20), (FAKE, 1024), (FAKE, 0)):
         with pytest.raises(tsg.TsgError) as e:
@@ -247,11 +263,11 @@ def test_tune_cache_save_load_roundtrip(tmp_path):
     default = tsg.tile_config_get(op, dt, 1000, 900, 800).as_dict()
     f = tmp_path / "tuned.txt"
     f.write_text("# comment\n"
-                 "0 0 0 1 1000 900 800 0  128 128 32 64 64 4 0 0 1  0.5\n"     # instantiated
-                 "0 0 0 1 1000 900 801 0  96 96 32 32 32 4 0 0 1  0.5\n"       # not instantiated
-                 "0 0 0 1 1000 900 802 0  128 128 32 64 64 3 0 0 1  0.5\n"     # no such access width
+                 "0 0 0 1 1000 900 800 0  128 128 32 64 64 4 0 0 1 0  0.5\n"     # instantiated
+                 "0 0 0 1 1000 900 801 0  96 96 32 32 32 4 0 0 1 0  0.5\n"       # not instantiated
+                 "0 0 0 1 1000 900 802 0  128 128 32 64 64 3 0 0 1 0  0.5\n"     # no such access width
                  "garbage line\n"
-                 "1 1 1 6 196 256 2305 0  64 64 64 32 32 8 1 4 2  0.03\n")
+                 "1 1 1 6 196 256 2305 0  64 64 64 32 32 8 1 4 2 1  0.03\n")
     assert tsg.tune_cache_load(str(f)) == (2, 3)
     assert tsg.tune_cache_size() == 2
     got = tsg.tile_config_get(op, dt, 1000, 900, 800).as_dict()
