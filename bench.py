@@ -95,8 +95,9 @@ def describe(k, c) -> str:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=None,
+                    help="timed steps (default: 100, or as many as make the timed region last 0.2 s)")
+    ap.add_argument("--warmup", type=int, default=None, help="untimed steps before them (default: a tenth of --steps)")
     ap.add_argument("--workload", type=int, default=3, choices=[1, 2, 3, 4, 5, 6, 7])
     ap.add_argument("--no-tune", action="store_true", help="use the shape heuristic instead of the tuner")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
@@ -104,7 +105,7 @@ def main() -> int:
                     help="record the K steps once into a HIP graph and time one replay (launch-bound workloads)")
     ap.add_argument("--evals", type=int, default=0, help="tuner budget: timed points, in cost-model order (0 = all)")
     ap.add_argument("--cpu-rows", type=int, default=4096, help="rows of the product the oracle is timed on")
-    ap.add_argument("--pin", default="", help="bm,bn,bk,wm,wn,vec,raster,sched[,split_k]: pin this tile config instead of tuning")
+    ap.add_argument("--pin", default="", help="bm,bn,bk,wm,wn,vec,raster,sched[,split_k[,split_tail]]: pin this tile config instead of tuning")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="also run one plain device copy of this many MiB (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -217,7 +218,8 @@ def main() -> int:
     if args.pin:
         v = [int(t) for t in args.pin.split(",")]
         tsg.tile_config_set(op, dt, tsg.TileConfig(bm=v[0], bn=v[1], bk=v[2], wm=v[3], wn=v[4], vec=v[5], raster=v[6], sched=v[7],
-                                                   split_k=(v[8] if len(v) > 8 else 1)))
+                                                   split_k=(v[8] if len(v) > 8 else 1),
+                                                   split_tail=(v[9] if len(v) > 9 else 0)))
         args.no_tune = True
     if not args.no_tune:
         tsg.search_set(args.evals, True)
@@ -232,6 +234,21 @@ def main() -> int:
             log("  tuner: %s -> %.4f ms (best so far %.4f)" % (r.config, r.ms, r.best_ms))
         log("tuner picked %s at %.4f ms" % (best, best_ms))
 
+    # A step of the small workloads takes tens of microseconds, and the first few milliseconds
+    # after an idle period run at a lower clock: unless the caller fixes the count, time enough
+    # steps for 0.2 s
+    if args.steps is None:
+        for _ in range(20):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(20):
+            step()
+        torch.cuda.synchronize()
+        est = (time.perf_counter() - t0) / 20
+        args.steps = max(100, min(1000 if args.graph else 20000, int(0.2 / est)))
+    if args.warmup is None:
+        args.warmup = max(10, args.steps // 10)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

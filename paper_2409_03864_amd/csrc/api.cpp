@@ -308,6 +308,24 @@ tsg_status enqueue(const Problem& p, const Plan& pl, hipStream_t s) {
     return TSG_OK;
 }
 
+// The cost model's pick walks the whole table times the splits, which is worth remembering in
+// a loop that calls the same problem again and again: the last few problems of each thread.
+tsg_tile_config heuristic_cached(tsg_dtype dt, int64_t batch, int64_t M, int64_t N, int64_t K, int64_t ws_bytes,
+                                 bool trans_b) {
+    struct Memo { int64_t key[7]; tsg_tile_config cfg; bool used; };
+    thread_local Memo memo[8] = {};
+    thread_local int next = 0;
+    const int64_t key[7] = {(int64_t)dt, batch, M, N, K, ws_bytes, (int64_t)trans_b};
+    for (const Memo& m : memo)
+        if (m.used && std::memcmp(m.key, key, sizeof key) == 0) return m.cfg;
+    Memo& m = memo[next];
+    next = (next + 1) % 8;
+    std::memcpy(m.key, key, sizeof key);
+    m.cfg = heuristic(dt, batch, M, N, K, ws_bytes, trans_b);
+    m.used = true;
+    return m.cfg;
+}
+
 // The chain of alternatives (Case Study 4: try, and on a silenceable failure fall through
 // to the next region): the caller's pinned config, else the tuner's result for this problem
 // -> the cost model's default -> that tile with scalar accesses, which has no precondition
@@ -326,12 +344,12 @@ tsg_status run(const Problem& p, hipStream_t s) {
         }
         ws_bytes = g_ws ? g_ws_bytes : 0;
     }
-    const tsg_tile_config heur = heuristic(p.dtype, p.batch, p.M, p.N, p.K, ws_bytes, p.trans_b);
     Plan pl;
     if (pinned) {
         if (make_plan(p, pin, 0, &pl) == TSG_OK) return enqueue(p, pl, s);
         if (p.flags & TSG_STRICT) return TSG_E_SILENCEABLE;
     }
+    const tsg_tile_config heur = heuristic_cached(p.dtype, p.batch, p.M, p.N, p.K, ws_bytes, p.trans_b);
     if (make_plan(p, heur, 1, &pl) == TSG_OK) return enqueue(p, pl, s);
     if ((p.flags & TSG_STRICT) || p.trans_b) return TSG_E_SILENCEABLE;   // no scalar form with a transposed B
     // last alternative: scalar accesses, which have no precondition.  The direct-to-LDS forms

@@ -508,6 +508,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
     int a_k[PA];
     bool a_in[PA];
     int cv_base[PA], cv_hi0[PA], cv_wi0[PA];
+    long long cv_off[PA];   // element offset of tap (0, 0), channel a_k of the chunk's pixel (may lie outside the tensor)
 #pragma unroll
     for (int q = 0; q < PA; ++q) {
         const int row = a_r + q * A_RPP;
@@ -531,6 +532,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
             cv_base[q] = n * p.H;
             cv_hi0[q] = ho * p.sh - p.ph;
             cv_wi0[q] = wo * p.sw - p.pw;
+            cv_off[q] = ((long long)(cv_base[q] + cv_hi0[q]) * p.W + cv_wi0[q]) * p.Cin + a_k[q];
         }
     }
     int cs_kh = 0, cs_kw = 0, cs_ci = 0;
@@ -573,17 +575,21 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
                 const bool in = a_in[q] && (!EDGE || k0 + a_k[q] < p.K);
                 src = in ? a_src[q] + (long long)k0 * p.lda : g_zero_chunk;
             } else {
-                const int k = k0 + a_k[q];
-                int kh = cs_kh, kw = cs_kw, ci = cs_ci + a_k[q];
-                if (!one_tap) {
-                    const int tap = k / p.Cin;
-                    ci = k - tap * p.Cin;
-                    kh = tap / p.KW;
-                    kw = tap - kh * p.KW;
+                if (one_tap) {
+                    // the whole step lies in tap (cs_kh, cs_kw), whose offset is the same for every
+                    // thread: scalar arithmetic, then one add and two compares per chunk
+                    const int hi = cv_hi0[q] + cs_kh, wi = cv_wi0[q] + cs_kw;
+                    const bool in = a_in[q] && (unsigned)hi < (unsigned)p.H && (unsigned)wi < (unsigned)p.W;
+                    const long long tap_off = ((long long)cs_kh * p.W + cs_kw) * p.Cin + cs_ci;
+                    src = in ? A + (cv_off[q] + tap_off) : g_zero_chunk;
+                } else {
+                    const int k = k0 + a_k[q];
+                    const int tap = k / p.Cin, ci = k - tap * p.Cin;
+                    const int kh = tap / p.KW, kw = tap - kh * p.KW;
+                    const int hi = cv_hi0[q] + kh, wi = cv_wi0[q] + kw;
+                    const bool in = a_in[q] && k < p.K && hi >= 0 && hi < p.H && wi >= 0 && wi < p.W;
+                    src = in ? A + ((long long)(cv_base[q] + hi) * p.W + wi) * p.Cin + ci : g_zero_chunk;
                 }
-                const int hi = cv_hi0[q] + kh, wi = cv_wi0[q] + kw;
-                const bool in = a_in[q] && k < p.K && hi >= 0 && hi < p.H && wi >= 0 && wi < p.W;
-                src = in ? A + ((long long)(cv_base[q] + hi) * p.W + wi) * p.Cin + ci : g_zero_chunk;
             }
             load_to_lds16(src, as + (unsigned)(q * NT) * 16u);
         }
@@ -688,17 +694,21 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
                 const bool in = a_in[q] && (!EDGE || k0 + a_k[q] < p.K);
                 src = in ? a_src[q] + (long long)k0 * p.lda : g_zero_chunk;
             } else {
-                const int k = k0 + a_k[q];
-                int kh = cs_kh, kw = cs_kw, ci = cs_ci + a_k[q];
-                if (!one_tap) {
-                    const int tap = k / p.Cin;
-                    ci = k - tap * p.Cin;
-                    kh = tap / p.KW;
-                    kw = tap - kh * p.KW;
+                if (one_tap) {
+                    // the whole step lies in tap (cs_kh, cs_kw), whose offset is the same for every
+                    // thread: scalar arithmetic, then one add and two compares per chunk
+                    const int hi = cv_hi0[q] + cs_kh, wi = cv_wi0[q] + cs_kw;
+                    const bool in = a_in[q] && (unsigned)hi < (unsigned)p.H && (unsigned)wi < (unsigned)p.W;
+                    const long long tap_off = ((long long)cs_kh * p.W + cs_kw) * p.Cin + cs_ci;
+                    src = in ? A + (cv_off[q] + tap_off) : g_zero_chunk;
+                } else {
+                    const int k = k0 + a_k[q];
+                    const int tap = k / p.Cin, ci = k - tap * p.Cin;
+                    const int kh = tap / p.KW, kw = tap - kh * p.KW;
+                    const int hi = cv_hi0[q] + kh, wi = cv_wi0[q] + kw;
+                    const bool in = a_in[q] && k < p.K && hi >= 0 && hi < p.H && wi >= 0 && wi < p.W;
+                    src = in ? A + ((long long)(cv_base[q] + hi) * p.W + wi) * p.Cin + ci : g_zero_chunk;
                 }
-                const int hi = cv_hi0[q] + kh, wi = cv_wi0[q] + kw;
-                const bool in = a_in[q] && k < p.K && hi >= 0 && hi < p.H && wi >= 0 && wi < p.W;
-                src = in ? A + ((long long)(cv_base[q] + hi) * p.W + wi) * p.Cin + ci : g_zero_chunk;
             }
             load_to_lds16(src, as + (unsigned)(q * NT) * 16u);
         } else {
@@ -776,8 +786,15 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
                 else wait_loads_outstanding<0>();
                 __syncthreads();
             }
-            constexpr int NX = LPT + NFRAG;
-            constexpr int PER = (NX + NM - 1) / NM;
+            // Behind the MFMAs of this group: first the fragments of the next one, all of them within
+            // the first quarter of the group (a wave that is alone on its SIMD has nobody to hide an
+            // LDS wait behind), then, in a step's last group, the loads of tile kt+D.
+            constexpr int FQ = NM / 4 > 0 ? NM / 4 : 1;
+            constexpr int FPER = (NFRAG + FQ - 1) / FQ;      // fragment reads behind one MFMA
+            constexpr int FM = (NFRAG + FPER - 1) / FPER;    // MFMAs that carry them
+            constexpr int LM = NM - FM > 0 ? NM - FM : 1;    // MFMAs that carry loads: the rest, or the last one
+            constexpr int L0 = NM - LM;
+            constexpr int LPER = (LPT + LM - 1) / LM;
 #pragma unroll
             for (int m = 0; m < NM; ++m) {
                 const int i = m / NI, j = m % NI;
@@ -788,16 +805,21 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
                 if constexpr (B_KMAJ) b = bfull[g & 1][j];
                 else b = __builtin_shufflevector(bh[g & 1][j][0], bh[g & 1][j][1], 0, 1, 2, 3, 4, 5, 6, 7);
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i][j], 0, 0, 0);
+                if (m < FM) {
 #pragma unroll
-                for (int u = 0; u < PER; ++u) {
-                    const int e = m * PER + u;
-                    if (e >= NX) continue;
-                    if (e < LPT) {
-                        if (last && kt + D < nk) issue_part(kt + D, fill, e);
-                    } else if (last) {
-                        frag_read(nxt, 0, e - LPT);
-                    } else {
-                        frag_read(cur, g + 1, e - LPT);
+                    for (int u = 0; u < FPER; ++u) {
+                        const int e = m * FPER + u;
+                        if (e >= NFRAG) continue;
+                        if (last) frag_read(nxt, 0, e);   // after the last step this reads a stage nobody multiplies
+                        else frag_read(cur, g + 1, e);
+                    }
+                }
+                if (last && m >= L0) {
+#pragma unroll
+                    for (int u = 0; u < LPER; ++u) {
+                        const int e = (m - L0) * LPER + u;
+                        if (e >= LPT) continue;
+                        if (kt + D < nk) issue_part(kt + D, fill, e);
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);
