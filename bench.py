@@ -85,9 +85,10 @@ def describe(k, c) -> str:
         return "cfg%d: %s full additive reduce of a %d x %d tensor, %s entries, seed %d" % (
             k, c["dtype"], c["rows"], c["cols"], c["dist"], c["seed"])
     if c["op"] == "conv2d_nhwc":
-        return ("cfg%d: %s conv2d NHWC N=%d H=W=%d Cin=%d Cout=%d %dx%d stride %d pad %d, seed %d"
+        return ("cfg%d: %s conv2d NHWC N=%d H=W=%d Cin=%d Cout=%d %dx%d stride %d pad %d, seed %d%s"
                 % (k, c["dtype"], c["N"], c["H"], c["Cin"], c["Cout"], c["KH"], c["KW"], c["stride"], c["pad"],
-                   c["seed"]))
+                   c["seed"], ", added into the interior of a tensor with a ring of %d pixels" % c["window_ring"]
+                   if c.get("window_ring") else ""))
     return "cfg%d: %s %s %sM=%d N=%d K=%d, %s entries, seed %d%s" % (
         k, c["dtype"], c["op"], "batch=%d " % c["B"] if "B" in c else "", c["M"], c["N"], c["K"], c["dist"], c["seed"],
         ", negate fused" if "negate" in c["flags"] else "")
@@ -99,7 +100,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=None,
                     help="timed steps (default: 100, or as many as make the timed region last 0.2 s)")
     ap.add_argument("--warmup", type=int, default=None, help="untimed steps before them (default: a tenth of --steps)")
-    ap.add_argument("--workload", type=int, default=3, choices=[1, 2, 3, 4, 5, 6, 7])
+    ap.add_argument("--workload", type=int, default=3, choices=list(range(1, 11)))
     ap.add_argument("--no-tune", action="store_true", help="use the shape heuristic instead of the tuner")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--graph", action="store_true",
@@ -132,7 +133,7 @@ def main() -> int:
     c, a, b = synth.config_inputs(k)
     log("inputs generated in %.1f s: %s" % (time.time() - t0, describe(k, c)))
     dt = tsg.F32 if c["dtype"] == "f32" else tsg.BF16_F32ACC
-    flags = tsg.NEGATE if "negate" in c["flags"] else 0
+    flags = (tsg.NEGATE if "negate" in c["flags"] else 0) | (tsg.ACCUMULATE if "accumulate" in c["flags"] else 0)
 
     def up(x):
         x = np.ascontiguousarray(x)
@@ -167,11 +168,22 @@ def main() -> int:
         M, N, K = c["N"] * Ho * Ho, c["Cout"], c["KH"] * c["KW"] * c["Cin"]
 
         pC = dC.data_ptr()
+        ring = c.get("window_ring", 0)
+        if ring:
+            # y is the interior of a larger tensor: the call adds into it in place
+            big = torch.zeros((c["N"], Ho + 2 * ring, Ho + 2 * ring, c["Cout"]), dtype=torch.float32, device=dev)
+            sw_ = c["Cout"]
+            sh_ = (Ho + 2 * ring) * sw_
+            sn_ = (Ho + 2 * ring) * sh_
+            pW = big.data_ptr() + 4 * (ring * sh_ + ring * sw_)
 
-        def step():
-            tsg.conv2d_nhwc(dt, *geom, pA, pB, pC, flags, st)
+            def step():
+                tsg.conv2d_nhwc_window(dt, *geom, pA, pB, pW, sn_, sh_, sw_, flags, st)
+        else:
+            def step():
+                tsg.conv2d_nhwc(dt, *geom, pA, pB, pC, flags, st)
 
-        def tune():
+        def tune():   # the window only changes where the epilogue writes: the layer's tuning serves both
             return tsg.autotune_conv2d_nhwc(dt, *geom, dA, dB, dC, flags, iters=tune_iters)
     elif c["op"] == "gemm_batched":
         nb, M, N, K = c["B"], c["M"], c["N"], c["K"]
@@ -186,6 +198,18 @@ def main() -> int:
         def tune():
             return tsg.autotune_gemm_batched(dt, False, nb, M, N, K, dA, K, M * K, dB, N, K * N, dC, N, M * N,
                                              flags, iters=tune_iters)
+    elif c["op"] == "gemm_trans":
+        M, N, K = c["M"], c["N"], c["K"]
+        op = tsg.OP_GEMM_TRANSA
+        dC = torch.zeros((M, N), dtype=torch.float32, device=dev)
+        pC = dC.data_ptr()
+
+        def step():
+            tsg.gemm_trans(dt, True, True, 1, M, N, K, pA, M, 0, pB, K, 0, pC, N, 0, flags, st)
+
+        def tune():
+            return tsg.autotune_gemm_trans(dt, True, True, 1, M, N, K, dA, M, 0, dB, K, 0, dC, N, 0, flags,
+                                           iters=tune_iters)
     else:
         M, N, K = c["M"], c["N"], c["K"]
         trans = c["op"] == "gemm_transA"
@@ -316,17 +340,17 @@ def main() -> int:
                    "sample": "rows 0..%d (%d elements, fp64 sum)" % (sub.shape[0] - 1, sub.size),
                    "seconds": round(dtc, 3)}
         elif c["op"] == "conv2d_nhwc":
-            xs = a[:1]
             t0 = time.perf_counter()
-            oracle.conv2d_nhwc(xs, b, stride=(c["stride"],) * 2, pad=(c["pad"],) * 2, with_s=False)
+            oracle.conv2d_nhwc(a, b, stride=(c["stride"],) * 2, pad=(c["pad"],) * 2, with_s=False)
             dtc = time.perf_counter() - t0
-            sflops, sample = flops // c["N"], "image 0 of %d (direct convolution)" % c["N"]
+            sflops, sample = flops, "the whole layer, all %d images (direct convolution)" % c["N"]
         else:
             rows = min(args.cpu_rows, M)
             a0, b0 = (a[0], b[0]) if c["op"] == "gemm_batched" else (a, b)
-            sub = np.ascontiguousarray(a0[:, :rows] if c["op"] == "gemm_transA" else a0[:rows])
+            ta, tb = c["op"] in ("gemm_transA", "gemm_trans"), c["op"] == "gemm_trans"
+            sub = np.ascontiguousarray(a0[:, :rows] if ta else a0[:rows])
             t0 = time.perf_counter()
-            oracle.gemm(sub, b0, trans_a=(c["op"] == "gemm_transA"), with_s=False)
+            oracle.gemm(sub, b0, trans_a=ta, trans_b=tb, with_s=False)
             dtc = time.perf_counter() - t0
             sflops, sample = 2 * rows * N * K, "rows 0..%d of C%s (%d x %d x %d triple loop)" % (
                 rows - 1, " of batch 0" if c["op"] == "gemm_batched" else "", rows, N, K)

@@ -130,27 +130,69 @@ __device__ __forceinline__ void finish_tile(const KArgs& p, f32x16 (&acc)[T::MI]
         if (tid == 0) p.counters[slot] = 0;   // ready for the next launch on this workspace
     }
 
+    // With ACCUMULATE the old values of a block are all loaded before its first store: a load
+    // behind a store to an address the compiler cannot tell apart would wait for it, one round
+    // trip to memory per element.
     const bool neg = p.flags & FLAG_NEGATE, accum = p.flags & FLAG_ACCUMULATE;
+    if (p.y_window) {
+        // output pixel row -> (n, ho, wo) -> its place in the larger tensor.  A lane holds runs of
+        // four consecutive rows: the first of a run is decoded, the others step from it
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int rg = 0; rg < 4; ++rg) {
+                const int row0 = m0 + wm0 + i * 32 + 8 * rg + 4 * lh;
+                int wo = row0 % p.Wo, t = row0 / p.Wo;
+                int ho = t % p.Ho, n = t / p.Ho;
+                float* dst[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    dst[e] = C + ((long long)n * p.y_sn + (long long)ho * p.y_sh + (long long)wo * p.y_sw) + n0 + wn0 + li;
+                    if (++wo == p.Wo) {
+                        wo = 0;
+                        if (++ho == p.Ho) { ho = 0; ++n; }
+                    }
+                }
+                float old[4][NI];
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int j = 0; j < NI; ++j) {
+                        const bool ok = interior || (row0 + e < p.M && n0 + wn0 + j * 32 + li < p.N);
+                        old[e][j] = (accum && ok) ? dst[e][j * 32] : 0.f;
+                    }
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+#pragma unroll
+                    for (int j = 0; j < NI; ++j) {
+                        const bool ok = interior || (row0 + e < p.M && n0 + wn0 + j * 32 + li < p.N);
+                        const float v = acc[i][j][rg * 4 + e];
+                        const float sv = neg ? -v : v;
+                        if (ok) dst[e][j * 32] = accum ? sv + old[e][j] : sv;   // no add without the flag: -0 stays -0
+                    }
+            }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < NI; ++j) {
             const int col = n0 + wn0 + j * 32 + li;
+            float* c0 = C + (long long)(m0 + wm0 + i * 32 + 4 * lh) * p.ldc + col;   // row of r = 0
+            float old[16];
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int row = m0 + wm0 + i * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
-                if (interior || (row < p.M && col < p.N)) {
-                    long long off = (long long)row * p.ldc;
-                    if (p.y_window) {   // output pixel row -> (n, ho, wo) -> its place in the larger tensor
-                        const int wo = row % p.Wo, t = row / p.Wo;
-                        off = (long long)(t / p.Ho) * p.y_sn + (long long)(t % p.Ho) * p.y_sh + (long long)wo * p.y_sw;
-                    }
-                    float* c = C + off + col;
-                    float v = acc[i][j][r];
-                    if (neg) v = -v;
-                    if (accum) v += *c;
-                    *c = v;
-                }
+                const int dr = 8 * (r >> 2) + (r & 3);
+                const bool ok = interior || (m0 + wm0 + i * 32 + 4 * lh + dr < p.M && col < p.N);
+                old[r] = (accum && ok) ? c0[(long long)dr * p.ldc] : 0.f;
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int dr = 8 * (r >> 2) + (r & 3);
+                const bool ok = interior || (m0 + wm0 + i * 32 + 4 * lh + dr < p.M && col < p.N);
+                const float v = acc[i][j][r];
+                const float sv = neg ? -v : v;
+                if (ok) c0[(long long)dr * p.ldc] = accum ? sv + old[r] : sv;   // no add without the flag: -0 stays -0
             }
         }
 }

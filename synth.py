@@ -146,6 +146,14 @@ CONFIGS = {
     6: dict(op="gemm_batched", dtype="f32", B=6, M=196, N=256, K=2305, dist="uniform", seed=5, flags=()),
     # the full additive reduce of Case Study 3 on a tensor larger than every cache (1 GiB)
     7: dict(op="reduce_sum", dtype="f32", rows=16384, cols=16384, dist="uniform", seed=6, flags=()),
+    # the rest of Case Study 3's rewrites on the contraction: the same layer in bf16; both
+    # operands stored transposed; the layer's result accumulated into the interior of a tensor
+    # with a ring of two more pixels (the sum with a zero-padded tensor, pad never formed)
+    8: dict(op="conv2d_nhwc", dtype="bf16", N=8, H=56, W=56, Cin=64, Cout=64, KH=3, KW=3,
+            stride=1, pad=1, seed=7, flags=()),
+    9: dict(op="gemm_trans", dtype="f32", M=4096, N=4096, K=4096, dist="normal", seed=8, flags=()),
+    10: dict(op="conv2d_nhwc", dtype="f32", N=8, H=56, W=56, Cin=64, Cout=64, KH=3, KW=3,
+             stride=1, pad=1, seed=9, flags=("accumulate",), window_ring=2),
 }
 
 PAPER_BATCH_MATMUL = dict(B=6, M=196, N=256, K=2305)
@@ -166,5 +174,11 @@ def config_inputs(k: int):
         a, b = gemm_inputs(c["M"], c["N"], c["K"], seed=c["seed"], dist=c["dist"],
                            trans_a=(c["op"] == "gemm_transA"), bf16=(c["dtype"] == "bf16"))
         return c, a, b
+    if c["op"] == "gemm_trans":
+        # A stored K x M and B stored N x K: the same streams as the plain product, reshaped
+        a, b = gemm_inputs(c["M"], c["N"], c["K"], seed=c["seed"], dist=c["dist"], trans_a=True)
+        return c, a, np.ascontiguousarray(b.reshape(c["N"], c["K"]))
     x, w = conv_inputs(c["N"], c["H"], c["W"], c["Cin"], c["Cout"], c["KH"], c["KW"], seed=c["seed"])
+    if c["dtype"] == "bf16":
+        x, w = f32_to_bf16_bits(x), f32_to_bf16_bits(w)
     return c, x, w

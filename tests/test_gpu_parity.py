@@ -602,6 +602,29 @@ def test_config4_conv_resnet_layer():
     assert nw <= 1e-4 and cw <= 1e-4, (nw, cw)
 
 
+def test_config4_conv_tail_only_split_full_size(workspace):
+    """The launch shape the tuner settles on for this layer: 392 tiles of 64 x 64, the 136 past
+    the first round of 256 split four ways.  Integer data at full size, bit for bit; then the
+    workload's own data within tolerance, and equal bits on a second call."""
+    c, x, w = synth.config_inputs(4)
+    op, dt = tsg.OP_CONV2D_NHWC, tsg.F32
+    cfg = tsg.TileConfig(bm=64, bn=64, bk=32, wm=32, wn=32, vec=4, raster=1, sched=4, split_k=4, split_tail=1)
+    assert tsg.tile_config_check(op, dt, 25088, 64, 576, cfg, contig=64) == tsg.OK
+    assert tsg.workspace_bytes(dt, 1, 25088, 64, cfg) == 65536 + 136 * 4 * 64 * 64 * 4
+    tsg.tile_config_set(op, dt, cfg)
+    xi, wi = synth.conv_inputs(8, 56, 56, 64, 64, 3, 3, seed=5, dist="ints")
+    yi = run_conv(dt, xi, wi, (1, 1), (1, 1), flags=tsg.STRICT)
+    li = tsg.last_launch()
+    assert li.alternative == 0 and li.config.split_tail == 1 and li.tiles_m == 392
+    assert np.array_equal(yi.astype(np.float64), oracle.conv2d_nhwc(xi, wi, pad=(1, 1), with_s=False))
+    y = run_conv(dt, x, w, (1, 1), (1, 1), flags=tsg.STRICT)
+    R, S = oracle.conv2d_nhwc(x, w, pad=(1, 1))
+    nw, cw = oracle.errors(y, R, S)
+    assert nw <= 1e-4 and cw <= 1e-4, (nw, cw)
+    y2 = run_conv(dt, x, w, (1, 1), (1, 1), flags=tsg.STRICT)
+    assert np.array_equal(y2.view(np.uint32), y.view(np.uint32))
+
+
 def test_config5_bf16_gemm_8192_negated_sampled_and_all_ones_full():
     c, A, B = synth.config_inputs(5)
     C = run_gemm(tsg.BF16_F32ACC, A, B, flags=tsg.NEGATE)
@@ -612,6 +635,69 @@ def test_config5_bf16_gemm_8192_negated_sampled_and_all_ones_full():
 
 
 # ------------------------------------------------------------------ search
+
+def test_config8_bf16_conv_resnet_layer():
+    """The layer of workload 4 with bfloat16 operands (rounded once on the host; the oracle
+    multiplies the same rounded values in fp64)."""
+    c, x, w = synth.config_inputs(8)
+    assert x.dtype == np.uint16 and w.dtype == np.uint16
+    y = run_conv(tsg.BF16_F32ACC, x, w, (1, 1), (1, 1))
+    assert tsg.last_launch().config.vec == 8
+    R, S = oracle.conv2d_nhwc(x, w, pad=(1, 1))
+    nw, cw = oracle.errors(y, R, S)
+    assert nw <= TOL[tsg.BF16_F32ACC] and cw <= TOL[tsg.BF16_F32ACC], (nw, cw)
+
+
+def test_config9_both_operands_transposed_4096_sampled():
+    """A stored K x M and B stored N x K at 4096^3: sampled rows and columns against the
+    oracle's own loop for the transposed right operand; then all-ones, every element = K."""
+    c, A, Bt = synth.config_inputs(9)
+    M = N = K = 4096
+    dA, dB = dev(A), dev(Bt)
+    dC = torch.full((M, N), -3.0, dtype=torch.float32, device=DEV)
+    tsg.gemm_trans(tsg.F32, True, True, 1, M, N, K, dA, M, 0, dB, K, 0, dC, N, 0, 0)
+    torch.cuda.synchronize()
+    li = tsg.last_launch()
+    assert li.config.sched >= 4 and li.edge == 0
+    C = dC.cpu().numpy()
+    rows = [0, 1, 255, 256, 2047, 4095]
+    R, S = oracle.gemm(np.ascontiguousarray(A[:, rows]), Bt, trans_a=True, trans_b=True)
+    nw, cw = oracle.errors(C[rows], R, S)
+    assert nw <= 1e-4 and cw <= 1e-4, (nw, cw)
+    cols = [0, 63, 64, 4095]
+    R, S = oracle.gemm(A, np.ascontiguousarray(Bt[cols]), trans_a=True, trans_b=True)
+    nw, cw = oracle.errors(C[:, cols], R, S)
+    assert nw <= 1e-4 and cw <= 1e-4, (nw, cw)
+    ones = torch.ones((K, M), dtype=torch.float32, device=DEV)
+    tsg.gemm_trans(tsg.F32, True, True, 1, M, N, K, ones, M, 0, ones, K, 0, dC, N, 0, 0)
+    torch.cuda.synchronize()
+    assert bool((dC == float(K)).all())
+
+
+def test_config10_conv_added_into_interior_full_size(workspace):
+    """Workload 10: the layer's result added into the interior of a tensor with a ring of two
+    pixels, the padded tensor never formed.  Against the oracle's explicit pad-then-add;
+    the ring must keep its bits."""
+    c, x, w = synth.config_inputs(10)
+    ring = c["window_ring"]
+    Nn, Ho, Co = 8, 56, 64
+    big0 = synth.uniform_pm1(12, 3, Nn * (Ho + 2 * ring) ** 2 * Co).reshape(Nn, Ho + 2 * ring, Ho + 2 * ring, Co)
+    dbig = dev(big0)
+    sw_ = Co
+    sh_ = (Ho + 2 * ring) * sw_
+    sn_ = (Ho + 2 * ring) * sh_
+    tsg.conv2d_nhwc_window(tsg.F32, 8, 56, 56, 64, 64, 3, 3, 1, 1, 1, 1, dev(x), dev(w),
+                           dbig.data_ptr() + 4 * (ring * sh_ + ring * sw_), sn_, sh_, sw_, tsg.ACCUMULATE)
+    torch.cuda.synchronize()
+    out = dbig.cpu().numpy()
+    R, S = oracle.conv2d_nhwc(x, w, pad=(1, 1))
+    ref = oracle.add_of_zero_pad(big0, R, (0, ring, ring, 0))
+    inner = (slice(None), slice(ring, ring + Ho), slice(ring, ring + Ho), slice(None))
+    nw, cw = oracle.errors(out[inner], ref[inner], S + np.abs(big0[inner]))
+    assert nw <= 1e-4 and cw <= 1e-4, (nw, cw)
+    mask = np.ones(big0.shape, bool); mask[inner] = False
+    assert np.array_equal(out[mask].view(np.uint32), big0[mask].view(np.uint32))
+
 
 def test_autotune_pins_the_fastest_legal_config():
     M, N, K = 512, 384, 256
