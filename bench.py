@@ -31,14 +31,17 @@ METRIC = "TFLOP/s and % of MI355X matrix peak, fp32 GEMM 4096^3 (1 GPU)"
 # An entry is reported only while the kernel sources still hash to the value it was taken
 # with and the launch uses the same tile config; otherwise `traffic` is null.
 TRAFFIC = {
-    1: [{"kernel_hash": "6b1957dee774b910", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 0, "split_k": 8, "split_tail": 0}, "bytes": 5196159}],
-    2: [{"kernel_hash": "6b1957dee774b910", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 1, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 29573142}],
-    3: [{"kernel_hash": "6b1957dee774b910", "tile": {"bm": 256, "bn": 256, "bk": 16, "wm": 128, "wn": 64, "vec": 4, "raster": 1, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 470754413},
-        {"kernel_hash": "6b1957dee774b910", "tile": {"bm": 256, "bn": 256, "bk": 16, "wm": 128, "wn": 64, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 713687976}],
-    4: [{"kernel_hash": "6b1957dee774b910", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 1, "sched": 4, "split_k": 4, "split_tail": 1}, "bytes": 23211402}],
-    5: [{"kernel_hash": "bdda5ab42a910df1", "tile": {"bm": 256, "bn": 256, "bk": 32, "wm": 128, "wn": 64, "vec": 8, "raster": 0, "sched": 5, "split_k": 1, "split_tail": 0}, "bytes": 1881386860}],
-    6: [{"kernel_hash": "6b1957dee774b910", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 8, "split_tail": 0}, "bytes": 96829692}],
-    7: [{"kernel_hash": "8cf17b77e81162e1", "tile": {}, "bytes": 1073772916}],
+    1: [{"kernel_hash": "2a4398268d753407", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 0, "split_k": 8, "split_tail": 0}, "bytes": 6160441}],
+    2: [{"kernel_hash": "2a4398268d753407", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 42057237}],
+    3: [{"kernel_hash": "2a4398268d753407", "tile": {"bm": 256, "bn": 256, "bk": 16, "wm": 128, "wn": 64, "vec": 4, "raster": 1, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 469923537},
+        {"kernel_hash": "2a4398268d753407", "tile": {"bm": 256, "bn": 256, "bk": 16, "wm": 128, "wn": 64, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 707450157}],
+    4: [{"kernel_hash": "2a4398268d753407", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 25403607}],
+    5: [{"kernel_hash": "587fe35b1d747f7e", "tile": {"bm": 256, "bn": 256, "bk": 32, "wm": 128, "wn": 64, "vec": 8, "raster": 1, "sched": 5, "split_k": 1, "split_tail": 0}, "bytes": 1886878293}],
+    6: [{"kernel_hash": "2a4398268d753407", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 8, "split_tail": 0}, "bytes": 103072302}],
+    7: [{"kernel_hash": "8cf17b77e81162e1", "tile": {}, "bytes": 1073778894}],
+    8: [{"kernel_hash": "587fe35b1d747f7e", "tile": {"bm": 64, "bn": 64, "bk": 64, "wm": 32, "wn": 32, "vec": 8, "raster": 1, "sched": 1, "split_k": 1, "split_tail": 0}, "bytes": 10398628}],
+    9: [{"kernel_hash": "2a4398268d753407", "tile": {"bm": 256, "bn": 256, "bk": 16, "wm": 128, "wn": 64, "vec": 4, "raster": 1, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 469979932}],
+    10: [{"kernel_hash": "2a4398268d753407", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 31862591}],
 }
 
 
