@@ -302,6 +302,27 @@ def test_split_tail_only_bit_exact(dtype, trans_a, workspace):
         tsg.gemm_batched(dtype, trans_a, nb, 1024, N, K, dA, ac, ar * ac, dB, N, K * N, dC, N, M * N, tsg.STRICT)
 
 
+def test_default_config_with_a_tail_only_split(workspace):
+    """With a workspace set the cost model's own pick for 1536^3 (576 tiles of 64 x 64, or 144
+    of 128 x 128: neither a multiple of 256) may split only the tail; whatever it picks, the
+    call without any pin or tuning must match the oracle bit for bit on integer data, on
+    sampled rows and columns, and say what it did."""
+    M = N = K = 1536
+    for dtype in (tsg.F32, tsg.BF16_F32ACC):
+        A, B = inputs(M, N, K, 91, "ints", False, dtype)
+        want = tsg.tile_config_get(tsg.OP_GEMM, dtype, M, N, K)
+        C = run_gemm(dtype, A, B)
+        li = tsg.last_launch()
+        assert li.alternative == 1 and li.config.as_dict() == want.as_dict()
+        if dtype == tsg.F32:
+            assert want.split_tail == 1 and want.split_k > 1     # the fp32 table has no tile that fills 256 CUs evenly here
+        rows = [0, 63, 64, 767, 1471, 1472, 1535]
+        assert np.array_equal(C[rows].astype(np.float64), oracle.gemm(np.ascontiguousarray(A[rows]), B, with_s=False))
+        cols = [0, 1, 1023, 1535]
+        assert np.array_equal(C[:, cols].astype(np.float64),
+                              oracle.gemm(A, np.ascontiguousarray(B[:, cols]), with_s=False))
+
+
 def test_one_hot_and_identity_on_device():
     M, N, K = 150, 140, 130
     B = synth.uniform_pm1(2, 1, K * N).reshape(K, N)
