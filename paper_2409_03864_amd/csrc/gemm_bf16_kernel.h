@@ -911,7 +911,6 @@ hipError_t launch_mode(int variant, const KArgs& a, int batch, hipStream_t s) {
     X(256, 256, 64, 128, 64, 2, 1)  \
     X(256, 256, 64, 128, 64, 2, 0)  \
     X(256, 256, 64, 64, 128, 2, 1)  \
-    X(256, 256, 64, 128, 128, 1, 1) \
     X(256, 256, 32, 128, 64, 2, 1)  \
     X(256, 128, 64, 64, 64, 2, 1)   \
     X(128, 128, 64, 64, 64, 2, 1)   \
@@ -921,6 +920,8 @@ hipError_t launch_mode(int variant, const KArgs& a, int batch, hipStream_t s) {
     X(64, 64, 64, 32, 32, 2, 0)     \
     X(256, 256, 32, 128, 64, 2, 4)  \
     X(256, 256, 32, 128, 64, 2, 5)  \
+    X(256, 256, 32, 128, 128, 1, 4) \
+    X(256, 256, 32, 128, 128, 1, 5) \
     X(256, 128, 64, 64, 64, 2, 4)   \
     X(128, 128, 64, 64, 64, 2, 4)   \
     X(128, 128, 32, 64, 64, 2, 5)   \
