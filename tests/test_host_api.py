@@ -301,3 +301,35 @@ def test_status_strings():
     assert "ok" in tsg.status_string(tsg.OK)
     assert "silenceable" in tsg.status_string(tsg.E_SILENCEABLE)
     assert "definite" in tsg.status_string(tsg.E_INVALID) and "definite" in tsg.status_string(tsg.E_RUNTIME)
+
+
+def test_bench_counts_and_traffic_lookup(monkeypatch):
+    """bench.py's own arithmetic: algorithmic flops (padding taps of the convolution are not
+    work), the refusal to run on more than one GPU, and the traffic table, which answers only
+    for the kernel sources and the tile config its figures were measured with."""
+    import subprocess
+    import sys
+    import bench
+    import synth
+    C = synth.CONFIGS
+    assert bench.workload_flops(C[1]) == 2 * 256 ** 3
+    assert bench.workload_flops(C[3]) == 137438953472
+    assert bench.workload_flops(C[5]) == 1099511627776
+    assert bench.workload_flops(C[6]) == 1387868160                      # 2 * 6 * 196 * 256 * 2305
+    assert bench.workload_flops(C[4]) == 2 * 8 * 166 * 166 * 64 * 64     # 166 valid taps per axis
+    assert bench.workload_flops(C[4]) == bench.workload_flops(C[8]) == bench.workload_flops(C[10])
+    assert bench.workload_flops(C[7]) == 16384 * 16384
+    for k, entries in bench.TRAFFIC.items():
+        for e in entries:
+            dtype, op = C[k]["dtype"], C[k]["op"]
+            monkeypatch.setattr(bench, "kernel_hash", lambda d, o="", h=e["kernel_hash"]: h)
+            assert bench.traffic_bytes(k, dtype, dict(e["tile"]), op) == e["bytes"]
+            if e["tile"]:
+                other = dict(e["tile"], bk=e["tile"]["bk"] * 2)
+                assert bench.traffic_bytes(k, dtype, other, op) in (None, *[x["bytes"] for x in entries if x is not e])
+            monkeypatch.setattr(bench, "kernel_hash", lambda d, o="": "changed")
+            assert bench.traffic_bytes(k, dtype, dict(e["tile"]), op) is None
+    monkeypatch.undo()
+    assert len(bench.kernel_hash("f32")) == 16 and bench.kernel_hash("f32") != bench.kernel_hash("bf16")
+    r = subprocess.run([sys.executable, bench.__file__, "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr and r.stdout == ""
