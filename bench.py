@@ -255,8 +255,10 @@ def main() -> int:
         tuner_log = [dict(r.config.as_dict(), ms=round(r.ms, 5), predicted_ms=round(r.predicted_ms, 5)) for r in recs]
         timed = [r for r in recs if r.ms >= 0]
         # the first timed point is the cost model's pick, i.e. what a call without tuning uses
+        # how many points, in the cost model's order, it took to get within 1 % of the final best
+        reach = next(i + 1 for i, r in enumerate(timed) if r.best_ms <= best_ms * 1.01)
         search = {"evaluations": len(timed), "default_ms": timed[0].ms, "best_ms": best_ms,
-                  "speedup_vs_default": timed[0].ms / best_ms,
+                  "speedup_vs_default": timed[0].ms / best_ms, "evaluations_to_within_1pct": reach,
                   "best_so_far_ms": [round(r.best_ms, 5) for r in timed]}
         for r in recs:
             log("  tuner: %s -> %.4f ms (best so far %.4f)" % (r.config, r.ms, r.best_ms))
