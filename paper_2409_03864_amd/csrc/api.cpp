@@ -268,7 +268,13 @@ tsg_status make_plan(const Problem& p, const tsg_tile_config& cfg, int alternati
     const bool edge = m_rest || n_rest || k_rest;
     out->entry = e;
     out->cfg = cfg;
-    out->variant = cfg.vec == 1 ? 2 : (edge ? 1 : 0);
+    // remainder variant 3: no chunk of an operand is cut by the end of a row, i.e. the extent
+    // along which each operand is contiguous is a multiple of the access width
+    const int64_t v = vec_max(p.dtype);
+    const bool a_k_contig = p.op != TSG_OP_GEMM_TRANSA;   // A rows run along k (also the gathered operand: Cin % v == 0)
+    const bool cut = (!p.trans_b && p.N % v) || (p.op == TSG_OP_GEMM_TRANSA && p.M % v) ||
+                     (((a_k_contig && p.op != TSG_OP_CONV2D_NHWC) || p.trans_b) && p.K % v);
+    out->variant = cfg.vec == 1 ? 2 : (edge ? (cut ? 1 : 3) : 0);
 
     KArgs& a = out->args;
     std::memset(&a, 0, sizeof a);

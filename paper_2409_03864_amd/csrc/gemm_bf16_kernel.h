@@ -10,6 +10,8 @@
 // group at row k0 + s/4, columns j0 + 4*(s%4) .. +3 therefore hands lane l the four
 // values B[k0 .. k0+3][j0 + l]: no transposition in registers or on the store side.
 #pragma once
+#include <type_traits>
+
 #include "tsg_internal.h"
 
 namespace tsg {
@@ -134,6 +136,11 @@ __device__ __forceinline__ void finish_tile(const KArgs& p, f32x16 (&acc)[T::MI]
     // behind a store to an address the compiler cannot tell apart would wait for it, one round
     // trip to memory per element.
     const bool neg = p.flags & FLAG_NEGATE, accum = p.flags & FLAG_ACCUMULATE;
+    // The bounds tests and the read of the old values are compiled into copies of their own,
+    // chosen once per tile: with the tests beside every element an interior tile of the
+    // remainder variant spent three times as long here.
+    auto emit = [&](auto check_tag, auto accum_tag) {
+    constexpr bool CHECK = decltype(check_tag)::value, ACCUM = decltype(accum_tag)::value;
     if (p.y_window) {
         // output pixel row -> (n, ho, wo) -> its place in the larger tensor.  A lane holds runs of
         // four consecutive rows: the first of a run is decoded, the others step from it
@@ -158,17 +165,17 @@ __device__ __forceinline__ void finish_tile(const KArgs& p, f32x16 (&acc)[T::MI]
                 for (int e = 0; e < 4; ++e)
 #pragma unroll
                     for (int j = 0; j < NI; ++j) {
-                        const bool ok = interior || (row0 + e < p.M && n0 + wn0 + j * 32 + li < p.N);
-                        old[e][j] = (accum && ok) ? dst[e][j * 32] : 0.f;
+                        const bool ok = !CHECK || (row0 + e < p.M && n0 + wn0 + j * 32 + li < p.N);
+                        old[e][j] = (ACCUM && ok) ? dst[e][j * 32] : 0.f;
                     }
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
 #pragma unroll
                     for (int j = 0; j < NI; ++j) {
-                        const bool ok = interior || (row0 + e < p.M && n0 + wn0 + j * 32 + li < p.N);
+                        const bool ok = !CHECK || (row0 + e < p.M && n0 + wn0 + j * 32 + li < p.N);
                         const float v = acc[i][j][rg * 4 + e];
                         const float sv = neg ? -v : v;
-                        if (ok) dst[e][j * 32] = accum ? sv + old[e][j] : sv;   // no add without the flag: -0 stays -0
+                        if (ok) dst[e][j * 32] = ACCUM ? sv + old[e][j] : sv;   // no add without the flag: -0 stays -0
                     }
             }
         return;
@@ -183,18 +190,26 @@ __device__ __forceinline__ void finish_tile(const KArgs& p, f32x16 (&acc)[T::MI]
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int dr = 8 * (r >> 2) + (r & 3);
-                const bool ok = interior || (m0 + wm0 + i * 32 + 4 * lh + dr < p.M && col < p.N);
-                old[r] = (accum && ok) ? c0[(long long)dr * p.ldc] : 0.f;
+                const bool ok = !CHECK || (m0 + wm0 + i * 32 + 4 * lh + dr < p.M && col < p.N);
+                old[r] = (ACCUM && ok) ? c0[(long long)dr * p.ldc] : 0.f;
             }
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int dr = 8 * (r >> 2) + (r & 3);
-                const bool ok = interior || (m0 + wm0 + i * 32 + 4 * lh + dr < p.M && col < p.N);
+                const bool ok = !CHECK || (m0 + wm0 + i * 32 + 4 * lh + dr < p.M && col < p.N);
                 const float v = acc[i][j][r];
                 const float sv = neg ? -v : v;
-                if (ok) c0[(long long)dr * p.ldc] = accum ? sv + old[r] : sv;   // no add without the flag: -0 stays -0
+                if (ok) c0[(long long)dr * p.ldc] = ACCUM ? sv + old[r] : sv;   // no add without the flag: -0 stays -0
             }
         }
+    };
+    if (interior) {
+        if (accum) emit(std::false_type{}, std::true_type{});
+        else emit(std::false_type{}, std::false_type{});
+    } else {
+        if (accum) emit(std::true_type{}, std::true_type{});
+        else emit(std::true_type{}, std::false_type{});
+    }
 }
 
 template <class T, int AMODE, int VEC, bool EDGE>
@@ -487,8 +502,14 @@ struct LdsDirect {
     static constexpr int BYTES = STAGES * STAGE * 2;
 };
 
-template <class T, int MODE, bool EDGE>
+// EDGEV: 0 = every loop divides (no remainder code); 1 = remainder code, chunks may be cut by the
+// end of a row (masked register path compiled in); 2 = remainder code for extents that are multiples
+// of the chunk: every chunk is wholly inside or wholly outside, so all steps are direct loads and the
+// loop stays one scheduling region (the masked path and its branch cost a 64 x 64 tile a third of its
+// speed even when it is never taken).
+template <class T, int MODE, int EDGEV>
 __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const KArgs p) {
+    constexpr bool EDGE = EDGEV != 0, CUT = EDGEV == 1;
     // address mode of the left operand, and whether the right one is stored transposed (N x K)
     constexpr int AMODE = MODE == A_ROW_BT ? A_ROW : MODE == A_COL_BT ? A_COL : MODE;
     constexpr bool B_KMAJ = MODE == A_ROW_BT || MODE == A_COL_BT;
@@ -532,12 +553,18 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
 
     // leading steps of this workgroup whose chunks are all whole (inside or outside)
     int n_direct = nk;
-    if constexpr (EDGE) {
+    if constexpr (CUT) {
         bool whole_tile = !(!B_KMAJ && (p.N & 7) && n0 + BN > p.N);
         if (AMODE == A_COL && (p.M & 7) && m0 + BM > p.M) whole_tile = false;
         if (!whole_tile) n_direct = 0;
         else if ((AMODE == A_ROW || B_KMAJ) && (p.K & 7)) n_direct = max(0, min(nk, p.k_full - kb));
     }
+
+    // The address of the block of zeros, taken once and kept in registers: derived where it is
+    // used, it costs a scalar load and a wait for every outstanding LDS read in the middle of
+    // the MFMA sequence of every step.
+    const u16* zero_chunk = g_zero_chunk;
+    asm volatile("" : "+s"(zero_chunk));
 
     const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) u16*)smem16 +
                           (unsigned)__builtin_amdgcn_readfirstlane(tid & ~63) * 16u;
@@ -612,10 +639,10 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
             const u16* src;
             if constexpr (AMODE == A_ROW) {
                 const bool in = a_in[q] && (!EDGE || k0 + a_k[q] < p.K);
-                src = in ? a_src[q] + k0 : g_zero_chunk;
+                src = in ? a_src[q] + k0 : zero_chunk;
             } else if constexpr (AMODE == A_COL) {
                 const bool in = a_in[q] && (!EDGE || k0 + a_k[q] < p.K);
-                src = in ? a_src[q] + (long long)k0 * p.lda : g_zero_chunk;
+                src = in ? a_src[q] + (long long)k0 * p.lda : zero_chunk;
             } else {
                 if (one_tap) {
                     // the whole step lies in tap (cs_kh, cs_kw), whose offset is the same for every
@@ -623,14 +650,14 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
                     const int hi = cv_hi0[q] + cs_kh, wi = cv_wi0[q] + cs_kw;
                     const bool in = a_in[q] && (unsigned)hi < (unsigned)p.H && (unsigned)wi < (unsigned)p.W;
                     const long long tap_off = ((long long)cs_kh * p.W + cs_kw) * p.Cin + cs_ci;
-                    src = in ? A + (cv_off[q] + tap_off) : g_zero_chunk;
+                    src = in ? A + (cv_off[q] + tap_off) : zero_chunk;
                 } else {
                     const int k = k0 + a_k[q];
                     const int tap = k / p.Cin, ci = k - tap * p.Cin;
                     const int kh = tap / p.KW, kw = tap - kh * p.KW;
                     const int hi = cv_hi0[q] + kh, wi = cv_wi0[q] + kw;
                     const bool in = a_in[q] && k < p.K && hi >= 0 && hi < p.H && wi >= 0 && wi < p.W;
-                    src = in ? A + ((long long)(cv_base[q] + hi) * p.W + wi) * p.Cin + ci : g_zero_chunk;
+                    src = in ? A + ((long long)(cv_base[q] + hi) * p.W + wi) * p.Cin + ci : zero_chunk;
                 }
             }
             load_to_lds16(src, as + (unsigned)(q * NT) * 16u);
@@ -638,7 +665,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
 #pragma unroll
         for (int q = 0; q < PB; ++q) {
             const bool in = b_in[q] && (!EDGE || k0 + b_k[q] < p.K);
-            const u16* src = in ? b_src[q] + (B_KMAJ ? (long long)k0 : (long long)k0 * p.ldb) : g_zero_chunk;
+            const u16* src = in ? b_src[q] + (B_KMAJ ? (long long)k0 : (long long)k0 * p.ldb) : zero_chunk;
             load_to_lds16(src, bs + (unsigned)(q * NT) * 16u);
         }
     };
@@ -688,7 +715,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
         }
     };
     auto issue = [&](int kt_local, int stage) {
-        if (!EDGE || kt_local < n_direct) issue_direct(kb + kt_local, stage);
+        if (!CUT || kt_local < n_direct) issue_direct(kb + kt_local, stage);
         else issue_masked(kb + kt_local, stage);
         if constexpr (AMODE == A_CONV) {
             cs_ci += BK;
@@ -731,10 +758,10 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
             const u16* src;
             if constexpr (AMODE == A_ROW) {
                 const bool in = a_in[q] && (!EDGE || k0 + a_k[q] < p.K);
-                src = in ? a_src[q] + k0 : g_zero_chunk;
+                src = in ? a_src[q] + k0 : zero_chunk;
             } else if constexpr (AMODE == A_COL) {
                 const bool in = a_in[q] && (!EDGE || k0 + a_k[q] < p.K);
-                src = in ? a_src[q] + (long long)k0 * p.lda : g_zero_chunk;
+                src = in ? a_src[q] + (long long)k0 * p.lda : zero_chunk;
             } else {
                 if (one_tap) {
                     // the whole step lies in tap (cs_kh, cs_kw), whose offset is the same for every
@@ -742,26 +769,26 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
                     const int hi = cv_hi0[q] + cs_kh, wi = cv_wi0[q] + cs_kw;
                     const bool in = a_in[q] && (unsigned)hi < (unsigned)p.H && (unsigned)wi < (unsigned)p.W;
                     const long long tap_off = ((long long)cs_kh * p.W + cs_kw) * p.Cin + cs_ci;
-                    src = in ? A + (cv_off[q] + tap_off) : g_zero_chunk;
+                    src = in ? A + (cv_off[q] + tap_off) : zero_chunk;
                 } else {
                     const int k = k0 + a_k[q];
                     const int tap = k / p.Cin, ci = k - tap * p.Cin;
                     const int kh = tap / p.KW, kw = tap - kh * p.KW;
                     const int hi = cv_hi0[q] + kh, wi = cv_wi0[q] + kw;
                     const bool in = a_in[q] && k < p.K && hi >= 0 && hi < p.H && wi >= 0 && wi < p.W;
-                    src = in ? A + ((long long)(cv_base[q] + hi) * p.W + wi) * p.Cin + ci : g_zero_chunk;
+                    src = in ? A + ((long long)(cv_base[q] + hi) * p.W + wi) * p.Cin + ci : zero_chunk;
                 }
             }
             load_to_lds16(src, as + (unsigned)(q * NT) * 16u);
         } else {
             const int q = x - PA;
             const bool in = b_in[q] && (!EDGE || k0 + b_k[q] < p.K);
-            const u16* src = in ? b_src[q] + (B_KMAJ ? (long long)k0 : (long long)k0 * p.ldb) : g_zero_chunk;
+            const u16* src = in ? b_src[q] + (B_KMAJ ? (long long)k0 : (long long)k0 * p.ldb) : zero_chunk;
             load_to_lds16(src, bs + (unsigned)(q * NT) * 16u);
         }
     };
     auto issue_part = [&](int kt_local, int stage, int x) {
-        if (!EDGE || kt_local < n_direct) load_one(kb + kt_local, stage, x);
+        if (!CUT || kt_local < n_direct) load_one(kb + kt_local, stage, x);
         else if (x == 0) issue_masked(kb + kt_local, stage);
         if constexpr (AMODE == A_CONV) {
             if (x == LPT - 1) {
@@ -883,17 +910,19 @@ hipError_t launch_mode(int variant, const KArgs& a, int batch, hipStream_t s) {
     } else if constexpr (T::SCHED >= 4) {
         if (variant == 2) return hipErrorInvalidValue;   // whole 16-byte chunks only
         bytes = LdsDirect<T>::BYTES;
-        fn = variant == 0 ? gemm_bf16_direct_kernel<T, AMODE, false> : gemm_bf16_direct_kernel<T, AMODE, true>;
+        fn = variant == 0 ? gemm_bf16_direct_kernel<T, AMODE, 0>
+             : variant == 3 ? gemm_bf16_direct_kernel<T, AMODE, 2> : gemm_bf16_direct_kernel<T, AMODE, 1>;
     } else {
         constexpr int A_SIZE = (AMODE != A_COL) ? T::BM * T::LDK : T::BK * T::LDA_T;
         bytes = 2 * (A_SIZE + T::BK * T::LDB) * 2;
         switch (variant) {
             case 0: fn = gemm_bf16_kernel<T, AMODE, 8, false>; break;
-            case 1: fn = gemm_bf16_kernel<T, AMODE, 8, true>; break;
+            case 1:
+            case 3: fn = gemm_bf16_kernel<T, AMODE, 8, true>; break;
             default: fn = gemm_bf16_kernel<T, AMODE, 1, true>; break;
         }
     }
-    static bool attr_done[3] = {false, false, false};
+    static bool attr_done[4] = {false, false, false, false};
     if (bytes > 48 * 1024 && !attr_done[variant]) {
         hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
         if (e != hipSuccess) return e;

@@ -21,6 +21,8 @@
 // arrival counter; the workgroup that arrives last adds the S partials in split order (so
 // the sum does not depend on who was last), applies the epilogue and resets the counter.
 #pragma once
+#include <type_traits>
+
 #include "tsg_internal.h"
 
 namespace tsg {
@@ -166,6 +168,11 @@ __device__ __forceinline__ void finish_tile(const KArgs& p, f32x16 (&acc)[T::MI]
     // behind a store to an address the compiler cannot tell apart would wait for it, one round
     // trip to memory per element.
     const bool neg = p.flags & FLAG_NEGATE, accum = p.flags & FLAG_ACCUMULATE;
+    // The bounds tests and the read of the old values are compiled into copies of their own,
+    // chosen once per tile: with the tests beside every element an interior tile of the
+    // remainder variant spent three times as long here.
+    auto emit = [&](auto check_tag, auto accum_tag) {
+    constexpr bool CHECK = decltype(check_tag)::value, ACCUM = decltype(accum_tag)::value;
     if (p.y_window) {
         // output pixel row -> (n, ho, wo) -> its place in the larger tensor.  A lane holds runs of
         // four consecutive rows: the first of a run is decoded, the others step from it
@@ -190,17 +197,17 @@ __device__ __forceinline__ void finish_tile(const KArgs& p, f32x16 (&acc)[T::MI]
                 for (int e = 0; e < 4; ++e)
 #pragma unroll
                     for (int j = 0; j < NI; ++j) {
-                        const bool ok = interior || (row0 + e < p.M && n0 + wn0 + j * 32 + li < p.N);
-                        old[e][j] = (accum && ok) ? dst[e][j * 32] : 0.f;
+                        const bool ok = !CHECK || (row0 + e < p.M && n0 + wn0 + j * 32 + li < p.N);
+                        old[e][j] = (ACCUM && ok) ? dst[e][j * 32] : 0.f;
                     }
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
 #pragma unroll
                     for (int j = 0; j < NI; ++j) {
-                        const bool ok = interior || (row0 + e < p.M && n0 + wn0 + j * 32 + li < p.N);
+                        const bool ok = !CHECK || (row0 + e < p.M && n0 + wn0 + j * 32 + li < p.N);
                         const float v = acc[i][j][rg * 4 + e];
                         const float sv = neg ? -v : v;
-                        if (ok) dst[e][j * 32] = accum ? sv + old[e][j] : sv;   // no add without the flag: -0 stays -0
+                        if (ok) dst[e][j * 32] = ACCUM ? sv + old[e][j] : sv;   // no add without the flag: -0 stays -0
                     }
             }
         return;
@@ -215,18 +222,26 @@ __device__ __forceinline__ void finish_tile(const KArgs& p, f32x16 (&acc)[T::MI]
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int dr = 8 * (r >> 2) + (r & 3);
-                const bool ok = interior || (m0 + wm0 + i * 32 + 4 * lh + dr < p.M && col < p.N);
-                old[r] = (accum && ok) ? c0[(long long)dr * p.ldc] : 0.f;
+                const bool ok = !CHECK || (m0 + wm0 + i * 32 + 4 * lh + dr < p.M && col < p.N);
+                old[r] = (ACCUM && ok) ? c0[(long long)dr * p.ldc] : 0.f;
             }
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int dr = 8 * (r >> 2) + (r & 3);
-                const bool ok = interior || (m0 + wm0 + i * 32 + 4 * lh + dr < p.M && col < p.N);
+                const bool ok = !CHECK || (m0 + wm0 + i * 32 + 4 * lh + dr < p.M && col < p.N);
                 const float v = acc[i][j][r];
                 const float sv = neg ? -v : v;
-                if (ok) c0[(long long)dr * p.ldc] = accum ? sv + old[r] : sv;   // no add without the flag: -0 stays -0
+                if (ok) c0[(long long)dr * p.ldc] = ACCUM ? sv + old[r] : sv;   // no add without the flag: -0 stays -0
             }
         }
+    };
+    if (interior) {
+        if (accum) emit(std::false_type{}, std::true_type{});
+        else emit(std::false_type{}, std::false_type{});
+    } else {
+        if (accum) emit(std::true_type{}, std::true_type{});
+        else emit(std::true_type{}, std::false_type{});
+    }
 }
 
 template <class T, int AMODE, int VEC, bool EDGE>
@@ -638,8 +653,14 @@ struct LdsDirect {
     static constexpr int BYTES = STAGES * STAGE * (int)sizeof(float);
 };
 
-template <class T, int MODE, bool EDGE>
+// EDGEV: 0 = every loop divides (no remainder code); 1 = remainder code, chunks may be cut by the
+// end of a row (masked register path compiled in); 2 = remainder code for extents that are multiples
+// of the chunk: every chunk is wholly inside or wholly outside, so all steps are direct loads and the
+// loop stays one scheduling region (the masked path and its branch cost a 64 x 64 tile a third of its
+// speed even when it is never taken).
+template <class T, int MODE, int EDGEV>
 __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const KArgs p) {
+    constexpr bool EDGE = EDGEV != 0, CUT = EDGEV == 1;
     // address mode of the left operand, and whether the right one is stored transposed (N x K)
     constexpr int AMODE = MODE == A_ROW_BT ? A_ROW : MODE == A_COL_BT ? A_COL : MODE;
     constexpr bool B_KMAJ = MODE == A_ROW_BT || MODE == A_COL_BT;
@@ -682,12 +703,18 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
 
     // Leading steps of this workgroup whose chunks are all whole (inside or outside).
     int n_direct = nk;
-    if constexpr (EDGE) {
+    if constexpr (CUT) {
         bool whole_tile = !(!B_KMAJ && (p.N & 3) && n0 + BN > p.N);            // rows of B are cut mid-chunk
         if (AMODE == A_COL && (p.M & 3) && m0 + BM > p.M) whole_tile = false;  // so are rows of A^T
         if (!whole_tile) n_direct = 0;
         else if ((AMODE == A_ROW || B_KMAJ) && (p.K & 3)) n_direct = max(0, min(nk, p.k_full - kb));
     }
+
+    // The address of the block of zeros, taken once and kept in registers: derived where it is
+    // used, it costs a scalar load and a wait for every outstanding LDS read in the middle of
+    // the MFMA sequence of every step.
+    const float* zero_chunk = g_zero_chunk;
+    asm volatile("" : "+s"(zero_chunk));
 
     // LDS byte address of this wave's 1 KiB slice of pass 0 of stage 0 (wave-uniform)
     const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) float*)smem +
@@ -764,10 +791,10 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
             const float* src;
             if constexpr (AMODE == A_ROW) {
                 const bool in = a_in[q] && (!EDGE || k0 + a_k[q] < p.K);
-                src = in ? a_src[q] + k0 : g_zero_chunk;
+                src = in ? a_src[q] + k0 : zero_chunk;
             } else if constexpr (AMODE == A_COL) {
                 const bool in = a_in[q] && (!EDGE || k0 + a_k[q] < p.K);
-                src = in ? a_src[q] + (long long)k0 * p.lda : g_zero_chunk;
+                src = in ? a_src[q] + (long long)k0 * p.lda : zero_chunk;
             } else {
                 if (one_tap) {
                     // the whole step lies in tap (cs_kh, cs_kw), whose offset is the same for every
@@ -775,14 +802,14 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
                     const int hi = cv_hi0[q] + cs_kh, wi = cv_wi0[q] + cs_kw;
                     const bool in = a_in[q] && (unsigned)hi < (unsigned)p.H && (unsigned)wi < (unsigned)p.W;
                     const long long tap_off = ((long long)cs_kh * p.W + cs_kw) * p.Cin + cs_ci;
-                    src = in ? A + (cv_off[q] + tap_off) : g_zero_chunk;
+                    src = in ? A + (cv_off[q] + tap_off) : zero_chunk;
                 } else {
                     const int k = k0 + a_k[q];
                     const int tap = k / p.Cin, ci = k - tap * p.Cin;
                     const int kh = tap / p.KW, kw = tap - kh * p.KW;
                     const int hi = cv_hi0[q] + kh, wi = cv_wi0[q] + kw;
                     const bool in = a_in[q] && k < p.K && hi >= 0 && hi < p.H && wi >= 0 && wi < p.W;
-                    src = in ? A + ((long long)(cv_base[q] + hi) * p.W + wi) * p.Cin + ci : g_zero_chunk;
+                    src = in ? A + ((long long)(cv_base[q] + hi) * p.W + wi) * p.Cin + ci : zero_chunk;
                 }
             }
             load_to_lds16(src, as + (unsigned)(q * NT) * 16u);
@@ -790,7 +817,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
 #pragma unroll
         for (int q = 0; q < PB; ++q) {
             const bool in = b_in[q] && (!EDGE || k0 + b_k[q] < p.K);
-            const float* src = in ? b_src[q] + (B_KMAJ ? (long long)k0 : (long long)k0 * p.ldb) : g_zero_chunk;
+            const float* src = in ? b_src[q] + (B_KMAJ ? (long long)k0 : (long long)k0 * p.ldb) : zero_chunk;
             load_to_lds16(src, bs + (unsigned)(q * NT) * 16u);
         }
     };
@@ -841,7 +868,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
         }
     };
     auto issue = [&](int kt_local, int stage) {
-        if (!EDGE || kt_local < n_direct) issue_direct(kb + kt_local, stage);
+        if (!CUT || kt_local < n_direct) issue_direct(kb + kt_local, stage);
         else issue_masked(kb + kt_local, stage);
         if constexpr (AMODE == A_CONV) {
             cs_ci += BK;
@@ -879,10 +906,10 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
             const float* src;
             if constexpr (AMODE == A_ROW) {
                 const bool in = a_in[q] && (!EDGE || k0 + a_k[q] < p.K);
-                src = in ? a_src[q] + k0 : g_zero_chunk;
+                src = in ? a_src[q] + k0 : zero_chunk;
             } else if constexpr (AMODE == A_COL) {
                 const bool in = a_in[q] && (!EDGE || k0 + a_k[q] < p.K);
-                src = in ? a_src[q] + (long long)k0 * p.lda : g_zero_chunk;
+                src = in ? a_src[q] + (long long)k0 * p.lda : zero_chunk;
             } else {
                 if (one_tap) {
                     // the whole step lies in tap (cs_kh, cs_kw), whose offset is the same for every
@@ -890,28 +917,28 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
                     const int hi = cv_hi0[q] + cs_kh, wi = cv_wi0[q] + cs_kw;
                     const bool in = a_in[q] && (unsigned)hi < (unsigned)p.H && (unsigned)wi < (unsigned)p.W;
                     const long long tap_off = ((long long)cs_kh * p.W + cs_kw) * p.Cin + cs_ci;
-                    src = in ? A + (cv_off[q] + tap_off) : g_zero_chunk;
+                    src = in ? A + (cv_off[q] + tap_off) : zero_chunk;
                 } else {
                     const int k = k0 + a_k[q];
                     const int tap = k / p.Cin, ci = k - tap * p.Cin;
                     const int kh = tap / p.KW, kw = tap - kh * p.KW;
                     const int hi = cv_hi0[q] + kh, wi = cv_wi0[q] + kw;
                     const bool in = a_in[q] && k < p.K && hi >= 0 && hi < p.H && wi >= 0 && wi < p.W;
-                    src = in ? A + ((long long)(cv_base[q] + hi) * p.W + wi) * p.Cin + ci : g_zero_chunk;
+                    src = in ? A + ((long long)(cv_base[q] + hi) * p.W + wi) * p.Cin + ci : zero_chunk;
                 }
             }
             load_to_lds16(src, as + (unsigned)(q * NT) * 16u);
         } else {
             const int q = x - PA;
             const bool in = b_in[q] && (!EDGE || k0 + b_k[q] < p.K);
-            const float* src = in ? b_src[q] + (B_KMAJ ? (long long)k0 : (long long)k0 * p.ldb) : g_zero_chunk;
+            const float* src = in ? b_src[q] + (B_KMAJ ? (long long)k0 : (long long)k0 * p.ldb) : zero_chunk;
             load_to_lds16(src, bs + (unsigned)(q * NT) * 16u);
         }
     };
     // the x-th part of bringing in tile kt_local: one direct load, or (steps with cut chunks)
     // the whole masked tile at x = 0; the convolution's tap state moves on after the last part
     auto issue_part = [&](int kt_local, int stage, int x) {
-        if (!EDGE || kt_local < n_direct) load_one(kb + kt_local, stage, x);
+        if (!CUT || kt_local < n_direct) load_one(kb + kt_local, stage, x);
         else if (x == 0) issue_masked(kb + kt_local, stage);
         if constexpr (AMODE == A_CONV) {
             if (x == LPT - 1) {
@@ -1026,16 +1053,18 @@ hipError_t launch_mode(int variant, const KArgs& a, int batch, hipStream_t s) {
         // the direct-to-LDS forms move whole 16-byte chunks only
         if (variant == 2) return hipErrorInvalidValue;
         bytes = LdsDirect<T, AMODE>::BYTES;
-        fn = variant == 0 ? gemm_f32_direct_kernel<T, AMODE, false> : gemm_f32_direct_kernel<T, AMODE, true>;
+        fn = variant == 0 ? gemm_f32_direct_kernel<T, AMODE, 0>
+             : variant == 3 ? gemm_f32_direct_kernel<T, AMODE, 2> : gemm_f32_direct_kernel<T, AMODE, 1>;
     } else {
         bytes = Lds<T, AMODE>::BYTES;
         switch (variant) {
             case 0: fn = gemm_f32_kernel<T, AMODE, 4, false>; break;
-            case 1: fn = gemm_f32_kernel<T, AMODE, 4, true>; break;
+            case 1:
+            case 3: fn = gemm_f32_kernel<T, AMODE, 4, true>; break;
             default: fn = gemm_f32_kernel<T, AMODE, 1, true>; break;
         }
     }
-    static bool attr_done[3] = {false, false, false};
+    static bool attr_done[4] = {false, false, false, false};
     if (bytes > 48 * 1024 && !attr_done[variant]) {
         hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
         if (e != hipSuccess) return e;
