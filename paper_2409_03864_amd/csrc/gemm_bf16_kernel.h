@@ -510,6 +510,10 @@ struct LdsDirect {
 template <class T, int MODE, int EDGEV>
 __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const KArgs p) {
     constexpr bool EDGE = EDGEV != 0, CUT = EDGEV == 1;
+    // EDGEV 2: rows and columns past M or N are read from the last valid row or chunk instead of
+    // being tested at every step: their products only reach elements of C that are never stored
+    // (k past K still reads the block of zeros: both factors must vanish there)
+    constexpr bool CLAMP = EDGEV == 2;
     // address mode of the left operand, and whether the right one is stored transposed (N x K)
     constexpr int AMODE = MODE == A_ROW_BT ? A_ROW : MODE == A_COL_BT ? A_COL : MODE;
     constexpr bool B_KMAJ = MODE == A_ROW_BT || MODE == A_COL_BT;
@@ -552,7 +556,10 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
     const int nk = (int)((long long)nk_all * (split + 1) / nsplit) - kb;
 
     // leading steps of this workgroup whose chunks are all whole (inside or outside)
-    int n_direct = nk;
+    // EDGEV 2 peels the k loop like Fig. 8: the ring runs the steps that lie wholly below K
+    // without any test, and a last partial step is staged through registers after it
+    const int nkp = CLAMP ? min(nk, max(0, p.k_full - kb)) : nk;   // steps that go through the ring
+    int n_direct = nkp;
     if constexpr (CUT) {
         bool whole_tile = !(!B_KMAJ && (p.N & 7) && n0 + BN > p.N);
         if (AMODE == A_COL && (p.M & 7) && m0 + BM > p.M) whole_tile = false;
@@ -583,19 +590,19 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
         const int row = a_r + q * A_RPP;
         if constexpr (AMODE == A_ROW) {
             a_k[q] = (a_cp ^ swz_k(row)) * 8;
-            a_in[q] = !EDGE || m0 + row < p.M;
-            a_src[q] = A + (long long)(m0 + row) * p.lda + a_k[q];
+            a_in[q] = !CUT || m0 + row < p.M;
+            a_src[q] = A + (long long)(CLAMP ? min(m0 + row, p.M - 1) : m0 + row) * p.lda + a_k[q];
         } else if constexpr (AMODE == A_COL) {
             a_k[q] = row;   // the stored row is the k index
             const int mc = (a_cp ^ swz_j(row)) * 8;
-            a_in[q] = !EDGE || m0 + mc < p.M;
-            a_src[q] = A + (long long)row * p.lda + m0 + mc;
+            a_in[q] = !CUT || m0 + mc < p.M;
+            a_src[q] = A + (long long)row * p.lda + (CLAMP ? min(m0 + mc, p.M - 8) : m0 + mc);
         } else {
             a_k[q] = (a_cp ^ swz_k(row)) * 8;
             const int m = m0 + row;
-            a_in[q] = !EDGE || m < p.M;
+            a_in[q] = !CUT || m < p.M;
             a_src[q] = A;
-            const int mm = a_in[q] ? m : 0;
+            const int mm = CLAMP ? min(m, p.M - 1) : a_in[q] ? m : 0;
             const int wo = mm % p.Wo, t = mm / p.Wo;
             const int ho = t % p.Ho, n = t / p.Ho;
             cv_base[q] = n * p.H;
@@ -620,13 +627,13 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
         const int row = b_r + q * B_RPP;
         if constexpr (B_KMAJ) {
             b_k[q] = (b_cp ^ swz_k(row)) * 8;
-            b_in[q] = !EDGE || n0 + row < p.N;
-            b_src[q] = B + (long long)(n0 + row) * p.ldb + b_k[q];
+            b_in[q] = !CUT || n0 + row < p.N;
+            b_src[q] = B + (long long)(CLAMP ? min(n0 + row, p.N - 1) : n0 + row) * p.ldb + b_k[q];
         } else {
             const int nc = (b_cp ^ swz_j(row)) * 8;
             b_k[q] = row;
-            b_in[q] = !EDGE || n0 + nc < p.N;
-            b_src[q] = B + (long long)row * p.ldb + n0 + nc;
+            b_in[q] = !CUT || n0 + nc < p.N;
+            b_src[q] = B + (long long)row * p.ldb + (CLAMP ? min(n0 + nc, p.N - 8) : n0 + nc);
         }
     }
 
@@ -638,10 +645,10 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
         for (int q = 0; q < PA; ++q) {
             const u16* src;
             if constexpr (AMODE == A_ROW) {
-                const bool in = a_in[q] && (!EDGE || k0 + a_k[q] < p.K);
+                const bool in = a_in[q] && (!CUT || k0 + a_k[q] < p.K);
                 src = in ? a_src[q] + k0 : zero_chunk;
             } else if constexpr (AMODE == A_COL) {
-                const bool in = a_in[q] && (!EDGE || k0 + a_k[q] < p.K);
+                const bool in = a_in[q] && (!CUT || k0 + a_k[q] < p.K);
                 src = in ? a_src[q] + (long long)k0 * p.lda : zero_chunk;
             } else {
                 if (one_tap) {
@@ -664,7 +671,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
         }
 #pragma unroll
         for (int q = 0; q < PB; ++q) {
-            const bool in = b_in[q] && (!EDGE || k0 + b_k[q] < p.K);
+            const bool in = b_in[q] && (!CUT || k0 + b_k[q] < p.K);
             const u16* src = in ? b_src[q] + (B_KMAJ ? (long long)k0 : (long long)k0 * p.ldb) : zero_chunk;
             load_to_lds16(src, bs + (unsigned)(q * NT) * 16u);
         }
@@ -749,7 +756,8 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
     const int tr_x = swz_j(tr_row);   // (row + 4) % 4 == row % 4: both reads share the mask
 
     // ---- one direct load: the x-th of the LPT loads that bring a tile in
-    auto load_one = [&](int kt, int stage, int x) {
+    // (`ktest`: also test the chunk's k against K, which the ring of the peeled variant never needs)
+    auto load_one = [&](int kt, int stage, int x, bool ktest) {
         const int k0 = kt * BK;
         const unsigned as = lds0 + (unsigned)(stage * L::STAGE) * 2u;
         const unsigned bs = as + (unsigned)L::A_ELEMS * 2u;
@@ -757,10 +765,10 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
             const int q = x;
             const u16* src;
             if constexpr (AMODE == A_ROW) {
-                const bool in = a_in[q] && (!EDGE || k0 + a_k[q] < p.K);
+                const bool in = a_in[q] && (!(CUT || ktest) || k0 + a_k[q] < p.K);
                 src = in ? a_src[q] + k0 : zero_chunk;
             } else if constexpr (AMODE == A_COL) {
-                const bool in = a_in[q] && (!EDGE || k0 + a_k[q] < p.K);
+                const bool in = a_in[q] && (!(CUT || ktest) || k0 + a_k[q] < p.K);
                 src = in ? a_src[q] + (long long)k0 * p.lda : zero_chunk;
             } else {
                 if (one_tap) {
@@ -782,13 +790,13 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
             load_to_lds16(src, as + (unsigned)(q * NT) * 16u);
         } else {
             const int q = x - PA;
-            const bool in = b_in[q] && (!EDGE || k0 + b_k[q] < p.K);
+            const bool in = b_in[q] && (!(CUT || ktest) || k0 + b_k[q] < p.K);
             const u16* src = in ? b_src[q] + (B_KMAJ ? (long long)k0 : (long long)k0 * p.ldb) : zero_chunk;
             load_to_lds16(src, bs + (unsigned)(q * NT) * 16u);
         }
     };
     auto issue_part = [&](int kt_local, int stage, int x) {
-        if (!CUT || kt_local < n_direct) load_one(kb + kt_local, stage, x);
+        if (!CUT || kt_local < n_direct) load_one(kb + kt_local, stage, x, false);
         else if (x == 0) issue_masked(kb + kt_local, stage);
         if constexpr (AMODE == A_CONV) {
             if (x == LPT - 1) {
@@ -837,14 +845,14 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
 
     // ---- ring, as in the fp32 kernels: the one barrier of a step sits before its last k group
     for (int t = 0; t < D; ++t)
-        if (t < nk) issue(t, t);
+        if (t < nkp) issue(t, t);
     if (D <= n_direct) wait_loads_outstanding<(D - 1) * LPT>();
     else wait_loads_outstanding<0>();
     __syncthreads();
 #pragma unroll
     for (int x = 0; x < NFRAG; ++x) frag_read(0, 0, x);
     int cur = 0;
-    for (int kt = 0; kt < nk; ++kt) {
+    for (int kt = 0; kt < nkp; ++kt) {
         const int nxt = cur + 1 == STAGES ? 0 : cur + 1;
         const int fill = cur == 0 ? STAGES - 1 : cur - 1;
 #pragma unroll
@@ -888,7 +896,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
                     for (int u = 0; u < LPER; ++u) {
                         const int e = (m - L0) * LPER + u;
                         if (e >= LPT) continue;
-                        if (kt + D < nk) issue_part(kt + D, fill, e);
+                        if (kt + D < nkp) issue_part(kt + D, fill, e);
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);
@@ -897,6 +905,33 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
         cur = nxt;
     }
 
+    if constexpr (CLAMP) {
+        if (nkp < nk) {
+            // the partial last step: into stage 0 with the chunks past K read from the block of
+            // zeros (every chunk is whole in this variant), multiplied group by group
+            __syncthreads();   // everybody has left the ring
+#pragma unroll
+            for (int x = 0; x < LPT; ++x) load_one(kb + nkp, 0, x, true);
+            wait_loads_outstanding<0>();
+            __syncthreads();
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+#pragma unroll
+                for (int x = 0; x < NFRAG; ++x) frag_read(0, g, x);
+#pragma unroll
+                for (int m = 0; m < NM; ++m) {
+                const int i = m / NI, j = m % NI;
+                bf16x8 a;
+                if constexpr (A_KMAJ) a = af[g & 1][i];
+                else a = __builtin_shufflevector(ah[g & 1][i][0], ah[g & 1][i][1], 0, 1, 2, 3, 4, 5, 6, 7);
+                bf16x8 b;
+                if constexpr (B_KMAJ) b = bfull[g & 1][j];
+                else b = __builtin_shufflevector(bh[g & 1][j][0], bh[g & 1][j][1], 0, 1, 2, 3, 4, 5, 6, 7);
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i][j], 0, 0, 0);
+                }
+            }
+        }
+    }
     finish_tile<T>(p, acc, C, slot, split, nsplit, m0, n0, wm0, wn0, interior);
 }
 

@@ -661,6 +661,10 @@ struct LdsDirect {
 template <class T, int MODE, int EDGEV>
 __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const KArgs p) {
     constexpr bool EDGE = EDGEV != 0, CUT = EDGEV == 1;
+    // EDGEV 2: rows and columns past M or N are read from the last valid row or chunk instead of
+    // being tested at every step: their products only reach elements of C that are never stored
+    // (k past K still reads the block of zeros: both factors must vanish there)
+    constexpr bool CLAMP = EDGEV == 2;
     // address mode of the left operand, and whether the right one is stored transposed (N x K)
     constexpr int AMODE = MODE == A_ROW_BT ? A_ROW : MODE == A_COL_BT ? A_COL : MODE;
     constexpr bool B_KMAJ = MODE == A_ROW_BT || MODE == A_COL_BT;
@@ -702,7 +706,10 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
     const int nk = (int)((long long)nk_all * (split + 1) / nsplit) - kb;
 
     // Leading steps of this workgroup whose chunks are all whole (inside or outside).
-    int n_direct = nk;
+    // EDGEV 2 peels the k loop like Fig. 8: the ring runs the steps that lie wholly below K
+    // without any test, and a last partial step is staged through registers after it
+    const int nkp = CLAMP ? min(nk, max(0, p.k_full - kb)) : nk;   // steps that go through the ring
+    int n_direct = nkp;
     if constexpr (CUT) {
         bool whole_tile = !(!B_KMAJ && (p.N & 3) && n0 + BN > p.N);            // rows of B are cut mid-chunk
         if (AMODE == A_COL && (p.M & 3) && m0 + BM > p.M) whole_tile = false;  // so are rows of A^T
@@ -734,18 +741,18 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
         const int row = a_r + q * A_RPP;
         if constexpr (AMODE == A_ROW) {
             a_k[q] = (a_cp ^ swz(row)) * 4;
-            a_in[q] = !EDGE || m0 + row < p.M;
-            a_src[q] = A + (long long)(m0 + row) * p.lda + a_k[q];
+            a_in[q] = !CUT || m0 + row < p.M;
+            a_src[q] = A + (long long)(CLAMP ? min(m0 + row, p.M - 1) : m0 + row) * p.lda + a_k[q];
         } else if constexpr (AMODE == A_COL) {
             a_k[q] = row;   // the stored row is the k index
-            a_in[q] = !EDGE || m0 + a_cp * 4 < p.M;
-            a_src[q] = A + (long long)row * p.lda + m0 + a_cp * 4;
+            a_in[q] = !CUT || m0 + a_cp * 4 < p.M;
+            a_src[q] = A + (long long)row * p.lda + (CLAMP ? min(m0 + a_cp * 4, p.M - 4) : m0 + a_cp * 4);
         } else {
             a_k[q] = (a_cp ^ swz(row)) * 4;
             const int m = m0 + row;
-            a_in[q] = !EDGE || m < p.M;
+            a_in[q] = !CUT || m < p.M;
             a_src[q] = A;
-            const int mm = a_in[q] ? m : 0;
+            const int mm = CLAMP ? min(m, p.M - 1) : a_in[q] ? m : 0;
             const int wo = mm % p.Wo, t = mm / p.Wo;
             const int ho = t % p.Ho, n = t / p.Ho;
             cv_base[q] = n * p.H;
@@ -772,12 +779,12 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
         const int row = b_r + q * B_RPP;
         if constexpr (B_KMAJ) {
             b_k[q] = (b_cp ^ swz(row)) * 4;
-            b_in[q] = !EDGE || n0 + row < p.N;
-            b_src[q] = B + (long long)(n0 + row) * p.ldb + b_k[q];
+            b_in[q] = !CUT || n0 + row < p.N;
+            b_src[q] = B + (long long)(CLAMP ? min(n0 + row, p.N - 1) : n0 + row) * p.ldb + b_k[q];
         } else {
             b_k[q] = row;
-            b_in[q] = !EDGE || n0 + b_cp * 4 < p.N;
-            b_src[q] = B + (long long)row * p.ldb + n0 + b_cp * 4;
+            b_in[q] = !CUT || n0 + b_cp * 4 < p.N;
+            b_src[q] = B + (long long)row * p.ldb + (CLAMP ? min(n0 + b_cp * 4, p.N - 4) : n0 + b_cp * 4);
         }
     }
 
@@ -790,10 +797,10 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
         for (int q = 0; q < PA; ++q) {
             const float* src;
             if constexpr (AMODE == A_ROW) {
-                const bool in = a_in[q] && (!EDGE || k0 + a_k[q] < p.K);
+                const bool in = a_in[q] && (!CUT || k0 + a_k[q] < p.K);
                 src = in ? a_src[q] + k0 : zero_chunk;
             } else if constexpr (AMODE == A_COL) {
-                const bool in = a_in[q] && (!EDGE || k0 + a_k[q] < p.K);
+                const bool in = a_in[q] && (!CUT || k0 + a_k[q] < p.K);
                 src = in ? a_src[q] + (long long)k0 * p.lda : zero_chunk;
             } else {
                 if (one_tap) {
@@ -816,7 +823,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
         }
 #pragma unroll
         for (int q = 0; q < PB; ++q) {
-            const bool in = b_in[q] && (!EDGE || k0 + b_k[q] < p.K);
+            const bool in = b_in[q] && (!CUT || k0 + b_k[q] < p.K);
             const float* src = in ? b_src[q] + (B_KMAJ ? (long long)k0 : (long long)k0 * p.ldb) : zero_chunk;
             load_to_lds16(src, bs + (unsigned)(q * NT) * 16u);
         }
@@ -897,7 +904,8 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
     const int a_x = lh ^ swz(li);   // wm0 + 32 i is a multiple of 32, so the swizzle depends on li alone
 
     // ---- one direct load: the x-th of the LPT loads that bring a tile in
-    auto load_one = [&](int kt, int stage, int x) {
+    // (`ktest`: also test the chunk's k against K, which the ring of the peeled variant never needs)
+    auto load_one = [&](int kt, int stage, int x, bool ktest) {
         const int k0 = kt * BK;
         const unsigned as = lds0 + (unsigned)(stage * L::STAGE) * 4u;
         const unsigned bs = as + (unsigned)L::A_FLOATS * 4u;
@@ -905,10 +913,10 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
             const int q = x;
             const float* src;
             if constexpr (AMODE == A_ROW) {
-                const bool in = a_in[q] && (!EDGE || k0 + a_k[q] < p.K);
+                const bool in = a_in[q] && (!(CUT || ktest) || k0 + a_k[q] < p.K);
                 src = in ? a_src[q] + k0 : zero_chunk;
             } else if constexpr (AMODE == A_COL) {
-                const bool in = a_in[q] && (!EDGE || k0 + a_k[q] < p.K);
+                const bool in = a_in[q] && (!(CUT || ktest) || k0 + a_k[q] < p.K);
                 src = in ? a_src[q] + (long long)k0 * p.lda : zero_chunk;
             } else {
                 if (one_tap) {
@@ -930,7 +938,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
             load_to_lds16(src, as + (unsigned)(q * NT) * 16u);
         } else {
             const int q = x - PA;
-            const bool in = b_in[q] && (!EDGE || k0 + b_k[q] < p.K);
+            const bool in = b_in[q] && (!(CUT || ktest) || k0 + b_k[q] < p.K);
             const float* src = in ? b_src[q] + (B_KMAJ ? (long long)k0 : (long long)k0 * p.ldb) : zero_chunk;
             load_to_lds16(src, bs + (unsigned)(q * NT) * 16u);
         }
@@ -938,7 +946,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
     // the x-th part of bringing in tile kt_local: one direct load, or (steps with cut chunks)
     // the whole masked tile at x = 0; the convolution's tap state moves on after the last part
     auto issue_part = [&](int kt_local, int stage, int x) {
-        if (!CUT || kt_local < n_direct) load_one(kb + kt_local, stage, x);
+        if (!CUT || kt_local < n_direct) load_one(kb + kt_local, stage, x, false);
         else if (x == 0) issue_masked(kb + kt_local, stage);
         if constexpr (AMODE == A_CONV) {
             if (x == LPT - 1) {
@@ -984,14 +992,14 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
     // tile kt+D go into the stage step kt-1 used and the first fragments of step kt+1 are
     // fetched.  No wave ever starts a step, or leaves a barrier, with its MFMA operands missing.
     for (int t = 0; t < D; ++t)
-        if (t < nk) issue(t, t);
+        if (t < nkp) issue(t, t);
     if (D <= n_direct) wait_loads_outstanding<(D - 1) * LPT>();
     else wait_loads_outstanding<0>();
     __syncthreads();
 #pragma unroll
     for (int x = 0; x < NFRAG; ++x) frag_read(0, 0, x);
     int cur = 0;
-    for (int kt = 0; kt < nk; ++kt) {
+    for (int kt = 0; kt < nkp; ++kt) {
         const int nxt = cur + 1 == STAGES ? 0 : cur + 1;
         const int fill = cur == 0 ? STAGES - 1 : cur - 1;
 #pragma unroll
@@ -1030,7 +1038,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
                     for (int u = 0; u < LPER; ++u) {
                         const int e = (m - L0) * LPER + u;
                         if (e >= LPT) continue;
-                        if (kt + D < nk) issue_part(kt + D, fill, e);
+                        if (kt + D < nkp) issue_part(kt + D, fill, e);
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);
@@ -1039,6 +1047,27 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
         cur = nxt;
     }
 
+    if constexpr (CLAMP) {
+        if (nkp < nk) {
+            // the partial last step: into stage 0 with the chunks past K read from the block of
+            // zeros (every chunk is whole in this variant), multiplied group by group
+            __syncthreads();   // everybody has left the ring
+#pragma unroll
+            for (int x = 0; x < LPT; ++x) load_one(kb + nkp, 0, x, true);
+            wait_loads_outstanding<0>();
+            __syncthreads();
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+#pragma unroll
+                for (int x = 0; x < NFRAG; ++x) frag_read(0, g, x);
+#pragma unroll
+                for (int m = 0; m < NM; ++m) {
+                const int t = m / (MI * NI), i = (m / NI) % MI, j = m % NI;
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[g & 1][i][t], bf[g & 1][j][t], acc[i][j], 0, 0, 0);
+                }
+            }
+        }
+    }
     finish_tile<T>(p, acc, C, slot, split, nsplit, m0, n0, wm0, wn0, interior);
 }
 
