@@ -268,12 +268,11 @@ tsg_status make_plan(const Problem& p, const tsg_tile_config& cfg, int alternati
     const bool edge = m_rest || n_rest || k_rest;
     out->entry = e;
     out->cfg = cfg;
-    // remainder variant 3: no chunk of an operand is cut by the end of a row, i.e. the extent
-    // along which each operand is contiguous is a multiple of the access width
+    // remainder variant 3: no chunk is cut by the end of a row along M or N (operands that are
+    // contiguous along those extents have them as multiples of the access width); a chunk cut by
+    // K only occurs in the last k step, which that variant peels off
     const int64_t v = vec_max(p.dtype);
-    const bool a_k_contig = p.op != TSG_OP_GEMM_TRANSA;   // A rows run along k (also the gathered operand: Cin % v == 0)
-    const bool cut = (!p.trans_b && p.N % v) || (p.op == TSG_OP_GEMM_TRANSA && p.M % v) ||
-                     (((a_k_contig && p.op != TSG_OP_CONV2D_NHWC) || p.trans_b) && p.K % v);
+    const bool cut = (!p.trans_b && p.N % v) || (p.op == TSG_OP_GEMM_TRANSA && p.M % v);
     out->variant = cfg.vec == 1 ? 2 : (edge ? (cut ? 1 : 3) : 0);
 
     KArgs& a = out->args;

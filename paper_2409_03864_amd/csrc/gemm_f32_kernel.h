@@ -654,10 +654,11 @@ struct LdsDirect {
 };
 
 // EDGEV: 0 = every loop divides (no remainder code); 1 = remainder code, chunks may be cut by the
-// end of a row (masked register path compiled in); 2 = remainder code for extents that are multiples
-// of the chunk: every chunk is wholly inside or wholly outside, so all steps are direct loads and the
-// loop stays one scheduling region (the masked path and its branch cost a 64 x 64 tile a third of its
-// speed even when it is never taken).
+// end of a row in every step (masked register path compiled into the ring); 2 = remainder code for
+// operands whose chunks along M and N are never cut: rows and columns past the end are clamped, the
+// ring runs the full k steps without a test as one scheduling region, and the partial last k step
+// is peeled off (the masked path and its branch inside the ring cost a 64 x 64 tile a third of its
+// speed even when never taken).
 template <class T, int MODE, int EDGEV>
 __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const KArgs p) {
     constexpr bool EDGE = EDGEV != 0, CUT = EDGEV == 1;
@@ -1049,12 +1050,17 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
 
     if constexpr (CLAMP) {
         if (nkp < nk) {
-            // the partial last step: into stage 0 with the chunks past K read from the block of
-            // zeros (every chunk is whole in this variant), multiplied group by group
+            // the partial last step into stage 0, multiplied group by group: chunks past K come
+            // from the block of zeros, or, when K cuts a chunk of a k-contiguous operand, the
+            // whole tile goes through registers with element masks
             __syncthreads();   // everybody has left the ring
+            if (p.K % 4) {
+                issue_masked(kb + nkp, 0);
+            } else {
 #pragma unroll
-            for (int x = 0; x < LPT; ++x) load_one(kb + nkp, 0, x, true);
-            wait_loads_outstanding<0>();
+                for (int x = 0; x < LPT; ++x) load_one(kb + nkp, 0, x, true);
+                wait_loads_outstanding<0>();
+            }
             __syncthreads();
 #pragma unroll
             for (int g = 0; g < G; ++g) {
