@@ -508,7 +508,10 @@ struct LdsDirect {
 // ring runs the full k steps without a test as one scheduling region, and the partial last k step
 // is peeled off (the masked path and its branch inside the ring cost a 64 x 64 tile a third of its
 // speed even when never taken).
-template <class T, int MODE, int EDGEV>
+// ONE_TAP (convolution only): Cin is a multiple of BK, so a k step lies inside one filter tap.
+// A template parameter rather than a test at run time: the general form divides per chunk, and
+// a two-sided branch between the MFMAs of a step splits the step's scheduling region.
+template <class T, int MODE, int EDGEV, bool ONE_TAP = false>
 __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const KArgs p) {
     constexpr bool EDGE = EDGEV != 0, CUT = EDGEV == 1;
     // EDGEV 2: rows and columns past M or N are read from the last valid row or chunk instead of
@@ -613,12 +616,14 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
         }
     }
     int cs_kh = 0, cs_kw = 0, cs_ci = 0;
-    const bool one_tap = AMODE == A_CONV && p.Cin % BK == 0;
+    long long cs_off = 0;   // element offset of (cs_kh, cs_kw, cs_ci) from tap (0, 0), channel 0 of a pixel
+    constexpr bool one_tap = AMODE == A_CONV && ONE_TAP;
     if constexpr (AMODE == A_CONV) {
         const int k = kb * BK, tap = k / p.Cin;
         cs_ci = k - tap * p.Cin;
         cs_kh = tap / p.KW;
         cs_kw = tap - cs_kh * p.KW;
+        cs_off = ((long long)cs_kh * p.W + cs_kw) * p.Cin + cs_ci;
     }
     const u16* b_src[PB];
     int b_k[PB];          // k offset of the chunk inside a step
@@ -652,13 +657,13 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
                 const bool in = a_in[q] && (!CUT || k0 + a_k[q] < p.K);
                 src = in ? a_src[q] + (long long)k0 * p.lda : zero_chunk;
             } else {
-                if (one_tap) {
+                if constexpr (one_tap) {
                     // the whole step lies in tap (cs_kh, cs_kw), whose offset is the same for every
-                    // thread: scalar arithmetic, then one add and two compares per chunk
+                    // thread and moves on with the tap state: one add and two compares per chunk
                     const int hi = cv_hi0[q] + cs_kh, wi = cv_wi0[q] + cs_kw;
                     const bool in = a_in[q] && (unsigned)hi < (unsigned)p.H && (unsigned)wi < (unsigned)p.W;
-                    const long long tap_off = ((long long)cs_kh * p.W + cs_kw) * p.Cin + cs_ci;
-                    src = in ? A + (cv_off[q] + tap_off) : zero_chunk;
+                    const u16* inside = A + (cv_off[q] + cs_off);
+                    src = in ? inside : zero_chunk;
                 } else {
                     const int k = k0 + a_k[q];
                     const int tap = k / p.Cin, ci = k - tap * p.Cin;
@@ -727,9 +732,10 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
         else issue_masked(kb + kt_local, stage);
         if constexpr (AMODE == A_CONV) {
             cs_ci += BK;
+            cs_off += BK;   // along ci and from one kw to the next the pixels' channels are consecutive
             while (cs_ci >= p.Cin) {
                 cs_ci -= p.Cin;
-                if (++cs_kw == p.KW) { cs_kw = 0; ++cs_kh; }
+                if (++cs_kw == p.KW) { cs_kw = 0; ++cs_kh; cs_off += (long long)(p.W - p.KW) * p.Cin; }
             }
         }
     };
@@ -772,13 +778,13 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
                 const bool in = a_in[q] && (!(CUT || ktest) || k0 + a_k[q] < p.K);
                 src = in ? a_src[q] + (long long)k0 * p.lda : zero_chunk;
             } else {
-                if (one_tap) {
+                if constexpr (one_tap) {
                     // the whole step lies in tap (cs_kh, cs_kw), whose offset is the same for every
-                    // thread: scalar arithmetic, then one add and two compares per chunk
+                    // thread and moves on with the tap state: one add and two compares per chunk
                     const int hi = cv_hi0[q] + cs_kh, wi = cv_wi0[q] + cs_kw;
                     const bool in = a_in[q] && (unsigned)hi < (unsigned)p.H && (unsigned)wi < (unsigned)p.W;
-                    const long long tap_off = ((long long)cs_kh * p.W + cs_kw) * p.Cin + cs_ci;
-                    src = in ? A + (cv_off[q] + tap_off) : zero_chunk;
+                    const u16* inside = A + (cv_off[q] + cs_off);
+                    src = in ? inside : zero_chunk;
                 } else {
                     const int k = k0 + a_k[q];
                     const int tap = k / p.Cin, ci = k - tap * p.Cin;
@@ -802,9 +808,10 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_bf16_direct_kernel(const 
         if constexpr (AMODE == A_CONV) {
             if (x == LPT - 1) {
                 cs_ci += BK;
+                cs_off += BK;   // along ci and from one kw to the next the pixels' channels are consecutive
                 while (cs_ci >= p.Cin) {
                     cs_ci -= p.Cin;
-                    if (++cs_kw == p.KW) { cs_kw = 0; ++cs_kh; }
+                    if (++cs_kw == p.KW) { cs_kw = 0; ++cs_kh; cs_off += (long long)(p.W - p.KW) * p.Cin; }
                 }
             }
         }
@@ -945,7 +952,7 @@ template <class T, int AMODE>
 hipError_t launch_mode(int variant, const KArgs& a, int batch, hipStream_t s) {
     const dim3 grid(a.split_first + (a.tiles_m * a.tiles_n - a.split_first) * a.split_k, batch, 1), block(T::NT, 1, 1);
     void (*fn)(const KArgs) = nullptr;
-    int bytes;
+    int bytes, one_tap = 0;
     if constexpr ((AMODE == A_ROW_BT || AMODE == A_COL_BT) && T::SCHED < 4) {
         return hipErrorInvalidValue;   // a transposed right operand exists in the direct-to-LDS forms only
     } else if constexpr (T::SCHED >= 4) {
@@ -953,6 +960,13 @@ hipError_t launch_mode(int variant, const KArgs& a, int batch, hipStream_t s) {
         bytes = LdsDirect<T>::BYTES;
         fn = variant == 0 ? gemm_bf16_direct_kernel<T, AMODE, 0>
              : variant == 3 ? gemm_bf16_direct_kernel<T, AMODE, 2> : gemm_bf16_direct_kernel<T, AMODE, 1>;
+        if constexpr (AMODE == A_CONV) {
+            if (a.Cin % T::BK == 0) {
+                one_tap = 1;
+                fn = variant == 0 ? gemm_bf16_direct_kernel<T, AMODE, 0, true>
+                     : variant == 3 ? gemm_bf16_direct_kernel<T, AMODE, 2, true> : gemm_bf16_direct_kernel<T, AMODE, 1, true>;
+            }
+        }
     } else {
         constexpr int A_SIZE = (AMODE != A_COL) ? T::BM * T::LDK : T::BK * T::LDA_T;
         bytes = 2 * (A_SIZE + T::BK * T::LDB) * 2;
@@ -963,11 +977,12 @@ hipError_t launch_mode(int variant, const KArgs& a, int batch, hipStream_t s) {
             default: fn = gemm_bf16_kernel<T, AMODE, 1, true>; break;
         }
     }
-    static bool attr_done[4] = {false, false, false, false};
-    if (bytes > 48 * 1024 && !attr_done[variant]) {
+    static bool attr_done[8] = {false, false, false, false, false, false, false, false};   // per kernel function
+    const int fi = variant + 4 * one_tap;
+    if (bytes > 48 * 1024 && !attr_done[fi]) {
         hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
         if (e != hipSuccess) return e;
-        attr_done[variant] = true;
+        attr_done[fi] = true;
     }
     hipLaunchKernelGGL(fn, grid, block, bytes, s, a);
     return hipGetLastError();
