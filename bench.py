@@ -31,17 +31,17 @@ METRIC = "TFLOP/s and % of MI355X matrix peak, fp32 GEMM 4096^3 (1 GPU)"
 # An entry is reported only while the kernel sources still hash to the value it was taken
 # with and the launch uses the same tile config; otherwise `traffic` is null.
 TRAFFIC = {
-    1: [{"kernel_hash": "2a4398268d753407", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 1, "sched": 4, "split_k": 4, "split_tail": 1}, "bytes": 4064479}],
-    2: [{"kernel_hash": "2a4398268d753407", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 42058444}],
-    3: [{"kernel_hash": "2a4398268d753407", "tile": {"bm": 256, "bn": 256, "bk": 16, "wm": 128, "wn": 64, "vec": 4, "raster": 1, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 469926417},
-        {"kernel_hash": "2a4398268d753407", "tile": {"bm": 256, "bn": 256, "bk": 16, "wm": 128, "wn": 64, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 709855264}],
-    4: [{"kernel_hash": "2a4398268d753407", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 25403881}],
-    5: [{"kernel_hash": "9ac0ff38d75db70a", "tile": {"bm": 256, "bn": 256, "bk": 32, "wm": 128, "wn": 64, "vec": 8, "raster": 0, "sched": 5, "split_k": 1, "split_tail": 0}, "bytes": 1880597642}],
-    6: [{"kernel_hash": "2a4398268d753407", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 8, "split_tail": 0}, "bytes": 103047594}],
-    7: [{"kernel_hash": "8cf17b77e81162e1", "tile": {}, "bytes": 1073774872}],
-    8: [{"kernel_hash": "9ac0ff38d75db70a", "tile": {"bm": 64, "bn": 64, "bk": 64, "wm": 32, "wn": 32, "vec": 8, "raster": 0, "sched": 1, "split_k": 1, "split_tail": 0}, "bytes": 15976876}],
-    9: [{"kernel_hash": "2a4398268d753407", "tile": {"bm": 256, "bn": 256, "bk": 16, "wm": 128, "wn": 64, "vec": 4, "raster": 1, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 469980207}],
-    10: [{"kernel_hash": "2a4398268d753407", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 31862621}],
+    1: [{"kernel_hash": "3a484716e0033959", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 1, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 1960750}],
+    2: [{"kernel_hash": "3a484716e0033959", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 1, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 29487148}],
+    3: [{"kernel_hash": "3a484716e0033959", "tile": {"bm": 256, "bn": 256, "bk": 16, "wm": 128, "wn": 64, "vec": 4, "raster": 1, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 469892211},
+        {"kernel_hash": "3a484716e0033959", "tile": {"bm": 256, "bn": 256, "bk": 16, "wm": 128, "wn": 64, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 712540832}],
+    4: [{"kernel_hash": "3a484716e0033959", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 25352256}],
+    5: [{"kernel_hash": "620d3d1bc12fe825", "tile": {"bm": 256, "bn": 256, "bk": 32, "wm": 128, "wn": 64, "vec": 8, "raster": 0, "sched": 5, "split_k": 1, "split_tail": 0}, "bytes": 1880338799}],
+    6: [{"kernel_hash": "3a484716e0033959", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 2, "split_tail": 0}, "bytes": 80558541}],
+    7: [{"kernel_hash": "5a5acfd210620a2a", "tile": {}, "bytes": 1073776865}],
+    8: [{"kernel_hash": "620d3d1bc12fe825", "tile": {"bm": 64, "bn": 64, "bk": 64, "wm": 32, "wn": 32, "vec": 8, "raster": 1, "sched": 0, "split_k": 1, "split_tail": 0}, "bytes": 10397376}],
+    9: [{"kernel_hash": "3a484716e0033959", "tile": {"bm": 256, "bn": 256, "bk": 16, "wm": 128, "wn": 64, "vec": 4, "raster": 1, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 469904175}],
+    10: [{"kernel_hash": "3a484716e0033959", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 31817016}],
 }
 
 
