@@ -79,19 +79,21 @@ __device__ __forceinline__ void tile_coords(const KArgs& p, int bid, int& tm, in
         // Give each XCD a contiguous range of tile ids, then walk the range in groups of
         // kGroupM tile rows so that concurrently resident tiles share A and B panels in
         // that XCD's L2.
-        const int T = p.tiles_m * p.tiles_n;
-        const int xcd = bid % kXcds, loc = bid / kXcds;
-        const int q = T / kXcds, r = T % kXcds;
-        id = (xcd < r) ? xcd * (q + 1) + loc : r * (q + 1) + (xcd - r) * q + loc;
-        const int gsize = kGroupM * p.tiles_n;
-        const int g = id / gsize, in_g = id - g * gsize;
-        const int first_m = g * kGroupM;
-        const int gm = min(p.tiles_m - first_m, kGroupM);
-        tm = first_m + in_g % gm;
-        tn = in_g / gm;
+        // (every quantity is non-negative: unsigned divisions, which are cheaper)
+        const unsigned T = (unsigned)(p.tiles_m * p.tiles_n), ub = (unsigned)bid;
+        const unsigned xcd = ub % kXcds, loc = ub / kXcds;
+        const unsigned q = T / kXcds, r = T % kXcds;
+        const unsigned uid = (xcd < r) ? xcd * (q + 1) + loc : r * (q + 1) + (xcd - r) * q + loc;
+        const unsigned gsize = kGroupM * (unsigned)p.tiles_n;
+        const unsigned g = uid / gsize, in_g = uid - g * gsize;
+        const unsigned first_m = g * kGroupM;
+        const unsigned gm = min((unsigned)p.tiles_m - first_m, (unsigned)kGroupM);
+        const unsigned tnu = in_g / gm;
+        tm = (int)(first_m + (in_g - tnu * gm));
+        tn = (int)tnu;
         return;
     }
-    tm = id / p.tiles_n;
+    tm = (int)((unsigned)id / (unsigned)p.tiles_n);
     tn = id - tm * p.tiles_n;
 }
 
@@ -105,7 +107,7 @@ __device__ __forceinline__ void decode_block(const KArgs& p, int tiles, int& til
         return;
     }
     const int r = bid - p.split_first, rem = tiles - p.split_first;
-    split = r / rem;
+    split = (int)((unsigned)r / (unsigned)rem);
     const int t = r - split * rem;
     tile = p.split_first + t;
     nsplit = p.split_k;
@@ -218,20 +220,27 @@ __device__ __forceinline__ void finish_tile(const KArgs& p, f32x16 (&acc)[T::MI]
         for (int j = 0; j < NI; ++j) {
             const int col = n0 + wn0 + j * 32 + li;
             float* c0 = C + (long long)(m0 + wm0 + i * 32 + 4 * lh) * p.ldc + col;   // row of r = 0
+            // element r sits 8 (r / 4) + r % 4 rows below: the row pointer steps, no multiply per element
             float old[16];
+            if constexpr (ACCUM) {
+                float* rp = c0;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int dr = 8 * (r >> 2) + (r & 3);
-                const bool ok = !CHECK || (m0 + wm0 + i * 32 + 4 * lh + dr < p.M && col < p.N);
-                old[r] = (ACCUM && ok) ? c0[(long long)dr * p.ldc] : 0.f;
+                for (int r = 0; r < 16; ++r) {
+                    const int dr = 8 * (r >> 2) + (r & 3);
+                    const bool ok = !CHECK || (m0 + wm0 + i * 32 + 4 * lh + dr < p.M && col < p.N);
+                    old[r] = ok ? *rp : 0.f;
+                    rp += (r & 3) == 3 ? 5 * p.ldc : p.ldc;
+                }
             }
+            float* rp = c0;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int dr = 8 * (r >> 2) + (r & 3);
                 const bool ok = !CHECK || (m0 + wm0 + i * 32 + 4 * lh + dr < p.M && col < p.N);
                 const float v = acc[i][j][r];
                 const float sv = neg ? -v : v;
-                if (ok) c0[(long long)dr * p.ldc] = ACCUM ? sv + old[r] : sv;   // no add without the flag: -0 stays -0
+                if (ok) *rp = ACCUM ? sv + old[r] : sv;   // no add without the flag: -0 stays -0
+                rp += (r & 3) == 3 ? 5 * p.ldc : p.ldc;
             }
         }
     };
@@ -268,8 +277,12 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_kernel(const KArgs p)
     const bool interior = !EDGE || (m0 + BM <= p.m_main && n0 + BN <= p.n_main);
     // this workgroup's k steps: [kb, kb + nk) of the (K + BK - 1) / BK steps of the whole loop
     const int nk_all = (p.K + BK - 1) / BK;
-    const int kb = (int)((long long)nk_all * split / nsplit);
-    const int nk = (int)((long long)nk_all * (split + 1) / nsplit) - kb;
+    // (unsigned 32-bit: nk_all < 2^27 and nsplit <= 16; an unsplit tile divides nothing)
+    int kb = 0, nk = nk_all;
+    if (nsplit > 1) {
+        kb = (int)((unsigned)(nk_all * split) / (unsigned)nsplit);
+        nk = (int)((unsigned)(nk_all * (split + 1)) / (unsigned)nsplit) - kb;
+    }
 
     // ---- per-thread global->LDS assignment: 4-element chunks along the contiguous dim
     constexpr int A_CPR = (AMODE == A_COL) ? BM / 4 : BK / 4;   // chunks per stored row
@@ -706,8 +719,12 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
 
     const bool interior = !EDGE || (m0 + BM <= p.m_main && n0 + BN <= p.n_main);
     const int nk_all = (p.K + BK - 1) / BK;
-    const int kb = (int)((long long)nk_all * split / nsplit);
-    const int nk = (int)((long long)nk_all * (split + 1) / nsplit) - kb;
+    // (unsigned 32-bit: nk_all < 2^27 and nsplit <= 16; an unsplit tile divides nothing)
+    int kb = 0, nk = nk_all;
+    if (nsplit > 1) {
+        kb = (int)((unsigned)(nk_all * split) / (unsigned)nsplit);
+        nk = (int)((unsigned)(nk_all * (split + 1)) / (unsigned)nsplit) - kb;
+    }
 
     // Leading steps of this workgroup whose chunks are all whole (inside or outside).
     // EDGEV 2 peels the k loop like Fig. 8: the ring runs the steps that lie wholly below K
