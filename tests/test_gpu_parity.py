@@ -323,6 +323,46 @@ def test_default_config_with_a_tail_only_split(workspace):
                               oracle.gemm(A, np.ascontiguousarray(B[:, cols]), with_s=False))
 
 
+@pytest.mark.parametrize("dtype", [tsg.F32, tsg.BF16_F32ACC])
+def test_remainder_variants_of_the_direct_kernels(dtype, workspace):
+    """The direct-to-LDS kernels treat a remainder in three ways: rows and columns past M / N
+    clamped to the last valid one, a partial last k step peeled off the ring (through the
+    block of zeros when K ends on a chunk boundary, through the masked path when it cuts a
+    chunk), and the general masked ring when chunks are cut along M or N.  One shape per case
+    and operand layout, with and without a split of k, integer data, bit for bit."""
+    v = 4 if dtype == tsg.F32 else 8
+    bk = 32 if dtype == tsg.F32 else 64
+    cases = [
+        (3 * 64 + 5, 2 * 64 + v, 4 * bk),            # M and N remainders only
+        (2 * 64, 2 * 64, 3 * bk + 2 * v),            # partial last k step, whole chunks
+        (2 * 64 + 9, 64 + 2 * v, 2 * bk + v + 1),    # K cuts a chunk
+        (64 + 3, 64 + v + 1, 2 * bk + 3),            # N cuts a chunk: the general variant
+        (v, v, 5), (64, 64, bk - 1), (1, 2 * v, 2 * bk),
+    ]
+    for ta in (False, True):
+        for tb in (False, True):
+            op = tsg.OP_GEMM_TRANSA if ta else tsg.OP_GEMM
+            for (M, N, K) in cases:
+                if ta and M % v:
+                    M += v - M % v                       # keep A^T's rows whole chunks except in the general case
+                A = inputs(M, 1, K, 61, "ints", ta, dtype)[0]
+                B = (inputs(N, 1, K, 62, "ints", False, dtype)[0] if tb
+                     else inputs(1, N, K, 62, "ints", False, dtype)[1])
+                R = oracle.gemm(A, B, trans_a=ta, trans_b=tb, with_s=False)
+                for split in (1, 2):
+                    c = tsg.TileConfig(bm=64, bn=64, bk=bk, wm=32, wn=32, vec=v, raster=0, sched=4, split_k=split)
+                    if tsg.tile_config_check(op, dtype, M, N, K, c) != tsg.OK:
+                        continue
+                    tsg.tile_config_set(op, dtype, c)
+                    dC = torch.full((M, N), -4.0, dtype=torch.float32, device=DEV)
+                    tsg.gemm_trans(dtype, ta, tb, 1, M, N, K, dev(A), A.shape[1], 0, dev(B), B.shape[1], 0, dC, N, 0,
+                                   tsg.STRICT)
+                    torch.cuda.synchronize()
+                    li = tsg.last_launch()
+                    assert li.alternative == 0 and li.config.sched == 4 and li.config.split_k == split
+                    assert np.array_equal(dC.cpu().numpy().astype(np.float64), R), (ta, tb, M, N, K, split)
+
+
 def test_one_hot_and_identity_on_device():
     M, N, K = 150, 140, 130
     B = synth.uniform_pm1(2, 1, K * N).reshape(K, N)
