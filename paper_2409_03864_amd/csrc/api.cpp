@@ -185,9 +185,11 @@ tsg_tile_config heuristic(tsg_dtype dt, int64_t batch, int64_t M, int64_t N, int
                 const double est = model_cycles(dt, t[i], split, tail, batch, M, N, K);
                 if (first || est < best * 0.999) { best = est; best_i = i; best_split = split; best_tail = tail; first = false; }
             }
-    // fp32: the XCD-aware raster takes the same time and fetches fewer bytes; bf16: the row-major
-    // order measured 1-6 % faster at every size tried
-    return config_of(t[best_i], vec_max(dt), dt == TSG_F32 ? 1 : 0, best_split, best_tail);
+    // fp32: the XCD-aware raster takes the same time and fetches fewer bytes once there is a tile for
+    // every CU; below that the row-major order does as well and decodes with one division instead of
+    // four.  bf16: the row-major order measured 1-6 % faster at every size tried
+    const int64_t n_tiles = batch * ((M + t[best_i].bm - 1) / t[best_i].bm) * ((N + t[best_i].bn - 1) / t[best_i].bn);
+    return config_of(t[best_i], vec_max(dt), dt == TSG_F32 && n_tiles >= kCUs ? 1 : 0, best_split, best_tail);
 }
 
 // Fill zero fields from `def` (Sec. 3.4: a tile size of 0 changes nothing, so the library default stands).
