@@ -270,11 +270,11 @@ tsg_status make_plan(const Problem& p, const tsg_tile_config& cfg, int alternati
     const bool edge = m_rest || n_rest || k_rest;
     out->entry = e;
     out->cfg = cfg;
-    // remainder variant 3: no chunk is cut by the end of a row along M or N (operands that are
-    // contiguous along those extents have them as multiples of the access width); a chunk cut by
-    // K only occurs in the last k step, which that variant peels off
+    // remainder variant 3 (clamped rows, peeled last k step) serves every shape whose extents
+    // along the operands' contiguous dimensions hold at least one whole access; narrower ones
+    // (N < 4 with a row-major B, M < 4 with a transposed A) take the general variant 1
     const int64_t v = vec_max(p.dtype);
-    const bool cut = (!p.trans_b && p.N % v) || (p.op == TSG_OP_GEMM_TRANSA && p.M % v);
+    const bool cut = (!p.trans_b && p.N < v) || (p.op == TSG_OP_GEMM_TRANSA && p.M < v);
     out->variant = cfg.vec == 1 ? 2 : (edge ? (cut ? 1 : 3) : 0);
 
     KArgs& a = out->args;

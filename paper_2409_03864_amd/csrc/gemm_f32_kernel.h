@@ -666,12 +666,12 @@ struct LdsDirect {
     static constexpr int BYTES = STAGES * STAGE * (int)sizeof(float);
 };
 
-// EDGEV: 0 = every loop divides (no remainder code); 1 = remainder code, chunks may be cut by the
-// end of a row in every step (masked register path compiled into the ring); 2 = remainder code for
-// operands whose chunks along M and N are never cut: rows and columns past the end are clamped, the
-// ring runs the full k steps without a test as one scheduling region, and the partial last k step
-// is peeled off (the masked path and its branch inside the ring cost a 64 x 64 tile a third of its
-// speed even when never taken).
+// EDGEV: 0 = every loop divides (no remainder code); 1 = remainder code with the masked register
+// path compiled into the ring (kept for operands narrower than one access); 2 = the remainder
+// variant in use: rows and columns past the end are clamped, the ring runs the full k steps without
+// a test as one scheduling region, and the last k step is peeled off when it is partial or when the
+// tile's chunks are cut along M or N (the masked path and its branch inside the ring cost a 64 x 64
+// tile a third of its speed even when never taken).
 // ONE_TAP (convolution only): Cin is a multiple of BK, so a k step lies inside one filter tap.
 // A template parameter rather than a test at run time: the general form divides per chunk, and
 // a two-sided branch between the MFMAs of a step splits the step's scheduling region.
@@ -729,7 +729,14 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
     // Leading steps of this workgroup whose chunks are all whole (inside or outside).
     // EDGEV 2 peels the k loop like Fig. 8: the ring runs the steps that lie wholly below K
     // without any test, and a last partial step is staged through registers after it
-    const int nkp = CLAMP ? min(nk, max(0, p.k_full - kb)) : nk;   // steps that go through the ring
+    // A tile whose chunks are cut by the end of a row along N (row-major B) or M (transposed A)
+    // still takes whole 16-byte loads in the ring: the bytes past the end of a row are the start
+    // of the next row, and only feed columns / rows of C that are never stored.  The last row of
+    // the operand has no next row, so for such a tile the last k step is always peeled.
+    const bool cut_tile = CLAMP && ((!B_KMAJ && (p.N % 4) && n0 + BN > p.N) || (AMODE == A_COL && (p.M % 4) && m0 + BM > p.M));
+    int nkp_ = CLAMP ? min(nk, max(0, p.k_full - kb)) : nk;
+    if (cut_tile && kb + nk == nk_all) nkp_ = min(nkp_, nk - 1);
+    const int nkp = nkp_;   // steps that go through the ring
     int n_direct = nkp;
     if constexpr (CUT) {
         bool whole_tile = !(!B_KMAJ && (p.N & 3) && n0 + BN > p.N);            // rows of B are cut mid-chunk
@@ -767,7 +774,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
         } else if constexpr (AMODE == A_COL) {
             a_k[q] = row;   // the stored row is the k index
             a_in[q] = !CUT || m0 + a_cp * 4 < p.M;
-            a_src[q] = A + (long long)row * p.lda + (CLAMP ? min(m0 + a_cp * 4, p.M - 4) : m0 + a_cp * 4);
+            a_src[q] = A + (long long)row * p.lda + (CLAMP && m0 + a_cp * 4 >= p.M ? max(p.M - 4, 0) : m0 + a_cp * 4);
         } else {
             a_k[q] = (a_cp ^ swz(row)) * 4;
             const int m = m0 + row;
@@ -807,7 +814,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
         } else {
             b_k[q] = row;
             b_in[q] = !CUT || n0 + b_cp * 4 < p.N;
-            b_src[q] = B + (long long)row * p.ldb + (CLAMP ? min(n0 + b_cp * 4, p.N - 4) : n0 + b_cp * 4);
+            b_src[q] = B + (long long)row * p.ldb + (CLAMP && n0 + b_cp * 4 >= p.N ? max(p.N - 4, 0) : n0 + b_cp * 4);
         }
     }
 
@@ -1075,10 +1082,11 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
     if constexpr (CLAMP) {
         if (nkp < nk) {
             // the partial last step into stage 0, multiplied group by group: chunks past K come
-            // from the block of zeros, or, when K cuts a chunk of a k-contiguous operand, the
-            // whole tile goes through registers with element masks
+            // from the block of zeros, or, when K cuts a chunk of a k-contiguous operand or the
+            // tile's chunks are cut along M or N, the whole tile goes through registers with
+            // element masks
             __syncthreads();   // everybody has left the ring
-            if (p.K % 4) {
+            if ((p.K % 4) || cut_tile) {
                 issue_masked(kb + nkp, 0);
             } else {
 #pragma unroll

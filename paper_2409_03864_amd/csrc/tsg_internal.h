@@ -54,7 +54,7 @@ struct KernelEntry {
     int vec;         // elements per 16-byte access for this dtype
     int lds_bytes;   // LDS per workgroup (both stages, k-contiguous A layout)
     // variant: 0 = vec, no remainder path; 1 = vec with remainder path; 3 = vec with the remainder
-    // path for operands whose 16-byte chunks are never cut along M or N; 2 = scalar
+    // path that clamps and peels (every operand at least one access wide); 2 = scalar
     // accesses with remainder path
     hipError_t (*launch)(int tile, int amode, int variant, const KArgs& a, int batch, hipStream_t s);
 };
