@@ -34,6 +34,11 @@
  *    alternatives (the config pinned by the caller, else the tuner's result for
  *    this very problem -> the library's default for the shape -> that tile with
  *    scalar accesses) and only fails definitely.
+ *  - Operands are fetched in 16-byte accesses from any element-aligned address.  An access
+ *    that starts inside a row may run up to 12 bytes past the row's end into the following
+ *    row of the same operand (ld >= row length keeps that inside the operand); the last
+ *    row of an operand is never read past its end, and nothing outside
+ *    [base, base + (rows - 1) * ld + row length) is touched.
  *  - Extents must fit in int32 (each of M, N, K, and every tensor's element count
  *    for convolution); larger values are TSG_E_INVALID.
  *  - The config registry, the tuner's results and the workspace pointer are guarded
