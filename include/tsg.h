@@ -35,7 +35,7 @@
  *    this very problem -> the library's default for the shape -> that tile with
  *    scalar accesses) and only fails definitely.
  *  - Operands are fetched in 16-byte accesses from any element-aligned address.  An access
- *    that starts inside a row may run up to 12 bytes past the row's end into the following
+ *    that starts inside a row may run past the row's end (by less than 16 bytes) into the following
  *    row of the same operand (ld >= row length keeps that inside the operand); the last
  *    row of an operand is never read past its end, and nothing outside
  *    [base, base + (rows - 1) * ld + row length) is touched.
