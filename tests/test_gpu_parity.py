@@ -954,3 +954,108 @@ def test_calls_recorded_into_a_hip_graph_replay_correctly(workspace):
         tsg.gemm(tsg.F32, M, N, K, dA, K, dB, N, tmp, N, tsg.STRICT)
         torch.cuda.synchronize()
         assert torch.equal(tmp, eager)
+
+
+# ------------------------------------------------------------------ seeded differential runs
+
+def test_many_seeded_gemm_cases_random_configs(workspace):
+    """1500 small products with everything drawn from a seeded generator: dtype, which operands
+    are stored transposed, batch, ragged extents, flags, and (70 %) a random legal config pinned
+    under TSG_STRICT, else the library's own choice.  Integer data, bit for bit."""
+    import random
+    rng = random.Random(20240903)
+    done = 0
+    while done < 1500:
+        dt = rng.choice([tsg.F32, tsg.BF16_F32ACC])
+        ta, tb = rng.random() < 0.4, rng.random() < 0.3
+        big = rng.random() < 0.2
+        M, N = rng.randint(1, 700 if big else 200), rng.randint(1, 700 if big else 200)
+        K = rng.randint(1, 200 if big else 500)
+        nb = rng.choice([1, 1, 1, 2, 3])
+        op = tsg.OP_GEMM_TRANSA if ta else tsg.OP_GEMM
+        seed = rng.randint(0, 1 << 20)
+        A = synth.small_ints(seed, 0, nb * M * K).reshape((nb, K, M) if ta else (nb, M, K))
+        B = synth.small_ints(seed, 1, nb * K * N).reshape((nb, N, K) if tb else (nb, K, N))
+        if dt == tsg.BF16_F32ACC:
+            A, B = synth.f32_to_bf16_bits(A), synth.f32_to_bf16_bits(B)
+        C0 = synth.small_ints(seed, 2, nb * M * N).reshape(nb, M, N)
+        flags = rng.choice([0, tsg.NEGATE, tsg.ACCUMULATE, tsg.NEGATE | tsg.ACCUMULATE])
+        pin = None
+        if rng.random() < 0.7:
+            cnt = tsg.tile_config_count(op, dt)
+            for _ in range(20):
+                c = tsg.tile_config_enum(op, dt, rng.randrange(cnt))
+                if tsg.tile_config_check(op, dt, M, N, K, c) == tsg.OK and not (tb and c.sched < 4):
+                    pin = c
+                    break
+        tsg.tile_config_set(op, dt, pin)
+        dA, dB, dC = dev(A), dev(B), dev(C0)
+        lda, ldb = A.shape[2], B.shape[2]
+        try:
+            tsg.gemm_trans(dt, ta, tb, nb, M, N, K, dA, lda, A.shape[1] * lda, dB, ldb, B.shape[1] * ldb, dC, N, M * N,
+                           flags | (tsg.STRICT if pin is not None else 0))
+        except tsg.SilenceableError:      # a split whose workspace need exceeds the fixture's, say
+            assert pin is not None
+            continue
+        torch.cuda.synchronize()
+        out = dC.cpu().numpy()
+        for b in range(nb):
+            ref = oracle.epilogue(oracle.gemm(A[b], B[b], trans_a=ta, trans_b=tb, with_s=False), flags & 3, C0[b])
+            assert np.array_equal(out[b].astype(np.float64), ref), (dt, ta, tb, nb, M, N, K, flags, pin, b)
+        done += 1
+
+
+def test_many_seeded_conv_cases_random_configs(workspace):
+    """2500 small convolutions drawn from a seeded generator (geometry, strides, padding, channel
+    counts on and off the access width, dtype, flags, a random legal config or the library's
+    choice), each written into a window of a larger tensor with a random ring and channel
+    padding.  Integer data: the whole larger tensor must match, window and surroundings."""
+    import random
+    rng = random.Random(3864)
+    op = tsg.OP_CONV2D_NHWC
+    done = 0
+    while done < 2500:
+        dt = rng.choice([tsg.F32, tsg.BF16_F32ACC])
+        Nn, H, W = rng.randint(1, 4), rng.randint(1, 24), rng.randint(1, 24)
+        Cin = rng.choice([1, 3, 4, 8, 12, 16, 24, 32, 64])
+        Cout = rng.choice([1, 5, 8, 16, 64, 70, 130])
+        KH, KW = rng.choice([1, 2, 3, 5]), rng.choice([1, 2, 3, 5])
+        st = (rng.choice([1, 2]), rng.choice([1, 2]))
+        pd = (rng.randint(0, 2), rng.randint(0, 2))
+        if H + 2 * pd[0] < KH or W + 2 * pd[1] < KW:
+            continue
+        Ho, Wo = oracle.conv_out_dim(H, KH, st[0], pd[0]), oracle.conv_out_dim(W, KW, st[1], pd[1])
+        seed = rng.randint(0, 1 << 20)
+        x, w = synth.conv_inputs(Nn, H, W, Cin, Cout, KH, KW, seed=seed, dist="ints")
+        if dt == tsg.BF16_F32ACC:
+            x, w = synth.f32_to_bf16_bits(x), synth.f32_to_bf16_bits(w)
+        flags = rng.choice([0, tsg.NEGATE, tsg.ACCUMULATE, tsg.NEGATE | tsg.ACCUMULATE])
+        ring, cpad = rng.choice([0, 0, 1, 3]), rng.choice([0, 0, 4])
+        pin = None
+        if rng.random() < 0.7:
+            cnt = tsg.tile_config_count(op, dt)
+            for _ in range(20):
+                c = tsg.tile_config_enum(op, dt, rng.randrange(cnt))
+                if tsg.tile_config_check(op, dt, Nn * Ho * Wo, Cout, KH * KW * Cin, c, contig=Cin) == tsg.OK:
+                    pin = c
+                    break
+        tsg.tile_config_set(op, dt, pin)
+        big0 = synth.small_ints(seed, 2, Nn * (Ho + 2 * ring) * (Wo + 2 * ring) * (Cout + cpad)).reshape(
+            Nn, Ho + 2 * ring, Wo + 2 * ring, Cout + cpad)
+        dbig = dev(big0)
+        sw_ = Cout + cpad
+        sh_ = (Wo + 2 * ring) * sw_
+        sn_ = (Ho + 2 * ring) * sh_
+        try:
+            tsg.conv2d_nhwc_window(dt, Nn, H, W, Cin, Cout, KH, KW, st[0], st[1], pd[0], pd[1], dev(x), dev(w),
+                                   dbig.data_ptr() + 4 * (ring * sh_ + ring * sw_), sn_, sh_, sw_,
+                                   flags | (tsg.STRICT if pin is not None else 0))
+        except tsg.SilenceableError:
+            assert pin is not None
+            continue
+        torch.cuda.synchronize()
+        ref = big0.astype(np.float64).copy()
+        inner = (slice(None), slice(ring, ring + Ho), slice(ring, ring + Wo), slice(0, Cout))
+        ref[inner] = oracle.epilogue(oracle.conv2d_nhwc(x, w, stride=st, pad=pd, with_s=False), flags & 3, big0[inner])
+        assert np.array_equal(dbig.cpu().numpy().astype(np.float64), ref), (dt, Nn, H, W, Cin, Cout, KH, KW, st, pd, flags, ring, cpad, pin)
+        done += 1
