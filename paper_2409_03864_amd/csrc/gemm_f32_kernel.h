@@ -183,8 +183,9 @@ __device__ __forceinline__ void finish_tile(const KArgs& p, f32x16 (&acc)[T::MI]
 #pragma unroll
             for (int rg = 0; rg < 4; ++rg) {
                 const int row0 = m0 + wm0 + i * 32 + 8 * rg + 4 * lh;
-                int wo = row0 % p.Wo, t = row0 / p.Wo;
-                int ho = t % p.Ho, n = t / p.Ho;
+                // (non-negative: unsigned divisions)
+                const unsigned tq = (unsigned)row0 / (unsigned)p.Wo, nq = tq / (unsigned)p.Ho;
+                int wo = row0 - (int)tq * p.Wo, ho = (int)(tq - nq * (unsigned)p.Ho), n = (int)nq;
                 float* dst[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -781,8 +782,9 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_f32_direct_kernel(const K
             a_in[q] = !CUT || m < p.M;
             a_src[q] = A;
             const int mm = CLAMP ? min(m, p.M - 1) : a_in[q] ? m : 0;
-            const int wo = mm % p.Wo, t = mm / p.Wo;
-            const int ho = t % p.Ho, n = t / p.Ho;
+            // (non-negative: unsigned divisions)
+            const unsigned tq = (unsigned)mm / (unsigned)p.Wo, nq = tq / (unsigned)p.Ho;
+            const int wo = mm - (int)tq * p.Wo, ho = (int)(tq - nq * (unsigned)p.Ho), n = (int)nq;
             cv_base[q] = n * p.H;
             cv_hi0[q] = ho * p.sh - p.ph;
             cv_wi0[q] = wo * p.sw - p.pw;
