@@ -31,17 +31,17 @@ METRIC = "TFLOP/s and % of MI355X matrix peak, fp32 GEMM 4096^3 (1 GPU)"
 # An entry is reported only while the kernel sources still hash to the value it was taken
 # with and the launch uses the same tile config; otherwise `traffic` is null.
 TRAFFIC = {
-    1: [{"kernel_hash": "bdedbfe49ad5f9ee", "tile": {"bm": 64, "bn": 64, "bk": 64, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 2, "split_tail": 0}, "bytes": 3005080}],
-    2: [{"kernel_hash": "bdedbfe49ad5f9ee", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 42050398}],
-    3: [{"kernel_hash": "bdedbfe49ad5f9ee", "tile": {"bm": 256, "bn": 256, "bk": 16, "wm": 128, "wn": 64, "vec": 4, "raster": 1, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 469851375},
-        {"kernel_hash": "bdedbfe49ad5f9ee", "tile": {"bm": 256, "bn": 256, "bk": 16, "wm": 128, "wn": 64, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 713156771}],
-    4: [{"kernel_hash": "bdedbfe49ad5f9ee", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 25338654}],
-    5: [{"kernel_hash": "3021d531056e3737", "tile": {"bm": 256, "bn": 256, "bk": 32, "wm": 128, "wn": 64, "vec": 8, "raster": 0, "sched": 5, "split_k": 1, "split_tail": 0}, "bytes": 1882348969}],
-    6: [{"kernel_hash": "bdedbfe49ad5f9ee", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 2, "split_tail": 0}, "bytes": 80535450}],
-    7: [{"kernel_hash": "d10a7497de24466a", "tile": {}, "bytes": 1073783483}],
-    8: [{"kernel_hash": "3021d531056e3737", "tile": {"bm": 64, "bn": 64, "bk": 64, "wm": 32, "wn": 32, "vec": 8, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 15951979}],
-    9: [{"kernel_hash": "bdedbfe49ad5f9ee", "tile": {"bm": 256, "bn": 256, "bk": 16, "wm": 128, "wn": 64, "vec": 4, "raster": 1, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 469873961}],
-    10: [{"kernel_hash": "bdedbfe49ad5f9ee", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 31817979}],
+    1: [{"kernel_hash": "5aedbfbce58f8f9b", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 1, "sched": 0, "split_k": 2, "split_tail": 1}, "bytes": 2986531}],
+    2: [{"kernel_hash": "5aedbfbce58f8f9b", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 42057384}],
+    3: [{"kernel_hash": "5aedbfbce58f8f9b", "tile": {"bm": 256, "bn": 256, "bk": 16, "wm": 128, "wn": 64, "vec": 4, "raster": 1, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 469877892},
+        {"kernel_hash": "5aedbfbce58f8f9b", "tile": {"bm": 256, "bn": 256, "bk": 16, "wm": 128, "wn": 64, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 711738764}],
+    4: [{"kernel_hash": "5aedbfbce58f8f9b", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 25338801}],
+    5: [{"kernel_hash": "f63d1a24b38d7b5e", "tile": {"bm": 256, "bn": 256, "bk": 32, "wm": 128, "wn": 64, "vec": 8, "raster": 1, "sched": 5, "split_k": 1, "split_tail": 0}, "bytes": 1883097699}],
+    6: [{"kernel_hash": "5aedbfbce58f8f9b", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 2, "split_tail": 0}, "bytes": 80547169}],
+    7: [{"kernel_hash": "d10a7497de24466a", "tile": {}, "bytes": 1073783428}],
+    8: [{"kernel_hash": "f63d1a24b38d7b5e", "tile": {"bm": 64, "bn": 64, "bk": 64, "wm": 32, "wn": 32, "vec": 8, "raster": 1, "sched": 0, "split_k": 1, "split_tail": 0}, "bytes": 10379953}],
+    9: [{"kernel_hash": "5aedbfbce58f8f9b", "tile": {"bm": 256, "bn": 256, "bk": 16, "wm": 128, "wn": 64, "vec": 4, "raster": 1, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 469852450}],
+    10: [{"kernel_hash": "5aedbfbce58f8f9b", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 31818942}],
 }
 
 
