@@ -31,17 +31,17 @@ METRIC = "TFLOP/s and % of MI355X matrix peak, fp32 GEMM 4096^3 (1 GPU)"
 # An entry is reported only while the kernel sources still hash to the value it was taken
 # with and the launch uses the same tile config; otherwise `traffic` is null.
 TRAFFIC = {
-    1: [{"kernel_hash": "5aedbfbce58f8f9b", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 1, "sched": 0, "split_k": 2, "split_tail": 1}, "bytes": 2986531}],
-    2: [{"kernel_hash": "5aedbfbce58f8f9b", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 42057384}],
-    3: [{"kernel_hash": "5aedbfbce58f8f9b", "tile": {"bm": 256, "bn": 256, "bk": 16, "wm": 128, "wn": 64, "vec": 4, "raster": 1, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 469877892},
-        {"kernel_hash": "5aedbfbce58f8f9b", "tile": {"bm": 256, "bn": 256, "bk": 16, "wm": 128, "wn": 64, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 711738764}],
-    4: [{"kernel_hash": "5aedbfbce58f8f9b", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 25338801}],
-    5: [{"kernel_hash": "f63d1a24b38d7b5e", "tile": {"bm": 256, "bn": 256, "bk": 32, "wm": 128, "wn": 64, "vec": 8, "raster": 1, "sched": 5, "split_k": 1, "split_tail": 0}, "bytes": 1883097699}],
-    6: [{"kernel_hash": "5aedbfbce58f8f9b", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 2, "split_tail": 0}, "bytes": 80547169}],
-    7: [{"kernel_hash": "d10a7497de24466a", "tile": {}, "bytes": 1073783428}],
-    8: [{"kernel_hash": "f63d1a24b38d7b5e", "tile": {"bm": 64, "bn": 64, "bk": 64, "wm": 32, "wn": 32, "vec": 8, "raster": 1, "sched": 0, "split_k": 1, "split_tail": 0}, "bytes": 10379953}],
-    9: [{"kernel_hash": "5aedbfbce58f8f9b", "tile": {"bm": 256, "bn": 256, "bk": 16, "wm": 128, "wn": 64, "vec": 4, "raster": 1, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 469852450}],
-    10: [{"kernel_hash": "5aedbfbce58f8f9b", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 31818942}],
+    1: [{"kernel_hash": "5aedbfbce58f8f9b", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 1, "sched": 0, "split_k": 2, "split_tail": 1}, "bytes": 2986531, "source": "profiles/gemm_f32_256.txt"}],
+    2: [{"kernel_hash": "5aedbfbce58f8f9b", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 42057384, "source": "profiles/gemm_f32_transA_1024.txt"}],
+    3: [{"kernel_hash": "5aedbfbce58f8f9b", "tile": {"bm": 256, "bn": 256, "bk": 16, "wm": 128, "wn": 64, "vec": 4, "raster": 1, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 469877892, "source": "profiles/gemm_f32_4096.txt"},
+        {"kernel_hash": "5aedbfbce58f8f9b", "tile": {"bm": 256, "bn": 256, "bk": 16, "wm": 128, "wn": 64, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 711738764, "source": "profiles/gemm_f32_4096.txt"}],
+    4: [{"kernel_hash": "5aedbfbce58f8f9b", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 25338801, "source": "profiles/conv2d_f32_8x56x56x64.txt"}],
+    5: [{"kernel_hash": "f63d1a24b38d7b5e", "tile": {"bm": 256, "bn": 256, "bk": 32, "wm": 128, "wn": 64, "vec": 8, "raster": 1, "sched": 5, "split_k": 1, "split_tail": 0}, "bytes": 1883097699, "source": "profiles/gemm_bf16_8192_negate.txt"}],
+    6: [{"kernel_hash": "5aedbfbce58f8f9b", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 2, "split_tail": 0}, "bytes": 80547169, "source": "profiles/gemm_f32_batched_196x256x2305.txt"}],
+    7: [{"kernel_hash": "d10a7497de24466a", "tile": {}, "bytes": 1073783428, "source": "profiles/reduce_sum_f32_1gib.txt"}],
+    8: [{"kernel_hash": "f63d1a24b38d7b5e", "tile": {"bm": 64, "bn": 64, "bk": 64, "wm": 32, "wn": 32, "vec": 8, "raster": 1, "sched": 0, "split_k": 1, "split_tail": 0}, "bytes": 10379953, "source": "profiles/conv2d_bf16_8x56x56x64.txt"}],
+    9: [{"kernel_hash": "5aedbfbce58f8f9b", "tile": {"bm": 256, "bn": 256, "bk": 16, "wm": 128, "wn": 64, "vec": 4, "raster": 1, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 469852450, "source": "profiles/gemm_f32_both_transposed_4096.txt"}],
+    10: [{"kernel_hash": "5aedbfbce58f8f9b", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0}, "bytes": 31818942, "source": "profiles/conv2d_f32_window_accumulate.txt"}],
 }
 
 
@@ -57,10 +57,11 @@ def kernel_hash(dtype: str, op: str = "") -> str:
 
 
 def traffic_bytes(k: int, dtype: str, tile: dict, op: str = ""):
+    """(bytes per launch, the summary under profiles/ they were taken from), or (None, None)."""
     for e in TRAFFIC.get(k, ()):
         if e["kernel_hash"] == kernel_hash(dtype, op) and all(tile.get(key) == val for key, val in e["tile"].items()):
-            return e["bytes"]
-    return None
+            return e["bytes"], e.get("source")
+    return None, None
 
 
 def log(*a):
@@ -97,6 +98,47 @@ def describe(k, c) -> str:
         ", negate fused" if "negate" in c["flags"] else "")
 
 
+def result_record(k, c, mnk, steps, warmup, wall_s, kernel_ms_avg, tile, alternative, tuned, graph, cpu, search):
+    """The one JSON object of a run: a couple of kilobytes at most, so that a harness which
+    keeps only the tail of stdout still holds all of it.  The tuner's evaluated points are not
+    part of it (they go to stderr and, with --tuner-log, to a file)."""
+    M, N, K = mnk
+    flops = workload_flops(c)
+    hbm_bound = c["op"] == "reduce_sum"
+    step_s = wall_s / steps
+    if hbm_bound:
+        # bound by HBM: algorithmic bytes = every element read once (the 4-byte result is noise)
+        work, unit, peak, scale = c["rows"] * c["cols"] * 4, "GB/s", PEAK_HBM_GBS, 1e9
+    else:
+        work, unit, peak, scale = flops, "TFLOP/s", PEAK_TFLOPS[c["dtype"]], 1e12
+    value = work / step_s / scale
+    achieved = work / (kernel_ms_avg * 1e-3) / scale
+    traffic, source = traffic_bytes(k, c["dtype"], {} if hbm_bound else tile, c["op"])
+    roofline = {"bound": "hbm" if hbm_bound else "mfma", "achieved": achieved, "peak": peak, "unit": unit,
+                "frac": achieved / peak, "traffic": traffic,
+                # `traffic` is not measured by this run: it is the stored figure of two counter passes over
+                # this kernel (file named here), reported only while sources and tile config still match
+                "traffic_source": source,
+                # HBM rate those bytes amount to at this run's launch time
+                "hbm_gbs": None if traffic is None else traffic / (kernel_ms_avg * 1e-3) / 1e9,
+                "kernel_ms_avg": kernel_ms_avg, "kernel_hash": kernel_hash(c["dtype"], c["op"])}
+    out = {
+        "metric": METRIC if k == 3 else ("GB/s and % of MI355X HBM peak, " if hbm_bound else
+                                         "TFLOP/s and % of MI355X matrix peak, ") + describe(k, c),
+        "value": value, "unit": unit, "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": step_s * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": c["dtype"], "data": "synthetic",
+        "pct_of_peak": 100.0 * value / peak,
+        "config": {"workload": describe(k, c), "M": M, "N": N, "K": K, "flops_per_step": flops,
+                   "tile_config": tile, "alternative": alternative, "tuned": tuned, "hip_graph": graph},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    if search is not None:
+        out["search"] = search
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -109,6 +151,8 @@ def main() -> int:
     ap.add_argument("--graph", action="store_true",
                     help="record the K steps once into a HIP graph and time one replay (launch-bound workloads)")
     ap.add_argument("--evals", type=int, default=0, help="tuner budget: timed points, in cost-model order (0 = all)")
+    ap.add_argument("--tuner-log", default="", metavar="PATH",
+                    help="write the tuner's evaluated points (time, prediction, best so far) to this JSON file")
     ap.add_argument("--cpu-rows", type=int, default=4096, help="rows of the product the oracle is timed on")
     ap.add_argument("--pin", default="", help="bm,bn,bk,wm,wn,vec,raster,sched[,split_k[,split_tail]]: pin this tile config instead of tuning")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
@@ -252,14 +296,14 @@ def main() -> int:
     if not args.no_tune:
         tsg.search_set(args.evals, True)
         best, best_ms, recs = tune()
-        tuner_log = [dict(r.config.as_dict(), ms=round(r.ms, 5), predicted_ms=round(r.predicted_ms, 5)) for r in recs]
+        tuner_log = [dict(r.config.as_dict(), ms=round(r.ms, 5), predicted_ms=round(r.predicted_ms, 5),
+                          best_so_far_ms=round(r.best_ms, 5)) for r in recs]
         timed = [r for r in recs if r.ms >= 0]
         # the first timed point is the cost model's pick, i.e. what a call without tuning uses
         # how many points, in the cost model's order, it took to get within 1 % of the final best
         reach = next(i + 1 for i, r in enumerate(timed) if r.best_ms <= best_ms * 1.01)
         search = {"evaluations": len(timed), "default_ms": timed[0].ms, "best_ms": best_ms,
-                  "speedup_vs_default": timed[0].ms / best_ms, "evaluations_to_within_1pct": reach,
-                  "best_so_far_ms": [round(r.best_ms, 5) for r in timed]}
+                  "speedup_vs_default": timed[0].ms / best_ms, "evaluations_to_within_1pct": reach}
         for r in recs:
             log("  tuner: %s -> %.4f ms (best so far %.4f)" % (r.config, r.ms, r.best_ms))
         log("tuner picked %s at %.4f ms" % (best, best_ms))
@@ -365,26 +409,15 @@ def main() -> int:
         log("cpu oracle: %s in %.2f s on %d threads = %.4f %s" % (cpu["sample"], dtc, cpu["cores"], cpu["value"],
                                                                   cpu["unit"]))
 
-    out = {
-        "metric": METRIC if k == 3 else ("GB/s and % of MI355X HBM peak, " if hbm_bound else
-                                         "TFLOP/s and % of MI355X matrix peak, ") + describe(k, c),
-        "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": c["dtype"], "data": "synthetic",
-        "pct_of_peak": 100.0 * value / peak,
-        "config": {"workload": describe(k, c), "M": M, "N": N, "K": K, "flops_per_step": flops,
-                   "tile_config": None if hbm_bound else li.config.as_dict(),
-                   "alternative": None if hbm_bound else int(li.alternative), "tuned": not args.no_tune,
-                   "hip_graph": bool(args.graph)},
-        "roofline": {"bound": "hbm" if hbm_bound else "mfma", "achieved": achieved, "peak": peak, "unit": unit,
-                     "frac": achieved / peak,
-                     "traffic": traffic_bytes(k, c["dtype"], {} if hbm_bound else li.config.as_dict(), c["op"]),
-                     "kernel_ms_avg": avg_kern_ms, "kernel_hash": kernel_hash(c["dtype"], c["op"])},
-        "cpu_baseline": cpu,
-    }
-    if tuner_log is not None:
-        out["search"] = search
-        out["tuner_log"] = tuner_log
+    out = result_record(k, c, (M, N, K), args.steps, args.warmup, wall, avg_kern_ms,
+                        None if hbm_bound else li.config.as_dict(), None if hbm_bound else int(li.alternative),
+                        not args.no_tune, bool(args.graph), cpu, search)
+    if tuner_log is not None and args.tuner_log:
+        # the evaluated points with the best-so-far time after each (the curve of Fig. 11)
+        with open(args.tuner_log, "w") as fh:
+            json.dump({"workload": describe(k, c), "points": tuner_log}, fh)
+        log("tuner log: %d points written to %s" % (len(tuner_log), args.tuner_log))
+    sys.stderr.flush()
     print(json.dumps(out), flush=True)
     return 0
 

@@ -219,3 +219,18 @@ def errors(C, ref, S):
     if (~nz).any() and d[~nz].max() != 0:
         comp = float("inf")
     return normwise, comp
+
+
+def elementwise_relative(C, ref, floor: float = 1e-3) -> float:
+    """Plain element-wise relative error max |C-ref|_ij / |ref|_ij, restricted to the entries
+    with |ref|_ij >= floor * max|ref| (a sum that cancels to almost nothing has no meaningful
+    relative error).  Reported next to the two gated figures of `errors`; 0.0 when no entry
+    qualifies."""
+    C = np.asarray(C, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    mag = np.abs(ref)
+    mx = float(mag.max()) if mag.size else 0.0
+    keep = mag >= floor * mx
+    if mx == 0.0 or not keep.any():
+        return 0.0
+    return float((np.abs(C - ref)[keep] / mag[keep]).max())

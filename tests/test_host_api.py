@@ -323,12 +323,13 @@ def test_bench_counts_and_traffic_lookup(monkeypatch):
         for e in entries:
             dtype, op = C[k]["dtype"], C[k]["op"]
             monkeypatch.setattr(bench, "kernel_hash", lambda d, o="", h=e["kernel_hash"]: h)
-            assert bench.traffic_bytes(k, dtype, dict(e["tile"]), op) == e["bytes"]
+            assert bench.traffic_bytes(k, dtype, dict(e["tile"]), op) == (e["bytes"], e["source"])
+            assert os.path.exists(os.path.join(os.path.dirname(bench.__file__), e["source"]))
             if e["tile"]:
                 other = dict(e["tile"], bk=e["tile"]["bk"] * 2)
-                assert bench.traffic_bytes(k, dtype, other, op) in (None, *[x["bytes"] for x in entries if x is not e])
+                assert bench.traffic_bytes(k, dtype, other, op)[0] in (None, *[x["bytes"] for x in entries if x is not e])
             monkeypatch.setattr(bench, "kernel_hash", lambda d, o="": "changed")
-            assert bench.traffic_bytes(k, dtype, dict(e["tile"]), op) is None
+            assert bench.traffic_bytes(k, dtype, dict(e["tile"]), op) == (None, None)
     monkeypatch.undo()
     assert len(bench.kernel_hash("f32")) == 16 and bench.kernel_hash("f32") != bench.kernel_hash("bf16")
     r = subprocess.run([sys.executable, bench.__file__, "--gpus", "2"], capture_output=True, text=True)

@@ -395,3 +395,46 @@ def test_transposed_right_operand_pins():
     want = [[sum(Fraction(int(a[i, k])) * Fraction(int(b[j, k])) for k in range(2)) for j in range(2)] for i in range(2)]
     got = oracle.gemm(a, b, trans_b=True, with_s=False)
     assert all(Fraction(got[i, j]) == want[i][j] for i in range(2) for j in range(2))
+
+
+def test_conv_bf16_branch_reads_the_exact_bf16_values():
+    """The convolution oracle on bfloat16 bit patterns: (i) equal, bit for bit, to the fp32
+    branch fed the same values widened to fp32 (R and S); (ii) one geometry with stride,
+    asymmetric padding and a ragged filter against literal loops in exact rationals over the
+    widened values; (iii) a value that only exists in bf16 form (0x3F81 = 1 + 2^-7) summed in
+    closed form, which a branch that read the bits as integers, as halves or as fp32 words
+    would miss."""
+    x, w = synth.conv_inputs(2, 5, 4, 3, 2, 3, 2, seed=29)
+    xb, wb = synth.f32_to_bf16_bits(x), synth.f32_to_bf16_bits(w)
+    xf, wf = synth.bf16_bits_to_f32(xb), synth.bf16_bits_to_f32(wb)
+    assert not np.array_equal(xf, x)          # rounding did change the inputs
+    R16, S16 = oracle.conv2d_nhwc(xb, wb, stride=(2, 1), pad=(1, 0))
+    R32, S32 = oracle.conv2d_nhwc(xf, wf, stride=(2, 1), pad=(1, 0))
+    assert np.array_equal(R16, R32) and np.array_equal(S16, S32)
+    ref = _conv_brute(xf, wf, (2, 1), (1, 0))
+    N, Ho, Wo, Cout = R16.shape
+    for n in range(N):
+        for ho in range(Ho):
+            for wo in range(Wo):
+                for co in range(Cout):
+                    exact = ref[n][ho][wo][co]
+                    assert abs(Fraction(R16[n, ho, wo, co]) - exact) <= Fraction(S16[n, ho, wo, co]) * Fraction(1, 2 ** 48)
+    xb1 = np.full((1, 4, 4, 8), 0x3F81, np.uint16)    # 1 + 2^-7
+    wb1 = np.full((3, 3, 8, 2), 0x4000, np.uint16)    # 2.0
+    R = oracle.conv2d_nhwc(xb1, wb1, pad=(1, 1), with_s=False)
+    v = 2.0 * (1.0 + 2.0 ** -7) * 8
+    assert np.all(R[0, 0, 0] == 4 * v) and np.all(R[0, 0, 1] == 6 * v) and np.all(R[0, 1, 1] == 9 * v)
+    with pytest.raises(TypeError):
+        oracle.conv2d_nhwc(xb, w)             # mixed element types are refused
+
+
+def test_elementwise_relative_error_definition():
+    """max |C-ref| / |ref| over the entries whose reference is at least `floor` of the largest."""
+    ref = np.array([[100.0, -50.0], [0.05, 2.0]])
+    C = ref + np.array([[0.1, 0.1], [0.04, 0.01]])
+    # floor 1e-3 * 100 = 0.1: the 0.05 entry (relative error 0.8) is left out
+    assert abs(oracle.elementwise_relative(C, ref) - 0.005) < 1e-15
+    # with a lower floor it is the maximum
+    assert abs(oracle.elementwise_relative(C, ref, floor=1e-4) - 0.8) < 1e-12
+    assert oracle.elementwise_relative(ref, ref) == 0.0
+    assert oracle.elementwise_relative(np.zeros((2, 2)), np.zeros((2, 2))) == 0.0
