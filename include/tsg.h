@@ -33,17 +33,24 @@
  *    definite.  Without TSG_STRICT a compute call walks its own chain of
  *    alternatives (the config pinned by the caller, else the tuner's result for
  *    this very problem -> the library's default for the shape -> that tile with
- *    scalar accesses) and only fails definitely.
+ *    scalar accesses) and only fails definitely: the last alternative has no
+ *    precondition beyond valid arguments.  With TSG_STRICT the call takes the first
+ *    alternative only -- the pinned config; with no pin, the tuner's remembered
+ *    result for this problem; with neither, the library's default -- and returns
+ *    TSG_E_SILENCEABLE if its preconditions fail.
  *  - Operands are fetched in 16-byte accesses from any element-aligned address.  An access
  *    that starts inside a row may run past the row's end (by less than 16 bytes) into the following
  *    row of the same operand (ld >= row length keeps that inside the operand); the last
  *    row of an operand is never read past its end, and nothing outside
  *    [base, base + (rows - 1) * ld + row length) is touched.
  *  - Extents must fit in int32 (each of M, N, K, and every tensor's element count
- *    for convolution); larger values are TSG_E_INVALID.
- *  - The config registry, the tuner's results and the workspace pointer are guarded
- *    by a mutex; compute calls are re-entrant, except that calls which use the
- *    workspace must be ordered on one stream.
+ *    for convolution), batch <= 65535 and ceil(M/64) * ceil(N/64) <= 2^26; operand
+ *    pointers must be aligned to their element type.  Anything else is TSG_E_INVALID.
+ *  - The config registry, the tuner's results and the workspace table are guarded
+ *    by a mutex; compute calls are re-entrant.  Calls that share one workspace
+ *    buffer must be ordered on one stream; calls on different streams may split k
+ *    at the same time if each stream has a buffer of its own
+ *    (tsg_workspace_set_stream).
  */
 #ifndef TSG_H
 #define TSG_H
@@ -72,7 +79,7 @@ typedef enum { TSG_OP_GEMM = 0, TSG_OP_GEMM_TRANSA = 1, TSG_OP_CONV2D_NHWC = 2 }
 enum {
     TSG_NEGATE = 1u,     /* C = -(op(A).B): the negate sunk into the epilogue (Case Study 3) */
     TSG_ACCUMULATE = 2u, /* C += ... : the `+=` of Fig. 7; without it C is overwritten */
-    TSG_STRICT = 4u      /* use exactly the config set by tsg_tile_config_set or fail silenceably */
+    TSG_STRICT = 4u      /* first alternative only (pin, else tuned result, else default) or fail silenceably */
 };
 
 /*
@@ -240,11 +247,19 @@ tsg_status tsg_tile_config_get(tsg_op op, tsg_dtype dtype, int64_t M, int64_t N,
 /* Workspace for split_k > 1: `ws` is a DEVICE buffer of `bytes` bytes, 256-byte aligned,
  * owned by the caller, who keeps it alive and unused by anything else until it is replaced
  * or cleared with (NULL, 0).  The library keeps arrival counters in its first 64 KiB (this
- * call zeroes them, synchronously) and partial tiles after that.  Compute calls that use
+ * call zeroes them, synchronously; the kernels leave them at zero; the last one is the full
+ * reduce's, so a GEMM and a reduce may follow each other on one buffer) and partial tiles
+ * after that.  Compute calls that use
  * the workspace must be ordered on one stream: two of them in flight at once race.
  * Without a workspace (or with one that is too small for a config) split_k > 1 is a
  * silenceable failure and the chain of alternatives continues with split_k = 1. */
 tsg_status tsg_workspace_set(void *ws, int64_t bytes);
+
+/* The same for the calls made on one stream only: a compute call on `stream` (the handle it
+ * is given, NULL = the default stream) uses this buffer in place of the process-wide one, so
+ * calls on different streams, each with its own buffer, may split k concurrently.  (NULL, 0)
+ * removes the stream's entry.  Same requirements and return codes as tsg_workspace_set. */
+tsg_status tsg_workspace_set_stream(void *stream, void *ws, int64_t bytes);
 
 /* Bytes of workspace a call with this batch, M, N and config needs (0 when split_k is 1);
  * -1 for malformed arguments or a tile that is not instantiated. */
@@ -258,7 +273,10 @@ tsg_status tsg_last_launch(tsg_launch_info *out);
 
 /* off[m*KH*KW + kh*KW + kw] = element offset of x[n][hi][wi][0] for output pixel
  * m = (n*Ho + ho)*Wo + wo, hi = ho*stride_h + kh - pad_h, wi likewise; -1 where the
- * tap falls in the zero padding.  `off` is a HOST array of N*Ho*Wo*KH*KW int32. */
+ * tap falls in the zero padding.  `off` is a HOST array of N*Ho*Wo*KH*KW int32.
+ * This is the map the lowering is DEFINED by, evaluated on the host; the kernels' own
+ * gather is not exported (it runs on the device) and is held to this map through results:
+ * on integer-valued data a wrong offset or mask changes C, which must match bit for bit. */
 tsg_status tsg_conv2d_index_map(int64_t N, int64_t H, int64_t W, int64_t Cin,
                                 int64_t KH, int64_t KW, int64_t stride_h, int64_t stride_w,
                                 int64_t pad_h, int64_t pad_w, int32_t *off);

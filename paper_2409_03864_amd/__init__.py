@@ -74,6 +74,7 @@ def _load():
         "tsg_tile_config_get": [i32, i32, i64, i64, i64, cfgp],
         "tsg_last_launch": [ctypes.POINTER(LaunchInfo)],
         "tsg_workspace_set": [vp, i64],
+        "tsg_workspace_set_stream": [vp, vp, i64],
         "tsg_search_set": [i32, i32],
         "tsg_tune_cache_clear": [],
         "tsg_tune_cache_save": [ctypes.c_char_p],
@@ -116,7 +117,7 @@ EXPORTS = ("tsg_gemm", "tsg_gemm_transA", "tsg_gemm_batched", "tsg_gemm_trans", 
            "tsg_reduce_sum", "tsg_split",
            "tsg_tile_config_count", "tsg_tile_config_enum", "tsg_tile_config_check",
            "tsg_tile_config_set", "tsg_tile_config_get", "tsg_last_launch", "tsg_workspace_set",
-           "tsg_workspace_bytes", "tsg_search_set", "tsg_tune_cache_size", "tsg_tune_cache_clear",
+           "tsg_workspace_set_stream", "tsg_workspace_bytes", "tsg_search_set", "tsg_tune_cache_size", "tsg_tune_cache_clear",
            "tsg_tune_cache_save", "tsg_tune_cache_load", "tsg_conv2d_index_map",
            "tsg_gemm_index_map", "tsg_autotune_gemm", "tsg_autotune_gemm_batched", "tsg_autotune_conv2d_nhwc",
            "tsg_status_string", "tsg_version")
@@ -242,6 +243,17 @@ def workspace_set(ws, nbytes=None):
     if nbytes is None:
         nbytes = ws.numel() * ws.element_size()
     _check(_lib.tsg_workspace_set(_ptr(ws), nbytes), "tsg_workspace_set")
+
+
+def workspace_set_stream(stream, ws, nbytes=None):
+    """The same for the calls made on one stream (a torch stream or a raw handle; None = the
+    current stream): ws None removes the stream's entry."""
+    if ws is None:
+        _check(_lib.tsg_workspace_set_stream(_stream(stream), None, 0), "tsg_workspace_set_stream")
+        return
+    if nbytes is None:
+        nbytes = ws.numel() * ws.element_size()
+    _check(_lib.tsg_workspace_set_stream(_stream(stream), _ptr(ws), nbytes), "tsg_workspace_set_stream")
 
 
 def workspace_bytes(dtype, batch, M, N, cfg) -> int:

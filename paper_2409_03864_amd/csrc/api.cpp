@@ -37,6 +37,10 @@ struct Problem {
     // output window strides (elements); y_window = 0: y is a plain [N*Ho*Wo][Cout] matrix
     int y_window = 0;
     int64_t y_sn = 0, y_sh = 0, y_sw = 0;
+    // scratch for split k, resolved when the call enters the library: the buffer registered for
+    // the call's stream, else the process-wide one (none: split k is not available)
+    void* ws = nullptr;
+    int64_t ws_bytes = 0;
 };
 
 std::mutex g_mu;
@@ -50,14 +54,29 @@ using TuneKey = std::array<int64_t, 8>;
 struct TuneVal { tsg_tile_config cfg; float ms; };
 std::map<TuneKey, TuneVal> g_tuned;
 
-// Caller-owned workspace for split k: arrival counters first, partial tiles after them.
-constexpr int64_t kMaxSlots = 16384;                       // (batch x tile) counters
+// Caller-owned workspace for split k: arrival counters first, partial tiles after them.  The
+// last counter belongs to the full reduce, the others to the (batch x tile) slots of a GEMM.
+constexpr int64_t kMaxSlots = tsg::kWorkspaceReduceSlot;
 constexpr int64_t kCounterBytes = tsg::kWorkspaceCounterBytes;
-static_assert(kCounterBytes == kMaxSlots * 4, "one counter per slot");
+static_assert(kCounterBytes == (kMaxSlots + 1) * 4, "one counter per slot, and the reduce's");
 constexpr int kMaxSplit = 16;
+constexpr int64_t kMaxBatch = 65535;                       // the batch index is the grid's y dimension
+constexpr int64_t kMaxTiles = (int64_t)1 << 26;            // 64 x 64 tiles of C (x 16 splits fits the grid's x)
 void* g_ws = nullptr;
 int64_t g_ws_bytes = 0;
+// workspaces registered for one stream each (tsg_workspace_set_stream): calls on different
+// streams then split k at the same time without sharing scratch
+struct StreamWs { void* ws; int64_t bytes; };
+std::map<void*, StreamWs> g_stream_ws;
 thread_local tsg_launch_info t_last;
+
+void resolve_workspace(void* stream, void** ws, int64_t* bytes) {
+    std::lock_guard<std::mutex> g(g_mu);
+    const auto it = g_stream_ws.find(stream);
+    if (it != g_stream_ws.end()) { *ws = it->second.ws; *bytes = it->second.bytes; return; }
+    *ws = g_ws;
+    *bytes = g_ws ? g_ws_bytes : 0;
+}
 
 const KernelEntry* kernels(tsg_dtype dt, int* n) {
     return dt == TSG_F32 ? tsg::f32_kernels(n) : tsg::bf16_kernels(n);
@@ -217,8 +236,6 @@ tsg_tile_config fill_defaults(tsg_tile_config c, const tsg_tile_config& def) {
 bool vec_legal(const Problem& p, int vec) {
     if (vec == 1) return true;
     if (vec != vec_max(p.dtype)) return false;
-    const uintptr_t es = (uintptr_t)elem_size(p.dtype);
-    if (reinterpret_cast<uintptr_t>(p.A) % es || reinterpret_cast<uintptr_t>(p.B) % es) return false;
     if (p.op == TSG_OP_CONV2D_NHWC) return p.Cin % vec == 0;
     return true;
 }
@@ -252,7 +269,6 @@ tsg_status make_plan(const Problem& p, const tsg_tile_config& cfg, int alternati
     tsg_split(p.N, e->bn, &n_main, &n_rest, &t);
     tsg_split(p.K, e->bk, &k_main, &k_rest, &t);
     const int64_t tiles_m = (p.M + e->bm - 1) / e->bm, tiles_n = (p.N + e->bn - 1) / e->bn;
-    if (tiles_m * tiles_n * cfg.split_k > 0x7fffffff / 2 || p.batch > 65535) return TSG_E_SILENCEABLE;
     void* ws = nullptr;
     const int64_t n_split = split_tiles(tiles_m * tiles_n, cfg.split_k, cfg.split_tail);
     if (cfg.split_k > 1) {
@@ -261,10 +277,9 @@ tsg_status make_plan(const Problem& p, const tsg_tile_config& cfg, int alternati
         if (cfg.split_k > (p.K + e->bk - 1) / e->bk) return TSG_E_SILENCEABLE;
         if (n_split == 0) return TSG_E_SILENCEABLE;
         if (p.batch * n_split > kMaxSlots) return TSG_E_SILENCEABLE;
-        std::lock_guard<std::mutex> g(g_mu);
-        if (!g_ws || ws_bytes_needed(*e, p.batch, p.M, p.N, cfg.split_k, cfg.split_tail) > g_ws_bytes)
+        if (!p.ws || ws_bytes_needed(*e, p.batch, p.M, p.N, cfg.split_k, cfg.split_tail) > p.ws_bytes)
             return TSG_E_SILENCEABLE;
-        ws = g_ws;
+        ws = p.ws;
     }
 
     const bool edge = m_rest || n_rest || k_rest;
@@ -342,7 +357,7 @@ tsg_tile_config heuristic_cached(tsg_dtype dt, int64_t batch, int64_t M, int64_t
 tsg_status run(const Problem& p, hipStream_t s) {
     bool pinned;
     tsg_tile_config pin;
-    int64_t ws_bytes;
+    const int64_t ws_bytes = p.ws ? p.ws_bytes : 0;
     {
         std::lock_guard<std::mutex> g(g_mu);
         pinned = g_pinned[p.op][p.dtype];
@@ -351,7 +366,6 @@ tsg_status run(const Problem& p, hipStream_t s) {
             const auto it = g_tuned.find(tune_key(p));
             if (it != g_tuned.end()) { pinned = true; pin = it->second.cfg; }
         }
-        ws_bytes = g_ws ? g_ws_bytes : 0;
     }
     Plan pl;
     if (pinned) {
@@ -360,7 +374,10 @@ tsg_status run(const Problem& p, hipStream_t s) {
     }
     const tsg_tile_config heur = heuristic_cached(p.dtype, p.batch, p.M, p.N, p.K, ws_bytes, p.trans_b);
     if (make_plan(p, heur, 1, &pl) == TSG_OK) return enqueue(p, pl, s);
-    if ((p.flags & TSG_STRICT) || p.trans_b) return TSG_E_SILENCEABLE;   // no scalar form with a transposed B
+    if (p.flags & TSG_STRICT) return TSG_E_SILENCEABLE;
+    // (a valid problem always passes the default's preconditions when B is stored transposed:
+    // those forms have no scalar variant to fall back to)
+    if (p.trans_b) return TSG_E_INVALID;
     // last alternative: scalar accesses, which have no precondition.  The direct-to-LDS forms
     // have no scalar variant, so the same tile is taken in a register-staged form (or, if
     // that one is not instantiated, the smallest tile of the table).
@@ -376,12 +393,12 @@ tsg_status run(const Problem& p, hipStream_t s) {
             int pick = -1;
             for (int i = 0; i < n; ++i)
                 if (t[i].sched < 4 && (pick < 0 || t[i].bm * t[i].bn < t[pick].bm * t[pick].bn)) pick = i;
-            if (pick < 0) return TSG_E_SILENCEABLE;
+            if (pick < 0) return TSG_E_INVALID;
             scalar = config_of(t[pick], 1, heur.raster, 1);
         }
     }
     if (make_plan(p, scalar, 2, &pl) == TSG_OK) return enqueue(p, pl, s);
-    return TSG_E_SILENCEABLE;
+    return TSG_E_INVALID;   // unreachable for arguments that passed validation: the scalar form has no precondition
 }
 
 bool fits_i32(int64_t v) { return v >= 0 && v <= 0x7fffffff; }
@@ -393,6 +410,11 @@ tsg_status check_gemm(int dtype, int64_t batch, int64_t M, int64_t N, int64_t K,
     if (!A || !B || !C) return TSG_E_INVALID;
     if (M <= 0 || N <= 0 || K <= 0 || batch <= 0) return TSG_E_INVALID;
     if (!fits_i32(M) || !fits_i32(N) || !fits_i32(K)) return TSG_E_INVALID;
+    if (batch > kMaxBatch || ((M + 63) / 64) * ((N + 63) / 64) > kMaxTiles) return TSG_E_INVALID;
+    const uintptr_t es = dtype == TSG_F32 ? 4 : 2;
+    if (reinterpret_cast<uintptr_t>(A) % es || reinterpret_cast<uintptr_t>(B) % es ||
+        reinterpret_cast<uintptr_t>(C) % 4)
+        return TSG_E_INVALID;   // operands are arrays of their element type
     if (lda < (trans_a ? M : K) || ldb < (trans_b ? K : N) || ldc < N) return TSG_E_INVALID;
     if (flags & ~(uint32_t)(TSG_NEGATE | TSG_ACCUMULATE | TSG_STRICT)) return TSG_E_INVALID;
     return TSG_OK;
@@ -412,6 +434,11 @@ tsg_status conv_problem(int dtype, int64_t N, int64_t H, int64_t W, int64_t Cin,
     if (N > lim / Ho || N * Ho > lim / Wo || N * Ho * Wo > lim / Cout) return TSG_E_INVALID;
     if (KH > lim / KW || KH * KW > lim / Cin || KH * KW * Cin > lim / Cout) return TSG_E_INVALID;
     if (ph > (1 << 20) || pw > (1 << 20) || sh > (1 << 20) || sw > (1 << 20)) return TSG_E_INVALID;
+    if (((N * Ho * Wo + 63) / 64) * ((Cout + 63) / 64) > kMaxTiles) return TSG_E_INVALID;
+    const uintptr_t es = dtype == TSG_F32 ? 4 : 2;
+    if (reinterpret_cast<uintptr_t>(x) % es || reinterpret_cast<uintptr_t>(w) % es ||
+        reinterpret_cast<uintptr_t>(y) % 4)
+        return TSG_E_INVALID;
     p->op = TSG_OP_CONV2D_NHWC;
     p->dtype = (tsg_dtype)dtype;
     p->M = N * Ho * Wo; p->N = Cout; p->K = KH * KW * Cin;
@@ -548,11 +575,11 @@ tsg_status autotune(Problem p, hipStream_t s, int iters, tsg_tile_config* best, 
 
 }  // namespace
 
-bool tsg::workspace_get(void** ws, long long* bytes) {
-    std::lock_guard<std::mutex> g(g_mu);
-    *ws = g_ws;
-    *bytes = g_ws_bytes;
-    return g_ws != nullptr;
+bool tsg::workspace_get(void* stream, void** ws, long long* bytes) {
+    int64_t b = 0;
+    resolve_workspace(stream, ws, &b);
+    *bytes = b;
+    return *ws != nullptr;
 }
 
 extern "C" {
@@ -595,6 +622,7 @@ tsg_status tsg_gemm_trans(tsg_dtype dtype, int32_t trans_a, int32_t trans_b, int
     p.stride_a = stride_a; p.stride_b = stride_b; p.stride_c = stride_c;
     p.trans_b = trans_b != 0;
     p.flags = flags;
+    resolve_workspace(stream, &p.ws, &p.ws_bytes);
     return run(p, (hipStream_t)stream);
 }
 
@@ -623,6 +651,7 @@ tsg_status tsg_conv2d_nhwc(tsg_dtype dtype, int64_t N, int64_t H, int64_t W, int
     const tsg_status v = conv_problem(dtype, N, H, W, Cin, Cout, KH, KW, stride_h, stride_w, pad_h, pad_w, x, w, y,
                                       flags, &p);
     if (v != TSG_OK) return v;
+    resolve_workspace(stream, &p.ws, &p.ws_bytes);
     return run(p, (hipStream_t)stream);
 }
 
@@ -641,6 +670,7 @@ tsg_status tsg_conv2d_nhwc_window(tsg_dtype dtype, int64_t N, int64_t H, int64_t
     if (y_stride_n > (int64_t)0x7fffffff * 64) return TSG_E_INVALID;
     p.y_window = 1;
     p.y_sn = y_stride_n; p.y_sh = y_stride_h; p.y_sw = y_stride_w;
+    resolve_workspace(stream, &p.ws, &p.ws_bytes);
     return run(p, (hipStream_t)stream);
 }
 
@@ -723,6 +753,16 @@ tsg_status tsg_workspace_set(void* ws, int64_t bytes) {
     std::lock_guard<std::mutex> g(g_mu);
     g_ws = ws;
     g_ws_bytes = bytes;
+    return TSG_OK;
+}
+
+tsg_status tsg_workspace_set_stream(void* stream, void* ws, int64_t bytes) {
+    if ((ws == nullptr) != (bytes == 0) || bytes < 0) return TSG_E_INVALID;
+    if (ws && (bytes <= kCounterBytes || (reinterpret_cast<uintptr_t>(ws) & 255u))) return TSG_E_INVALID;
+    if (ws && hipMemset(ws, 0, kCounterBytes) != hipSuccess) return TSG_E_RUNTIME;   // counters start at zero
+    std::lock_guard<std::mutex> g(g_mu);
+    if (ws) g_stream_ws[stream] = StreamWs{ws, bytes};
+    else g_stream_ws.erase(stream);
     return TSG_OK;
 }
 
@@ -855,6 +895,7 @@ tsg_status tsg_autotune_gemm_trans(tsg_dtype dtype, int32_t trans_a, int32_t tra
     p.lda = lda; p.ldb = ldb; p.ldc = ldc;
     p.stride_a = stride_a; p.stride_b = stride_b; p.stride_c = stride_c;
     p.flags = flags;
+    resolve_workspace(stream, &p.ws, &p.ws_bytes);
     return autotune(p, (hipStream_t)stream, iters, best, best_ms, log, log_cap, n_log);
 }
 
@@ -884,6 +925,7 @@ tsg_status tsg_autotune_conv2d_nhwc(tsg_dtype dtype, int64_t N, int64_t H, int64
     const tsg_status v = conv_problem(dtype, N, H, W, Cin, Cout, KH, KW, stride_h, stride_w, pad_h, pad_w, x, w, y,
                                       flags, &p);
     if (v != TSG_OK) return v;
+    resolve_workspace(stream, &p.ws, &p.ws_bytes);
     return autotune(p, (hipStream_t)stream, iters, best, best_ms, log, log_cap, n_log);
 }
 

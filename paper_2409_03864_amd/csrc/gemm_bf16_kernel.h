@@ -10,6 +10,7 @@
 // group at row k0 + s/4, columns j0 + 4*(s%4) .. +3 therefore hands lane l the four
 // values B[k0 .. k0+3][j0 + l]: no transposition in registers or on the store side.
 #pragma once
+#include <atomic>
 #include <type_traits>
 
 #include "tsg_internal.h"
@@ -131,7 +132,8 @@ __device__ __forceinline__ void finish_tile(const KArgs& p, f32x16 (&acc)[T::MI]
 #pragma unroll
                     for (int r = 0; r < 16; ++r) acc[i][j][r] = sp == 0 ? t[j][r] : acc[i][j][r] + t[j][r];
             }
-        if (tid == 0) p.counters[slot] = 0;   // ready for the next launch on this workspace
+        if (tid == 0)   // ready for the next launch on this workspace
+            __hip_atomic_store(p.counters + slot, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 
     // With ACCUMULATE the old values of a block are all loaded before its first store: a load
@@ -1004,12 +1006,12 @@ hipError_t launch_mode(int variant, const KArgs& a, int batch, hipStream_t s) {
             default: fn = gemm_bf16_kernel<T, AMODE, 1, true>; break;
         }
     }
-    static bool attr_done[8] = {false, false, false, false, false, false, false, false};   // per kernel function
+    static std::atomic<bool> attr_done[8];   // per kernel function; setting the attribute twice is harmless
     const int fi = variant + 4 * one_tap;
-    if (bytes > 48 * 1024 && !attr_done[fi]) {
+    if (bytes > 48 * 1024 && !attr_done[fi].load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
         if (e != hipSuccess) return e;
-        attr_done[fi] = true;
+        attr_done[fi].store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL(fn, grid, block, bytes, s, a);
     return hipGetLastError();

@@ -21,6 +21,7 @@
 // arrival counter; the workgroup that arrives last adds the S partials in split order (so
 // the sum does not depend on who was last), applies the epilogue and resets the counter.
 #pragma once
+#include <atomic>
 #include <type_traits>
 
 #include "tsg_internal.h"
@@ -163,7 +164,8 @@ __device__ __forceinline__ void finish_tile(const KArgs& p, f32x16 (&acc)[T::MI]
 #pragma unroll
                     for (int r = 0; r < 16; ++r) acc[i][j][r] = sp == 0 ? t[j][r] : acc[i][j][r] + t[j][r];
             }
-        if (tid == 0) p.counters[slot] = 0;   // ready for the next launch on this workspace
+        if (tid == 0)   // ready for the next launch on this workspace
+            __hip_atomic_store(p.counters + slot, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 
     // With ACCUMULATE the old values of a block are all loaded before its first store: a load
@@ -1140,12 +1142,12 @@ hipError_t launch_mode(int variant, const KArgs& a, int batch, hipStream_t s) {
             default: fn = gemm_f32_kernel<T, AMODE, 1, true>; break;
         }
     }
-    static bool attr_done[8] = {false, false, false, false, false, false, false, false};   // per kernel function
+    static std::atomic<bool> attr_done[8];   // per kernel function; setting the attribute twice is harmless
     const int fi = variant + 4 * one_tap;
-    if (bytes > 48 * 1024 && !attr_done[fi]) {
+    if (bytes > 48 * 1024 && !attr_done[fi].load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
         if (e != hipSuccess) return e;
-        attr_done[fi] = true;
+        attr_done[fi].store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL(fn, grid, block, bytes, s, a);
     return hipGetLastError();

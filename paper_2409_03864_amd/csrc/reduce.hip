@@ -105,7 +105,7 @@ __global__ void __launch_bounds__(kThreads) reduce_sum_kernel(const void* __rest
         for (int i = tid; i < G; i += kThreads)
             t += __hip_atomic_load(partials + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         s = block_sum(t);
-        if (tid == 0) *counter = 0;
+        if (tid == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     if (tid == 0) {
         if (flags & TSG_NEGATE) s = -s;
@@ -131,14 +131,16 @@ extern "C" tsg_status tsg_reduce_sum(tsg_dtype dtype, int64_t rows, int64_t cols
     groups = groups < 1 ? 1 : groups > tsg::kMaxGroups ? tsg::kMaxGroups : groups;
     void* ws = nullptr;
     int64_t ws_bytes = 0;
-    long long wsb = 0; tsg::workspace_get(&ws, &wsb); ws_bytes = wsb;
+    long long wsb = 0;
+    tsg::workspace_get(stream, &ws, &wsb);
+    ws_bytes = wsb;
     if (groups > 1 && (!ws || ws_bytes < tsg::kWorkspaceCounterBytes + groups * 4)) {
         // more than one workgroup needs the workspace for its partial sums
         if (flags & TSG_STRICT) return TSG_E_SILENCEABLE;
         groups = 1;
     }
     float* partials = ws ? (float*)((char*)ws + tsg::kWorkspaceCounterBytes) : nullptr;
-    int* counter = (int*)ws;
+    int* counter = ws ? (int*)ws + tsg::kWorkspaceReduceSlot : nullptr;   // its own slot: a GEMM may share the buffer
     const unsigned f = flags & (TSG_NEGATE | TSG_ACCUMULATE);
     if (dtype == TSG_F32)
         hipLaunchKernelGGL(tsg::reduce_sum_kernel<false>, dim3((unsigned)groups), dim3(tsg::kThreads), 0,

@@ -59,10 +59,13 @@ struct KernelEntry {
     hipError_t (*launch)(int tile, int amode, int variant, const KArgs& a, int batch, hipStream_t s);
 };
 
-// The caller's workspace (tsg_workspace_set): arrival counters in the first
-// kWorkspaceCounterBytes, partial results after them.  Returns false if none is set.
+// The caller's workspace (tsg_workspace_set, tsg_workspace_set_stream): arrival counters in the
+// first kWorkspaceCounterBytes, partial results after them.  The GEMM kernels count arrivals in
+// slots [0, kWorkspaceReduceSlot), the full reduce in slot kWorkspaceReduceSlot.  workspace_get
+// returns the buffer a call on `stream` uses, false if there is none.
 constexpr long long kWorkspaceCounterBytes = 16384 * 4;
-bool workspace_get(void** ws, long long* bytes);
+constexpr long long kWorkspaceReduceSlot = 16383;
+bool workspace_get(void* stream, void** ws, long long* bytes);
 
 const KernelEntry* f32_kernels(int* count);
 const KernelEntry* bf16_kernels(int* count);

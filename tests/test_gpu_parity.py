@@ -266,6 +266,66 @@ def test_split_k_batched_paper_loop_nest(workspace):
         assert nw <= TOL[dt] and cw <= TOL[dt], (i, nw, cw)
 
 
+def test_two_streams_split_k_concurrently_with_their_own_workspaces():
+    """Each stream has a workspace of its own (tsg_workspace_set_stream), so two products that
+    split k may be in flight at once.  Long k, few tiles: both launches are resident together.
+    Integer data: each result must equal the oracle bit for bit, many times over."""
+    dt = tsg.F32
+    M, N, K = 192, 128, 8192
+    cfg = tsg.TileConfig(bm=64, bn=64, bk=32, wm=32, wn=32, vec=4, raster=0, sched=4, split_k=8, split_tail=0)
+    tsg.tile_config_set(tsg.OP_GEMM, dt, cfg)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    w1 = torch.empty(8 << 20, dtype=torch.uint8, device=DEV)
+    w2 = torch.empty(8 << 20, dtype=torch.uint8, device=DEV)
+    tsg.workspace_set_stream(s1, w1)
+    tsg.workspace_set_stream(s2, w2)
+    try:
+        A1, B1 = synth.gemm_inputs(M, N, K, seed=41, dist="ints")
+        A2, B2 = synth.gemm_inputs(M, N, K, seed=42, dist="ints")
+        dA1, dB1, dA2, dB2 = dev(A1), dev(B1), dev(A2), dev(B2)
+        C1 = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+        C2 = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+        R1 = oracle.gemm(A1, B1, with_s=False)
+        R2 = oracle.gemm(A2, B2, with_s=False)
+        torch.cuda.synchronize()
+        for rep in range(20):
+            tsg.gemm(dt, M, N, K, dA1, K, dB1, N, C1, N, tsg.STRICT, s1)
+            assert tsg.last_launch().config.split_k == 8
+            tsg.gemm(dt, M, N, K, dA2, K, dB2, N, C2, N, tsg.STRICT, s2)
+        torch.cuda.synchronize()
+        assert np.array_equal(C1.cpu().numpy().astype(np.float64), R1)
+        assert np.array_equal(C2.cpu().numpy().astype(np.float64), R2)
+        # a stream without an entry has no workspace here: the pinned split fails silenceably
+        with pytest.raises(tsg.SilenceableError):
+            tsg.gemm(dt, M, N, K, dA1, K, dB1, N, C1, N, tsg.STRICT)
+    finally:
+        torch.cuda.synchronize()
+        tsg.workspace_set_stream(s1, None)
+        tsg.workspace_set_stream(s2, None)
+
+
+def test_gemm_and_reduce_share_one_workspace_on_one_stream(workspace):
+    """The reduce counts its arrivals in a slot of its own, so a split-k product and a reduce can
+    follow each other on one buffer, repeatedly, with exact results on integer data."""
+    dt = tsg.F32
+    M, N, K = 128, 128, 4096
+    cfg = tsg.TileConfig(bm=64, bn=64, bk=32, wm=32, wn=32, vec=4, raster=0, sched=4, split_k=4, split_tail=0)
+    tsg.tile_config_set(tsg.OP_GEMM, dt, cfg)
+    A, B = synth.gemm_inputs(M, N, K, seed=43, dist="ints")
+    x = synth.small_ints(44, 0, 1 << 22).reshape(2048, 2048)
+    dA, dB, dx = dev(A), dev(B), dev(x)
+    C = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+    out = torch.zeros((1,), dtype=torch.float32, device=DEV)
+    R = oracle.gemm(A, B, with_s=False)
+    total = oracle.reduce_sum(x)[0]
+    for rep in range(5):
+        tsg.gemm(dt, M, N, K, dA, K, dB, N, C, N, tsg.STRICT)
+        tsg.reduce_sum(dt, 2048, 2048, dx, 2048, out, tsg.STRICT)
+    torch.cuda.synchronize()
+    assert np.array_equal(C.cpu().numpy().astype(np.float64), R)
+    assert float(out.item()) == total
+
+
 @pytest.mark.parametrize("dtype", [tsg.F32, tsg.BF16_F32ACC])
 @pytest.mark.parametrize("trans_a", [False, True])
 def test_split_tail_only_bit_exact(dtype, trans_a, workspace):

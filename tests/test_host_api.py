@@ -216,6 +216,37 @@ def test_invalid_arguments_are_definite_errors():
     with pytest.raises(tsg.TsgError) as e:
         tsg.gemm_batched(tsg.F32, 0, 2, 8, 8, 8, FAKE, 8, 64, FAKE, 8, 64, FAKE, 8, 32, 0, 0)  # C overlap
     assert e.value.status == tsg.E_INVALID
+    # limits of the launch grid and operand alignment are argument errors, with or without STRICT
+    for flags in (0, tsg.STRICT):
+        with pytest.raises(tsg.TsgError) as e:
+            tsg.gemm_batched(tsg.F32, 0, 65536, 8, 8, 8, FAKE, 8, 64, FAKE, 8, 64, FAKE, 8, 64, flags, 0)
+        assert e.value.status == tsg.E_INVALID
+        with pytest.raises(tsg.TsgError) as e:
+            tsg.gemm(tsg.F32, 1 << 20, 1 << 20, 8, FAKE, 8, FAKE, 1 << 20, FAKE, 1 << 20, flags, 0)   # 2^28 tiles
+        assert e.value.status == tsg.E_INVALID
+        for kw in (dict(A=FAKE + 2), dict(B=FAKE + 1), dict(C=FAKE + 2)):
+            with pytest.raises(tsg.TsgError) as e:
+                tsg.gemm(**dict(ok, flags=flags, **kw))
+            assert e.value.status == tsg.E_INVALID, kw
+        with pytest.raises(tsg.TsgError) as e:     # a transposed right operand, misaligned: definite as well
+            tsg.gemm_trans(tsg.F32, 0, 1, 1, 8, 8, 8, FAKE, 8, 0, FAKE + 2, 8, 0, FAKE, 8, 0, flags, 0)
+        assert e.value.status == tsg.E_INVALID
+        with pytest.raises(tsg.TsgError) as e:
+            tsg.gemm(tsg.BF16_F32ACC, 8, 8, 8, FAKE + 1, 8, FAKE, 8, FAKE, 8, flags, 0)
+        assert e.value.status == tsg.E_INVALID
+        with pytest.raises(tsg.TsgError) as e:
+            tsg.conv2d_nhwc(tsg.F32, 1, 4, 4, 4, 4, 3, 3, 1, 1, 1, 1, FAKE + 2, FAKE, FAKE, flags, 0)
+        assert e.value.status == tsg.E_INVALID
+
+
+def test_workspace_per_stream_arguments():
+    """Host side of tsg_workspace_set_stream: malformed buffers are refused, removing an entry
+    that does not exist is fine."""
+    for ws, nbytes in ((FAKE, 65536), (FAKE + 8, 1 << 20), (FAKE, -1), (0, 1 << 20)):
+        with pytest.raises(tsg.TsgError) as e:
+            tsg.workspace_set_stream(0x1234, ws, nbytes)
+        assert e.value.status == tsg.E_INVALID
+    tsg.workspace_set_stream(0x1234, None)
 
 
 def test_strict_call_with_failed_precondition_is_silenceable_and_enqueues_nothing():
