@@ -65,7 +65,8 @@ typedef enum {
     TSG_OK = 0,
     TSG_E_SILENCEABLE = 1, /* precondition failed, nothing modified (Sec. 3) */
     TSG_E_INVALID = 2,     /* definite: null pointer, bad extent / ld / enum */
-    TSG_E_RUNTIME = 3      /* definite: HIP launch or runtime failure */
+    TSG_E_RUNTIME = 3,     /* definite: HIP launch or runtime failure */
+    TSG_E_TOO_LARGE = 4    /* definite: beyond the size limit of tsg_gemm_trans_static */
 } tsg_status;
 
 typedef enum {
@@ -180,6 +181,30 @@ tsg_status tsg_gemm_trans(tsg_dtype dtype, int32_t trans_a, int32_t trans_b, int
                           const void *B, int64_t ldb, int64_t stride_b,
                           float *C, int64_t ldc, int64_t stride_c,
                           uint32_t flags, void *stream);
+
+/* tsg_gemm_trans for callers that cannot allocate device memory and so have no workspace to
+ * hand over: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, same results (bit for bit, for the same tile config) as
+ * tsg_gemm_trans with a workspace of TSG_STATIC_SCRATCH_BYTES bytes; the scratch for the
+ * split of the k loop is a device array of that size inside the library's code object (each
+ * GPU the library runs on holds one copy until the process ends).  The call allocates and
+ * frees nothing and only enqueues kernels on `stream`; its first use on a device also enqueues
+ * a kernel that zeroes the arrival counters.  Limit: batch * M * N, with M and N rounded up to
+ * multiples of 64, at most TSG_STATIC_MAX_OUTPUTS (a two-way split of every tile then fits):
+ * beyond it TSG_E_TOO_LARGE, nothing enqueued -- such outputs have tiles enough to fill the
+ * chip and do not need the split, so tsg_gemm_trans serves them without a workspace.  All
+ * calls on one GPU share that GPU's array: two of them in flight at once (different streams,
+ * or replays of two graphs) race, exactly like two calls sharing one caller-owned workspace.
+ * A pinned or tuned config that needs more scratch than the array holds is a silenceable
+ * failure and the chain of alternatives goes on, as in tsg_gemm_trans. */
+#define TSG_STATIC_SCRATCH_BYTES (65536 + (8 << 20))
+#define TSG_STATIC_MAX_OUTPUTS (1 << 20)
+tsg_status tsg_gemm_trans_static(tsg_dtype dtype, int32_t trans_a, int32_t trans_b, int64_t batch,
+                                 int64_t M, int64_t N, int64_t K,
+                                 const void *A, int64_t lda, int64_t stride_a,
+                                 const void *B, int64_t ldb, int64_t stride_b,
+                                 float *C, int64_t ldc, int64_t stride_c,
+                                 uint32_t flags, void *stream);
 
 /* y[N][Ho][Wo][Cout] = +-conv(x[N][H][W][Cin], w[KH][KW][Cin][Cout]) (+ y), zero
  * padding (pad_h, pad_w) never materialised; Ho = (H + 2*pad_h - KH)/stride_h + 1. */

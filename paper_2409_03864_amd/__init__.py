@@ -14,7 +14,9 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libtsg.so")
 
-OK, E_SILENCEABLE, E_INVALID, E_RUNTIME = 0, 1, 2, 3
+OK, E_SILENCEABLE, E_INVALID, E_RUNTIME, E_TOO_LARGE = 0, 1, 2, 3, 4
+STATIC_SCRATCH_BYTES = 65536 + (8 << 20)      # TSG_STATIC_SCRATCH_BYTES
+STATIC_MAX_OUTPUTS = 1 << 20                  # TSG_STATIC_MAX_OUTPUTS
 F32, BF16_F32ACC = 0, 1
 OP_GEMM, OP_GEMM_TRANSA, OP_CONV2D_NHWC = 0, 1, 2
 NEGATE, ACCUMULATE, STRICT = 1, 2, 4
@@ -64,6 +66,7 @@ def _load():
         "tsg_gemm_transA": [i32, i64, i64, i64, vp, i64, vp, i64, vp, i64, u32, vp],
         "tsg_gemm_batched": [i32, i32, i64, i64, i64, i64, vp, i64, i64, vp, i64, i64, vp, i64, i64, u32, vp],
         "tsg_gemm_trans": [i32, i32, i32, i64, i64, i64, i64, vp, i64, i64, vp, i64, i64, vp, i64, i64, u32, vp],
+        "tsg_gemm_trans_static": [i32, i32, i32, i64, i64, i64, i64, vp, i64, i64, vp, i64, i64, vp, i64, i64, u32, vp],
         "tsg_conv2d_nhwc": [i32] + [i64] * 11 + [vp, vp, vp, u32, vp],
         "tsg_conv2d_nhwc_window": [i32] + [i64] * 11 + [vp, vp, vp, i64, i64, i64, u32, vp],
         "tsg_reduce_sum": [i32, i64, i64, vp, i64, vp, u32, vp],
@@ -113,7 +116,7 @@ def _load():
 
 _lib = _load()
 
-EXPORTS = ("tsg_gemm", "tsg_gemm_transA", "tsg_gemm_batched", "tsg_gemm_trans", "tsg_autotune_gemm_trans", "tsg_conv2d_nhwc", "tsg_conv2d_nhwc_window",
+EXPORTS = ("tsg_gemm", "tsg_gemm_transA", "tsg_gemm_batched", "tsg_gemm_trans", "tsg_gemm_trans_static", "tsg_autotune_gemm_trans", "tsg_conv2d_nhwc", "tsg_conv2d_nhwc_window",
            "tsg_reduce_sum", "tsg_split",
            "tsg_tile_config_count", "tsg_tile_config_enum", "tsg_tile_config_check",
            "tsg_tile_config_set", "tsg_tile_config_get", "tsg_last_launch", "tsg_workspace_set",
@@ -181,6 +184,13 @@ def gemm_trans(dtype, trans_a, trans_b, batch, M, N, K, A, lda, stride_a, B, ldb
     _check(_lib.tsg_gemm_trans(dtype, int(bool(trans_a)), int(bool(trans_b)), batch, M, N, K, _ptr(A), lda, stride_a,
                                _ptr(B), ldb, stride_b, _ptr(C), ldc, stride_c, flags, _stream(stream)),
            "tsg_gemm_trans")
+
+
+def gemm_trans_static(dtype, trans_a, trans_b, batch, M, N, K, A, lda, stride_a, B, ldb, stride_b, C, ldc,
+                      stride_c, flags=0, stream=None):
+    _check(_lib.tsg_gemm_trans_static(dtype, int(bool(trans_a)), int(bool(trans_b)), batch, M, N, K, _ptr(A), lda,
+                                      stride_a, _ptr(B), ldb, stride_b, _ptr(C), ldc, stride_c, flags,
+                                      _stream(stream)), "tsg_gemm_trans_static")
 
 
 def conv2d_nhwc(dtype, N, H, W, Cin, Cout, KH, KW, stride_h, stride_w, pad_h, pad_w, x, w, y,

@@ -19,8 +19,20 @@ LIB = os.path.join(HERE, "libtsg.so")
 SOURCES = ["api.cpp", "gemm_f32_row.hip", "gemm_f32_col.hip", "gemm_f32_conv.hip",
            "gemm_f32_row_bt.hip", "gemm_f32_col_bt.hip", "gemm_bf16_row_bt.hip", "gemm_bf16_col_bt.hip",
            "gemm_bf16_row.hip", "gemm_bf16_col.hip", "gemm_bf16_conv.hip", "reduce.hip"]
-HEADERS = [os.path.join(CSRC, h) for h in ("tsg_internal.h", "gemm_f32_kernel.h", "gemm_bf16_kernel.h")] + \
-          [os.path.join(HERE, "..", "include", "tsg.h")]
+PUBLIC_HEADER = os.path.join(HERE, "..", "include", "tsg.h")
+
+
+def _deps(src: str):
+    """Headers a source includes: the kernel units see their own kernel header, the C-ABI layer
+    and the reduce see the public header."""
+    deps = [os.path.join(CSRC, "tsg_internal.h")]
+    if src.startswith("gemm_f32"):
+        deps.append(os.path.join(CSRC, "gemm_f32_kernel.h"))
+    elif src.startswith("gemm_bf16"):
+        deps.append(os.path.join(CSRC, "gemm_bf16_kernel.h"))
+    else:
+        deps.append(PUBLIC_HEADER)
+    return deps
 
 # packed-fp32 instruction selection is switched off for all device code
 HIPCC_FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-fno-gpu-rdc",
@@ -45,7 +57,7 @@ def _stale(target: str, deps) -> bool:
 def _compile(src: str, force: bool) -> str:
     path = os.path.join(CSRC, src)
     obj = os.path.join(OBJ, src + ".o")
-    if force or _stale(obj, [path] + HEADERS):
+    if force or _stale(obj, [path] + _deps(src)):
         cmd = [_hipcc()] + HIPCC_FLAGS + ["-x", "hip", "-c", path, "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:

@@ -78,6 +78,42 @@ void resolve_workspace(void* stream, void** ws, int64_t* bytes) {
     *bytes = g_ws ? g_ws_bytes : 0;
 }
 
+// ---- scratch of the allocation-free entry point (tsg_gemm_trans_static) -------------------
+// Device memory that belongs to the library's code object: arrival counters first, partial
+// tiles after them, laid out like a caller's workspace.  Every GPU holds its own copy at its
+// own address; in host code the array's name only stands for the symbol, so the address is
+// looked up once per device and that pointer is what kernels are given.
+constexpr int64_t kStaticScratchBytes = TSG_STATIC_SCRATCH_BYTES;
+static_assert(kStaticScratchBytes > kCounterBytes && kStaticScratchBytes % 256 == 0, "scratch layout");
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];     // device address of `scratch` on device d, null until first used there
+std::mutex g_scratch_mu;
+
+__global__ void clear_words_kernel(int* w, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) w[i] = 0;
+}
+
+// The current device's copy of `scratch`.  The first call on a device looks the address up and
+// enqueues a kernel on `s` that zeroes the counters (a kernel, not a memset: the call may be
+// recorded into a graph); after that the kernels themselves leave every counter at zero.
+tsg_status static_scratch(hipStream_t s, void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return TSG_E_RUNTIME;
+    std::lock_guard<std::mutex> g(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return TSG_E_RUNTIME;
+        const int words = (int)(kCounterBytes / 4);
+        hipLaunchKernelGGL(clear_words_kernel, dim3((words + 255) / 256), dim3(256), 0, s, (int*)ptr, words);
+        if (hipGetLastError() != hipSuccess) return TSG_E_RUNTIME;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return TSG_OK;
+}
+
 const KernelEntry* kernels(tsg_dtype dt, int* n) {
     return dt == TSG_F32 ? tsg::f32_kernels(n) : tsg::bf16_kernels(n);
 }
@@ -590,6 +626,9 @@ const char* tsg_status_string(tsg_status s) {
         case TSG_E_SILENCEABLE: return "silenceable: precondition of the requested schedule failed, nothing modified";
         case TSG_E_INVALID: return "definite: invalid argument";
         case TSG_E_RUNTIME: return "definite: HIP runtime failure";
+        case TSG_E_TOO_LARGE:
+            return "definite: the output exceeds what the allocation-free entry point serves "
+                   "(batch * M * N, padded to 64 x 64 tiles, above TSG_STATIC_MAX_OUTPUTS); use tsg_gemm_trans";
     }
     return "unknown status";
 }
@@ -623,6 +662,33 @@ tsg_status tsg_gemm_trans(tsg_dtype dtype, int32_t trans_a, int32_t trans_b, int
     p.trans_b = trans_b != 0;
     p.flags = flags;
     resolve_workspace(stream, &p.ws, &p.ws_bytes);
+    return run(p, (hipStream_t)stream);
+}
+
+tsg_status tsg_gemm_trans_static(tsg_dtype dtype, int32_t trans_a, int32_t trans_b, int64_t batch, int64_t M,
+                                 int64_t N, int64_t K, const void* A, int64_t lda, int64_t stride_a, const void* B,
+                                 int64_t ldb, int64_t stride_b, float* C, int64_t ldc, int64_t stride_c,
+                                 uint32_t flags, void* stream) {
+    const tsg_status v = check_gemm(dtype, batch, M, N, K, A, lda, B, ldb, C, ldc, trans_a != 0, flags, trans_b != 0);
+    if (v != TSG_OK) return v;
+    if (stride_a < 0 || stride_b < 0 || stride_c < 0) return TSG_E_INVALID;
+    if (batch > 1 && stride_c < (M - 1) * ldc + N) return TSG_E_INVALID;
+    // served: outputs small enough that their tiles cannot fill the chip without a split of k,
+    // sized so that a two-way split of every 64 x 64 tile fits the scratch
+    if (batch * (((M + 63) / 64) * 64) * (((N + 63) / 64) * 64) > TSG_STATIC_MAX_OUTPUTS) return TSG_E_TOO_LARGE;
+    Problem p;
+    p.op = trans_a ? TSG_OP_GEMM_TRANSA : TSG_OP_GEMM;
+    p.dtype = dtype;
+    p.batch = batch;
+    p.M = M; p.N = N; p.K = K;
+    p.A = A; p.B = B; p.C = C;
+    p.lda = lda; p.ldb = ldb; p.ldc = ldc;
+    p.stride_a = stride_a; p.stride_b = stride_b; p.stride_c = stride_c;
+    p.trans_b = trans_b != 0;
+    p.flags = flags;
+    const tsg_status ss = static_scratch((hipStream_t)stream, &p.ws);
+    if (ss != TSG_OK) return ss;
+    p.ws_bytes = kStaticScratchBytes;
     return run(p, (hipStream_t)stream);
 }
 
