@@ -49,8 +49,9 @@ def kernel_hash(dtype: str, op: str = "") -> str:
     import hashlib
     h = hashlib.sha256()
     csrc = os.path.join(ROOT, "paper_2409_03864_amd", "csrc")
-    kernel = "reduce.hip" if op == "reduce_sum" else "gemm_f32_kernel.h" if dtype == "f32" else "gemm_bf16_kernel.h"
-    for f in ("tsg_internal.h", kernel):
+    # the sources a kernel is built from: both element types share one skeleton
+    h.update(dtype.encode() if op != "reduce_sum" else b"")
+    for f in ("tsg_internal.h",) + (("reduce.hip",) if op == "reduce_sum" else ("gemm_kernel.h", "gemm_elem.h")):
         with open(os.path.join(csrc, f), "rb") as fh:
             h.update(fh.read())
     return h.hexdigest()[:16]

@@ -89,7 +89,7 @@ enum {
  *                batch loop is not tiled).  0 = "library default for this loop" (tiling
  *                by 0 is a no-op, Sec. 3.4).  A tile larger than the extent is legal:
  *                the whole loop becomes remainder.
- *   wm, wn     : per-wavefront sub-tile (multiples of the 32x32 MFMA block).
+ *   wm, wn     : per-wavefront sub-tile (multiples of the MFMA block, see mfma).
  *   vec        : elements per global access along the contiguous dimension, the
  *                paper's `vect`: 1, or 4 (fp32) / 8 (bf16) = 16-byte accesses.  Fig. 10
  *                allows vect only when the innermost extent is divisible by the vector
@@ -99,14 +99,12 @@ enum {
  *                always legal; for the convolution the gathered operand is contiguous
  *                only along Cin, and vec must divide Cin.
  *   raster     : 0 = tiles in row-major order, 1 = XCD-aware grouped order.
- *   sched      : form of the inner loop: 0 = fragments read where they are used, order
- *                left to the compiler; 1 = explicit software pipeline (fragments one k
- *                group ahead, next tile parked in LDS mid-step); 2 = the same pipeline
- *                one MFMA ahead; 3 = as 2 with three LDS stages and the barrier in the
- *                middle of the step; 4 / 5 = operand tiles loaded from global memory
- *                straight into a ring of 3 / 4 LDS stages (two / three k steps in flight),
- *                wide accesses only.  -1 = library default.
- *                Only (tile, sched) pairs that are instantiated are legal.
+ *   sched      : kernel form: 0 = operand tiles staged through registers into two padded LDS
+ *                stages, instruction order left to the compiler (serves every access width);
+ *                4 / 5 = operand tiles loaded from global memory straight into a ring of
+ *                3 / 4 LDS stages (two / three k steps in flight), wide accesses only.
+ *                -1 = library default.  Only (tile, sched) pairs that are instantiated are
+ *                legal.
  *   split_k    : number of workgroups that share one tile of C, each taking a contiguous
  *                range of k steps (tiling the k loop at the grid level when i x j tiles
  *                alone cannot fill the chip).  1 = none; 0 = library default.  Values
@@ -127,6 +125,7 @@ typedef struct {
     int32_t sched;
     int32_t split_k;
     int32_t split_tail;
+    int32_t mfma;
 } tsg_tile_config;
 
 /* What the most recent compute call on the calling thread enqueued. */

@@ -24,7 +24,7 @@ NEGATE, ACCUMULATE, STRICT = 1, 2, 4
 
 class TileConfig(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("bm", "bn", "bk", "wm", "wn", "vec", "raster", "sched", "split_k",
-                                                   "split_tail")]
+                                                   "split_tail", "mfma")]
 
     def as_dict(self):
         return {n: int(getattr(self, n)) for n, _ in self._fields_}

@@ -26,10 +26,8 @@ def _deps(src: str):
     """Headers a source includes: the kernel units see their own kernel header, the C-ABI layer
     and the reduce see the public header."""
     deps = [os.path.join(CSRC, "tsg_internal.h")]
-    if src.startswith("gemm_f32"):
-        deps.append(os.path.join(CSRC, "gemm_f32_kernel.h"))
-    elif src.startswith("gemm_bf16"):
-        deps.append(os.path.join(CSRC, "gemm_bf16_kernel.h"))
+    if src.startswith("gemm_"):
+        deps += [os.path.join(CSRC, "gemm_kernel.h"), os.path.join(CSRC, "gemm_elem.h")]
     else:
         deps.append(PUBLIC_HEADER)
     return deps

@@ -1,6 +1,7 @@
 // C-ABI layer: argument validation, the loop split, the tile-config registry with its
 // legality rules, the chain of alternatives, launch planning and the tuner.
-// Host code only; the kernels live in gemm_f32_*.hip and gemm_bf16_*.hip.
+// Host code, plus the static scratch of the allocation-free entry point; the kernels live in
+// gemm_kernel.h (instantiated by gemm_f32_*.hip and gemm_bf16_*.hip) and reduce.hip.
 #include <algorithm>
 #include <array>
 #include <cstdio>
@@ -129,7 +130,7 @@ const KernelEntry* find_entry(tsg_dtype dt, const tsg_tile_config& c) {
     const KernelEntry* t = kernels(dt, &n);
     for (int i = 0; i < n; ++i)
         if (t[i].bm == c.bm && t[i].bn == c.bn && t[i].bk == c.bk && t[i].wm == c.wm && t[i].wn == c.wn &&
-            t[i].sched == c.sched)
+            t[i].sched == c.sched && t[i].mfma == c.mfma)
             return &t[i];
     return nullptr;
 }
@@ -138,6 +139,7 @@ tsg_tile_config config_of(const KernelEntry& e, int vec, int raster, int split_k
     tsg_tile_config c;
     c.bm = e.bm; c.bn = e.bn; c.bk = e.bk; c.wm = e.wm; c.wn = e.wn;
     c.vec = vec; c.raster = raster; c.sched = e.sched; c.split_k = split_k; c.split_tail = split_tail;
+    c.mfma = e.mfma;
     return c;
 }
 
@@ -253,12 +255,13 @@ tsg_tile_config fill_defaults(tsg_tile_config c, const tsg_tile_config& def) {
     if (c.bm <= 0) c.bm = def.bm;
     if (c.bn <= 0) c.bn = def.bn;
     if (c.bk <= 0) c.bk = def.bk;
-    if (!tile_given) { c.wm = def.wm; c.wn = def.wn; c.sched = def.sched; }
+    if (!tile_given) { c.wm = def.wm; c.wn = def.wn; c.sched = def.sched; c.mfma = def.mfma; }
     if (c.wm <= 0) c.wm = std::min(c.bm, 64);
     if (c.wn <= 0) c.wn = std::min(c.bn, 64);
     if (c.vec <= 0) c.vec = def.vec;
     if (c.raster < 0) c.raster = def.raster;
     if (c.sched < 0) c.sched = def.sched;
+    if (c.mfma < 0) c.mfma = 0;
     if (c.split_k <= 0) { c.split_k = tile_given ? 1 : def.split_k; c.split_tail = tile_given ? 0 : def.split_tail; }
     return c;
 }
@@ -863,14 +866,14 @@ tsg_status tsg_tune_cache_save(const char* path) {
     std::FILE* f = std::fopen(path, "w");
     if (!f) return TSG_E_RUNTIME;
     std::lock_guard<std::mutex> g(g_mu);
-    std::fprintf(f, "# tsg tuner results: op dtype trans_b batch M N K contig  bm bn bk wm wn vec raster sched split_k split_tail  ms\n");
+    std::fprintf(f, "# tsg tuner results: op dtype trans_b batch M N K contig  bm bn bk wm wn vec raster sched split_k split_tail mfma  ms\n");
     for (const auto& kv : g_tuned) {
         const TuneKey& k = kv.first;
         const tsg_tile_config& c = kv.second.cfg;
-        std::fprintf(f, "%lld %lld %lld %lld %lld %lld %lld %lld  %d %d %d %d %d %d %d %d %d %d  %.6f\n", (long long)k[0],
+        std::fprintf(f, "%lld %lld %lld %lld %lld %lld %lld %lld  %d %d %d %d %d %d %d %d %d %d %d  %.6f\n", (long long)k[0],
                      (long long)k[1], (long long)k[2], (long long)k[3], (long long)k[4], (long long)k[5],
                      (long long)k[6], (long long)k[7], c.bm, c.bn, c.bk, c.wm, c.wn, c.vec, c.raster, c.sched,
-                     c.split_k, c.split_tail, kv.second.ms);
+                     c.split_k, c.split_tail, c.mfma, kv.second.ms);
     }
     return std::fclose(f) == 0 ? TSG_OK : TSG_E_RUNTIME;
 }
@@ -886,11 +889,11 @@ tsg_status tsg_tune_cache_load(const char* path, int32_t* loaded, int32_t* rejec
         long long k[8];
         tsg_tile_config c;
         float ms = 0.f;
-        const int n = std::sscanf(line, "%lld %lld %lld %lld %lld %lld %lld %lld %d %d %d %d %d %d %d %d %d %d %f", &k[0],
+        const int n = std::sscanf(line, "%lld %lld %lld %lld %lld %lld %lld %lld %d %d %d %d %d %d %d %d %d %d %d %f", &k[0],
                                   &k[1], &k[2], &k[3], &k[4], &k[5], &k[6], &k[7], &c.bm, &c.bn, &c.bk, &c.wm, &c.wn,
-                                  &c.vec, &c.raster, &c.sched, &c.split_k, &c.split_tail, &ms);
+                                  &c.vec, &c.raster, &c.sched, &c.split_k, &c.split_tail, &c.mfma, &ms);
         // an entry is taken only if it names an instantiated, well-formed config of a valid problem
-        const bool good = n == 19 && valid_op((int)k[0]) && valid_dtype((int)k[1]) && (k[2] == 0 || k[2] == 1) &&
+        const bool good = n == 20 && valid_op((int)k[0]) && valid_dtype((int)k[1]) && (k[2] == 0 || k[2] == 1) &&
                           k[3] >= 1 && k[4] >= 1 && k[5] >= 1 && k[6] >= 1 && find_entry((tsg_dtype)k[1], c) &&
                           (c.vec == 1 || c.vec == vec_max((tsg_dtype)k[1])) && (c.raster == 0 || c.raster == 1) &&
                           c.split_k >= 1 && c.split_k <= kMaxSplit &&

@@ -1,4 +1,4 @@
-// bf16 kernels, transposed left operand read in place: op(A)(i,k) = A[k*lda + i].
-#include "gemm_bf16_kernel.h"
+// bfloat16 kernels, op(A)(i,k) = A[k*lda + i] (transposed left operand read in place).
+#include "gemm_kernel.h"
 
-TSG_BF16_DEFINE_MODE(launch_bf16_col, A_COL)
+TSG_DEFINE_MODE(launch_bf16_col, TSG_BF16_TILES, A_COL)

@@ -1,7 +1,7 @@
-// bf16 kernels, op(A)(i,k) = A[i*lda + k], and the table of instantiated tiles.
-#include "gemm_bf16_kernel.h"
+// bfloat16 kernels, op(A)(i,k) = A[i*lda + k], and the table of instantiated tiles.
+#include "gemm_kernel.h"
 
-TSG_BF16_DEFINE_MODE(launch_bf16_row, A_ROW)
+TSG_DEFINE_MODE(launch_bf16_row, TSG_BF16_TILES, A_ROW)
 
 namespace tsg {
 hipError_t launch_bf16_col(int tile, int variant, const KArgs& a, int batch, hipStream_t s);
@@ -19,13 +19,7 @@ hipError_t launch_any(int tile, int amode, int variant, const KArgs& a, int batc
         default: return launch_bf16_conv(tile, variant, a, batch, s);
     }
 }
-#define TSG_BF16_ENTRY(bm, bn, bk, wm, wn, mw, sc)                                                    \
-    KernelEntry{bm, bn, bk, wm, wn, sc, Tile<bm, bn, bk, wm, wn, mw, sc>::NT, 8,                       \
-                (sc >= 4 ? LdsDirect<Tile<bm, bn, bk, wm, wn, mw, sc>>::BYTES                          \
-                         : 4 * (bm * Tile<bm, bn, bk, wm, wn, mw, sc>::LDK +                          \
-                                bk * Tile<bm, bn, bk, wm, wn, mw, sc>::LDB)),                          \
-                &launch_any},
-const KernelEntry kTable[] = {TSG_BF16_TILES(TSG_BF16_ENTRY)};
+const KernelEntry kTable[] = {TSG_BF16_TILES(TSG_TABLE_ENTRY)};
 }  // namespace
 
 const KernelEntry* bf16_kernels(int* count) {

@@ -1,4 +1,4 @@
-// bf16 kernels, op(A)(i,k) = A[i*lda + k] and op(B)(k,j) = B[j*ldb + k] (both k contiguous).
-#include "gemm_bf16_kernel.h"
+// bfloat16 kernels, A row-major, B stored transposed (N x K) and read in place.
+#include "gemm_kernel.h"
 
-TSG_BF16_DEFINE_MODE(launch_bf16_row_bt, A_ROW_BT)
+TSG_DEFINE_MODE(launch_bf16_row_bt, TSG_BF16_TILES, A_ROW_BT)

@@ -1,4 +1,4 @@
-// fp32 kernels, transposed left operand read in place: op(A)(i,k) = A[k*lda + i].
-#include "gemm_f32_kernel.h"
+// fp32 kernels, op(A)(i,k) = A[k*lda + i] (transposed left operand read in place).
+#include "gemm_kernel.h"
 
-TSG_F32_DEFINE_MODE(launch_f32_col, A_COL)
+TSG_DEFINE_MODE(launch_f32_col, TSG_F32_TILES, A_COL)

@@ -1,4 +1,4 @@
-// fp32 kernels, both operands stored transposed: op(A)(i,k) = A[k*lda + i], op(B)(k,j) = B[j*ldb + k].
-#include "gemm_f32_kernel.h"
+// fp32 kernels, both operands stored transposed and read in place.
+#include "gemm_kernel.h"
 
-TSG_F32_DEFINE_MODE(launch_f32_col_bt, A_COL_BT)
+TSG_DEFINE_MODE(launch_f32_col_bt, TSG_F32_TILES, A_COL_BT)

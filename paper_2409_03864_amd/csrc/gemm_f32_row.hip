@@ -1,7 +1,7 @@
 // fp32 kernels, op(A)(i,k) = A[i*lda + k], and the table of instantiated tiles.
-#include "gemm_f32_kernel.h"
+#include "gemm_kernel.h"
 
-TSG_F32_DEFINE_MODE(launch_f32_row, A_ROW)
+TSG_DEFINE_MODE(launch_f32_row, TSG_F32_TILES, A_ROW)
 
 namespace tsg {
 hipError_t launch_f32_col(int tile, int variant, const KArgs& a, int batch, hipStream_t s);
@@ -19,12 +19,7 @@ hipError_t launch_any(int tile, int amode, int variant, const KArgs& a, int batc
         default: return launch_f32_conv(tile, variant, a, batch, s);
     }
 }
-#define TSG_F32_ENTRY(bm, bn, bk, wm, wn, mw, sc)                                                     \
-    KernelEntry{bm, bn, bk, wm, wn, sc, Tile<bm, bn, bk, wm, wn, mw, sc>::NT, 4,                       \
-                (sc >= 4 ? LdsDirect<Tile<bm, bn, bk, wm, wn, mw, sc>, A_ROW>::BYTES                   \
-                         : Lds<Tile<bm, bn, bk, wm, wn, mw, sc>, A_ROW>::BYTES),                          \
-                &launch_any},
-const KernelEntry kTable[] = {TSG_F32_TILES(TSG_F32_ENTRY)};
+const KernelEntry kTable[] = {TSG_F32_TILES(TSG_TABLE_ENTRY)};
 }  // namespace
 
 const KernelEntry* f32_kernels(int* count) {

@@ -1,4 +1,4 @@
-// fp32 kernels, op(A)(i,k) = A[i*lda + k] and op(B)(k,j) = B[j*ldb + k] (both k contiguous).
-#include "gemm_f32_kernel.h"
+// fp32 kernels, A row-major, B stored transposed (N x K) and read in place.
+#include "gemm_kernel.h"
 
-TSG_F32_DEFINE_MODE(launch_f32_row_bt, A_ROW_BT)
+TSG_DEFINE_MODE(launch_f32_row_bt, TSG_F32_TILES, A_ROW_BT)

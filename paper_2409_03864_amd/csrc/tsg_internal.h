@@ -49,7 +49,8 @@ struct KArgs {
 // One instantiated tile shape.  `launch` takes the entry's index in its table.
 struct KernelEntry {
     int bm, bn, bk, wm, wn;
-    int sched;       // inner-loop form, see the kernel headers
+    int sched;       // kernel form, see gemm_kernel.h
+    int mfma;        // MFMA block: 0 = 32 x 32, 1 = 16 x 16
     int threads;
     int vec;         // elements per 16-byte access for this dtype
     int lds_bytes;   // LDS per workgroup (both stages, k-contiguous A layout)

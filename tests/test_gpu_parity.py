@@ -212,10 +212,10 @@ def test_split_k_bit_exact_and_repeatable(dtype, trans_a, workspace):
     A, B = inputs(M, N, K, 31, "ints", trans_a, dtype)
     R = oracle.gemm(A, B, trans_a=trans_a, with_s=False)
     C0 = synth.small_ints(8, 2, M * N).reshape(M, N)
-    for bm, bn, bk, wm, wn in ((64, 64, 64, 32, 32), (128, 128, 32, 64, 64)):
+    for bm, bn, bk, wm, wn, sched in ((64, 64, 64, 32, 32, 0), (128, 128, 32, 64, 64, 4 if dtype == tsg.F32 else 0)):
         for split in (2, 4, 8, 16):
             c = tsg.TileConfig(bm=bm, bn=bn, bk=bk, wm=wm, wn=wn, vec=vmax, raster=0,
-                               sched=(0 if dtype == tsg.F32 else 1), split_k=split)
+                               sched=sched, split_k=split)
             assert tsg.tile_config_check(op, dtype, M, N, K, c) == tsg.OK
             tsg.tile_config_set(op, dtype, c)
             for rep in range(2):
@@ -234,7 +234,7 @@ def test_split_k_random_is_deterministic_and_within_tolerance(workspace):
     dt, op = tsg.F32, tsg.OP_GEMM
     M, N, K = 196, 256, 2305
     A, B = inputs(M, N, K, 5, "uniform", False, dt)
-    tsg.tile_config_set(op, dt, tsg.TileConfig(bm=64, bn=64, bk=64, wm=32, wn=32, vec=4, raster=0, sched=2,
+    tsg.tile_config_set(op, dt, tsg.TileConfig(bm=64, bn=64, bk=64, wm=32, wn=32, vec=4, raster=0, sched=0,
                                                split_k=8))
     runs = [run_gemm(dt, A, B, flags=tsg.STRICT) for _ in range(4)]
     for r in runs[1:]:
@@ -339,7 +339,7 @@ def test_split_tail_only_bit_exact(dtype, trans_a, workspace):
     A, B = inputs(M, N, K, 77, "ints", trans_a, dtype)
     R = oracle.gemm(A, B, trans_a=trans_a, with_s=False)
     C0 = synth.small_ints(8, 2, M * N).reshape(M, N)
-    for sched, raster in ((0 if dtype == tsg.F32 else 1, 0), (4, 1)):
+    for sched, raster in ((0, 0), (4, 1)):
         for split in (2, 4):
             c = tsg.TileConfig(bm=64, bn=64, bk=64, wm=32, wn=32, vec=vmax, raster=raster, sched=sched,
                                split_k=split, split_tail=1)

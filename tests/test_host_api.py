@@ -49,7 +49,7 @@ def test_search_space_enumeration():
             for i in range(n):
                 c = tsg.tile_config_enum(op, dt, i)
                 assert c.bm % c.wm == 0 and c.bn % c.wn == 0 and c.wm % 32 == 0 and c.wn % 32 == 0
-                assert c.vec in (1, vmax) and c.raster in (0, 1) and c.sched in (0, 1, 2, 3, 4, 5)
+                assert c.vec in (1, vmax) and c.raster in (0, 1) and c.sched in (0, 4, 5) and c.mfma in (0, 1)
                 assert c.split_k in (1, 2, 4, 8, 16)
                 key = tuple(c.as_dict().values())
                 assert key not in seen
@@ -294,15 +294,16 @@ def test_tune_cache_save_load_roundtrip(tmp_path):
     default = tsg.tile_config_get(op, dt, 1000, 900, 800).as_dict()
     f = tmp_path / "tuned.txt"
     f.write_text("# comment\n"
-                 "0 0 0 1 1000 900 800 0  128 128 32 64 64 4 0 0 1 0  0.5\n"     # instantiated
-                 "0 0 0 1 1000 900 801 0  96 96 32 32 32 4 0 0 1 0  0.5\n"       # not instantiated
-                 "0 0 0 1 1000 900 802 0  128 128 32 64 64 3 0 0 1 0  0.5\n"     # no such access width
+                 "0 0 0 1 1000 900 800 0  128 128 16 64 64 4 0 0 1 0 0  0.5\n"   # instantiated
+                 "0 0 0 1 1000 900 801 0  96 96 32 32 32 4 0 0 1 0 0  0.5\n"     # not instantiated
+                 "0 0 0 1 1000 900 802 0  128 128 16 64 64 3 0 0 1 0 0  0.5\n"   # no such access width
+                 "0 0 0 1 1000 900 803 0  128 128 16 64 64 4 0 0 1 0 1  0.5\n"   # no such MFMA block for this tile
                  "garbage line\n"
-                 "1 1 1 6 196 256 2305 0  64 64 64 32 32 8 1 4 2 1  0.03\n")
-    assert tsg.tune_cache_load(str(f)) == (2, 3)
+                 "1 1 1 6 196 256 2305 0  64 64 64 32 32 8 1 4 2 1 0  0.03\n")
+    assert tsg.tune_cache_load(str(f)) == (2, 4)
     assert tsg.tune_cache_size() == 2
     got = tsg.tile_config_get(op, dt, 1000, 900, 800).as_dict()
-    assert (got["bm"], got["bn"], got["bk"], got["sched"], got["raster"]) == (128, 128, 32, 0, 0)
+    assert (got["bm"], got["bn"], got["bk"], got["sched"], got["raster"]) == (128, 128, 16, 0, 0)
     assert tsg.tile_config_get(op, dt, 1000, 900, 801).as_dict() != got          # other extents: the default
     pin = tsg.tile_config_enum(op, dt, 5)
     tsg.tile_config_set(op, dt, pin)
