@@ -87,8 +87,9 @@ def workload_flops(c) -> int:
 
 def describe(k, c) -> str:
     if c["op"] == "reduce_sum":
-        return "cfg%d: %s full additive reduce of a %d x %d tensor, %s entries, seed %d" % (
-            k, c["dtype"], c["rows"], c["cols"], c["dist"], c["seed"])
+        return "cfg%d: %s full additive reduce of a %d x %d %s, %s entries, seed %d" % (
+            k, c["dtype"], c["rows"], c["cols"], "view with row pitch %d" % c["ld"] if "ld" in c else "tensor",
+            c["dist"], c["seed"])
     if c["op"] == "conv2d_nhwc":
         return ("cfg%d: %s conv2d NHWC N=%d H=W=%d Cin=%d Cout=%d %dx%d stride %d pad %d, seed %d%s"
                 % (k, c["dtype"], c["N"], c["H"], c["Cin"], c["Cout"], c["KH"], c["KW"], c["stride"], c["pad"],
@@ -140,13 +141,72 @@ def result_record(k, c, mnk, steps, warmup, wall_s, kernel_ms_avg, tile, alterna
     return out
 
 
+# Products the cost model's constants were NOT fitted on (they were fitted on workloads 1 - 6)
+HELD_OUT = [(512, 512, 512, False), (768, 768, 768, False), (1536, 1536, 1536, False), (2048, 2048, 2048, False),
+            (3072, 1024, 4096, False), (1000, 1000, 1000, False), (2048, 2048, 2048, True), (384, 8192, 640, False)]
+
+
+def search_report(tsg, torch, dev) -> int:
+    """For each held-out shape: exhaustive search in cost-model order (the reference), then what a
+    budget of 8 timed points finds in cost-model order and in the model-based order.  One JSON
+    line per shape: rank of the model's first pick among all timed points, its time over the best,
+    Spearman rank correlation of predicted and measured times, evaluations until within 1 % of the
+    best in both orders."""
+    ws = torch.empty(64 << 20, dtype=torch.uint8, device=dev)
+    tsg.workspace_set(ws)
+    for M, N, K, trans in HELD_OUT:
+        import synth
+        a, b = synth.gemm_inputs(M, N, K, seed=100, dist="uniform", trans_a=trans)
+        A, B = torch.from_numpy(a).to(dev), torch.from_numpy(b).to(dev)
+        C = torch.zeros((M, N), dtype=torch.float32, device=dev)
+        lda = M if trans else K
+        iters = 5 if 2.0 * M * N * K >= 1e10 else 30
+
+        def tune(budget, order):
+            tsg.tune_cache_clear()
+            tsg.search_set(budget, order)
+            best, ms, recs = tsg.autotune_gemm(tsg.F32, trans, M, N, K, A, lda, B, N, C, N, iters=iters, log_cap=4096)
+            return ms, [r for r in recs if r.ms >= 0]
+
+        best_ms, timed = tune(0, 1)
+        ranked = sorted(r.ms for r in timed)
+        first = timed[0].ms
+        # Spearman correlation of the two orders over the timed points
+        n = len(timed)
+        by_pred = sorted(range(n), key=lambda i: timed[i].predicted_ms)
+        by_meas = sorted(range(n), key=lambda i: timed[i].ms)
+        rp, rm = [0] * n, [0] * n
+        for rank, i in enumerate(by_pred):
+            rp[i] = rank
+        for rank, i in enumerate(by_meas):
+            rm[i] = rank
+        rho = 1.0 - 6.0 * sum((a - b) ** 2 for a, b in zip(rp, rm)) / (n * (n * n - 1.0))
+        reach1 = next(i + 1 for i, r in enumerate(timed) if r.best_ms <= best_ms * 1.01)
+        ms_b1, t1 = tune(8, 1)
+        ms_b2, t2 = tune(8, 2)
+        full2_ms, timed2 = tune(0, 2)
+        reach2 = next(i + 1 for i, r in enumerate(timed2) if r.best_ms <= min(best_ms, full2_ms) * 1.01)
+        print(json.dumps({"probe": "search_report", "shape": [M, N, K], "trans_a": trans, "timed_points": n,
+                          "best_ms": round(best_ms, 5), "model_first_pick_ms": round(first, 5),
+                          "first_pick_over_best": round(first / best_ms, 4),
+                          "first_pick_rank": 1 + sum(1 for v in ranked if v < first),
+                          "spearman_pred_vs_measured": round(rho, 3),
+                          "evals_to_1pct_model_order": reach1, "evals_to_1pct_adaptive_order": reach2,
+                          "budget8_model_order_over_best": round(ms_b1 / best_ms, 4),
+                          "budget8_adaptive_order_over_best": round(ms_b2 / best_ms, 4)}), flush=True)
+    tsg.search_set(0, 1)
+    tsg.tune_cache_clear()
+    tsg.workspace_set(None)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None,
                     help="timed steps (default: 100, or as many as make the timed region last 0.2 s)")
     ap.add_argument("--warmup", type=int, default=None, help="untimed steps before them (default: a tenth of --steps)")
-    ap.add_argument("--workload", type=int, default=3, choices=list(range(1, 11)))
+    ap.add_argument("--workload", type=int, default=3, choices=list(range(1, 12)))
     ap.add_argument("--no-tune", action="store_true", help="use the shape heuristic instead of the tuner")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--graph", action="store_true",
@@ -155,7 +215,13 @@ def main() -> int:
     ap.add_argument("--tuner-log", default="", metavar="PATH",
                     help="write the tuner's evaluated points (time, prediction, best so far) to this JSON file")
     ap.add_argument("--cpu-rows", type=int, default=4096, help="rows of the product the oracle is timed on")
-    ap.add_argument("--pin", default="", help="bm,bn,bk,wm,wn,vec,raster,sched[,split_k[,split_tail]]: pin this tile config instead of tuning")
+    ap.add_argument("--pin", default="", help="bm,bn,bk,wm,wn,vec,raster,sched[,split_k[,split_tail[,mfma]]]: pin this tile config instead of tuning")
+    ap.add_argument("--mfma-ceiling", action="store_true",
+                    help="instead of a workload, run the register-only MFMA loops (practical ceiling of the matrix "
+                         "pipes per dtype, block shape and operand values) and print one line per loop")
+    ap.add_argument("--search-report", action="store_true",
+                    help="instead of a workload, tune fp32 products of shapes the cost model was not fitted on and "
+                         "print, per shape, how the model's order compares with the measured one")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="also run one plain device copy of this many MiB (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -175,6 +241,26 @@ def main() -> int:
         return 3
     dev = "cuda:0"
     torch.cuda.set_device(0)
+
+    if args.mfma_ceiling:
+        sink = torch.empty(4 << 20, dtype=torch.uint8, device=dev)
+        for dtype, name, peak in ((tsg.F32, "f32", PEAK_TFLOPS["f32"]), (tsg.BF16_F32ACC, "bf16", PEAK_TFLOPS["bf16"])):
+            for mfma, shape in ((0, "32x32x2" if dtype == tsg.F32 else "32x32x16"),
+                                (1, "16x16x4" if dtype == tsg.F32 else "16x16x32")):
+                for rnd in (0, 1):
+                    for wps in (1, 2):
+                        best, sustained = tsg.mfma_ceiling(dtype, mfma, rnd, wps, 20, sink)
+                        # at full issue a CU retires 256 fp32 / 4096 bf16 flop per cycle: the rate is a clock
+                        ghz = sustained * 1e12 / (256 * (256 if dtype == tsg.F32 else 4096)) / 1e9
+                        print(json.dumps({"probe": "mfma_ceiling", "dtype": name, "mfma": shape,
+                                          "operands": "N(0,1)/90.5" if rnd else "constant 0.5", "waves_per_simd": wps,
+                                          "tflops_best": round(best, 1), "tflops_sustained": round(sustained, 1),
+                                          "frac_of_peak": round(sustained / peak, 4),
+                                          "effective_ghz": round(ghz, 3)}), flush=True)
+        return 0
+
+    if args.search_report:
+        return search_report(tsg, torch, dev)
 
     k = args.workload
     t0 = time.time()
@@ -203,8 +289,10 @@ def main() -> int:
         dC = torch.zeros((1,), dtype=torch.float32, device=dev)
         pC = dC.data_ptr()
 
+        ld = c.get("ld", N)
+
         def step():
-            tsg.reduce_sum(dt, M, N, pA, N, pC, flags, st)
+            tsg.reduce_sum(dt, M, N, pA, ld, pC, flags, st)
 
         args.no_tune = True      # one kernel form, nothing to search
     elif c["op"] == "conv2d_nhwc":
@@ -292,7 +380,8 @@ def main() -> int:
         v = [int(t) for t in args.pin.split(",")]
         tsg.tile_config_set(op, dt, tsg.TileConfig(bm=v[0], bn=v[1], bk=v[2], wm=v[3], wn=v[4], vec=v[5], raster=v[6], sched=v[7],
                                                    split_k=(v[8] if len(v) > 8 else 1),
-                                                   split_tail=(v[9] if len(v) > 9 else 0)))
+                                                   split_tail=(v[9] if len(v) > 9 else 0),
+                                                   mfma=(v[10] if len(v) > 10 else 0)))
         args.no_tune = True
     if not args.no_tune:
         tsg.search_set(args.evals, True)
@@ -382,7 +471,7 @@ def main() -> int:
     if not args.no_cpu:
         import oracle
         if c["op"] == "reduce_sum":
-            sub = a[:min(M, 4096)]
+            sub = np.ascontiguousarray(a[:min(M, 65536), :N])
             t0 = time.perf_counter()
             oracle.reduce_sum(sub)
             dtc = time.perf_counter() - t0

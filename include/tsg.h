@@ -141,7 +141,9 @@ typedef struct {
 /* One evaluation of the tuner (Case Study 5, Fig. 11: runtime per evaluated point). */
 typedef struct {
     tsg_tile_config config;
-    float ms;        /* mean time of one call (best of three batches); < 0 if illegal here */
+    float ms;        /* mean time of one call (best of three batches); not timed: -1 = illegal
+                        here, -2 = pruned (a split of k where the unsplit tiles already fill the
+                        chip twice over) */
     float best_ms;   /* best so far, including this evaluation */
     float predicted_ms; /* the cost model's estimate for this point (at 2.4 GHz) */
 } tsg_tune_record;
@@ -311,9 +313,14 @@ tsg_status tsg_gemm_index_map(int32_t trans_a, int64_t M, int64_t K, int64_t lda
 /* ---- search (Case Study 5) ----------------------------------------------------- */
 
 /* Budget and order of the tuner calls that follow.  max_evals: stop after that many timed
- * points (0 = all).  model_order: 1 = visit the points in the order of the library's cost
- * model, so that the first timed point is the library's default for the shape and a small
- * budget covers the likely winners; 0 = in enumeration order.  Default (0, 1). */
+ * points (0 = all).  model_order: 0 = visit the points in enumeration order; 1 = in the order
+ * of the library's cost model, so that the first timed point is the library's default for the
+ * shape and a small budget covers the likely winners; 2 = model-based search: the cost model is
+ * a prior, every timed point corrects it (the ratio measured / predicted, per kernel and
+ * overall), and the next point timed is the one with the smallest corrected prediction, so a
+ * kernel family the prior flatters drops back after its first measurement (Case Study 5 couples
+ * the parameters to a model-based tuner; this is the same loop with a hand-made surrogate).
+ * Default (0, 1). */
 tsg_status tsg_search_set(int32_t max_evals, int32_t model_order);
 
 /* Time every legal instantiated config on the caller's buffers (three batches of `iters`
@@ -364,6 +371,17 @@ int32_t    tsg_tune_cache_size(void);
 tsg_status tsg_tune_cache_clear(void);
 tsg_status tsg_tune_cache_save(const char *path);
 tsg_status tsg_tune_cache_load(const char *path, int32_t *loaded, int32_t *rejected);
+
+/* Measurement aid for the roofline figures: the rate the matrix pipes sustain with every
+ * operand in registers (no LDS, no memory, no barrier), one or two wavefronts per SIMD on every
+ * compute unit, for the MFMA block shape `mfma` (0 = 32 x 32, 1 = 16 x 16) of the dtype, with
+ * constant operands or (random_operands = 1) operands distributed like the workloads' entries.
+ * Runs `launches` (2..1000) kernels of about 10 ms on `stream` and SYNCHRONISES; tflops[0] =
+ * fastest launch, tflops[1] = mean over the second half of the launches (the sustained rate),
+ * both HOST floats.  `sink` is a DEVICE buffer of at least 2 MiB that receives throw-away
+ * results. */
+tsg_status tsg_mfma_ceiling(tsg_dtype dtype, int32_t mfma, int32_t random_operands, int32_t waves_per_simd,
+                            int32_t launches, float *sink, int64_t sink_bytes, float *tflops, void *stream);
 
 const char *tsg_status_string(tsg_status s);
 int32_t tsg_version(void);

@@ -70,6 +70,7 @@ def _load():
         "tsg_conv2d_nhwc": [i32] + [i64] * 11 + [vp, vp, vp, u32, vp],
         "tsg_conv2d_nhwc_window": [i32] + [i64] * 11 + [vp, vp, vp, i64, i64, i64, u32, vp],
         "tsg_reduce_sum": [i32, i64, i64, vp, i64, vp, u32, vp],
+        "tsg_mfma_ceiling": [i32, i32, i32, i32, i32, vp, i64, ctypes.POINTER(ctypes.c_float), vp],
         "tsg_split": [i64, i64, vp, vp, vp],
         "tsg_tile_config_enum": [i32, i32, i32, cfgp],
         "tsg_tile_config_check": [i32, i32, i64, i64, i64, i64, cfgp],
@@ -117,7 +118,7 @@ def _load():
 _lib = _load()
 
 EXPORTS = ("tsg_gemm", "tsg_gemm_transA", "tsg_gemm_batched", "tsg_gemm_trans", "tsg_gemm_trans_static", "tsg_autotune_gemm_trans", "tsg_conv2d_nhwc", "tsg_conv2d_nhwc_window",
-           "tsg_reduce_sum", "tsg_split",
+           "tsg_reduce_sum", "tsg_mfma_ceiling", "tsg_split",
            "tsg_tile_config_count", "tsg_tile_config_enum", "tsg_tile_config_check",
            "tsg_tile_config_set", "tsg_tile_config_get", "tsg_last_launch", "tsg_workspace_set",
            "tsg_workspace_set_stream", "tsg_workspace_bytes", "tsg_search_set", "tsg_tune_cache_size", "tsg_tune_cache_clear",
@@ -210,6 +211,14 @@ def reduce_sum(dtype, rows, cols, x, ld, out, flags=0, stream=None):
     _check(_lib.tsg_reduce_sum(dtype, rows, cols, _ptr(x), ld, _ptr(out), flags, _stream(stream)), "tsg_reduce_sum")
 
 
+def mfma_ceiling(dtype, mfma, random_operands, waves_per_simd, launches, sink, stream=None):
+    """(fastest, sustained) TFLOP/s of the register-only MFMA loop; `sink` is a device tensor of >= 2 MiB."""
+    out = (ctypes.c_float * 2)()
+    _check(_lib.tsg_mfma_ceiling(dtype, mfma, int(bool(random_operands)), waves_per_simd, launches, _ptr(sink),
+                                 sink.numel() * sink.element_size(), out, _stream(stream)), "tsg_mfma_ceiling")
+    return float(out[0]), float(out[1])
+
+
 # ---- schedule parameters (host only) -----------------------------------------------
 
 def split(ub, d):
@@ -289,8 +298,9 @@ def gemm_index_map(trans_a, M, K, lda, off):
 
 # ---- search ---------------------------------------------------------------------------
 
-def search_set(max_evals=0, model_order=True):
-    _check(_lib.tsg_search_set(max_evals, int(bool(model_order))), "tsg_search_set")
+def search_set(max_evals=0, model_order=1):
+    """model_order: 0 enumeration order, 1 (or True) cost-model order, 2 model corrected by the timed points."""
+    _check(_lib.tsg_search_set(max_evals, int(model_order)), "tsg_search_set")
 
 
 def tune_cache_size() -> int:

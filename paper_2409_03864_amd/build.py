@@ -18,7 +18,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtsg.so")
 SOURCES = ["api.cpp", "gemm_f32_row.hip", "gemm_f32_col.hip", "gemm_f32_conv.hip",
            "gemm_f32_row_bt.hip", "gemm_f32_col_bt.hip", "gemm_bf16_row_bt.hip", "gemm_bf16_col_bt.hip",
-           "gemm_bf16_row.hip", "gemm_bf16_col.hip", "gemm_bf16_conv.hip", "reduce.hip"]
+           "gemm_bf16_row.hip", "gemm_bf16_col.hip", "gemm_bf16_conv.hip", "reduce.hip", "ceiling.hip"]
 PUBLIC_HEADER = os.path.join(HERE, "..", "include", "tsg.h")
 
 

@@ -4,6 +4,7 @@
 // gemm_kernel.h (instantiated by gemm_f32_*.hip and gemm_bf16_*.hip) and reduce.hip.
 #include <algorithm>
 #include <array>
+#include <cmath>
 #include <cstdio>
 #include <map>
 #include <cstring>
@@ -174,21 +175,19 @@ double model_core(tsg_dtype dt, const KernelEntry& e, double ntiles, int split, 
     const double kLds = 160.0 * 1024;
     const int64_t nk_all = (K + e.bk - 1) / e.bk;
     const double tiles = ntiles * split;
-    const double blocks = (e.wm / 32) * (e.wn / 32);
     const double wg_wps = e.threads / 256.0;                        // waves per SIMD of one workgroup
-    const double wps_cap = (double)(int)(512.0 / (blocks * 16.0 + 64.0));   // register-file limit
+    const double wps_cap = (double)(int)(512.0 / (e.wm * e.wn / 64.0 + 64.0));   // register-file limit
     const double resident = std::max(1.0, std::min((double)(int)(kLds / e.lds_bytes),
                                                    (double)(int)(wps_cap / wg_wps)));
     const double rounds = (double)(int64_t)((tiles + kCUs * resident - 1) / (kCUs * resident));
     const double conc = std::min(resident, (double)(int64_t)((tiles + kCUs - 1) / kCUs));
     const double steps = (double)((nk_all + split - 1) / split);
-    // cycles one wave spends in MFMA per step: fp32 32x32x2 = 64 cycles, bf16 32x32x16 = 32
-    const double wave_mfma = dt == TSG_F32 ? blocks * e.bk * 32.0 : blocks * e.bk * 2.0;
+    // cycles one wave spends in MFMA per step: a SIMD retires 64 fp32 or 1024 bf16 flop per cycle
+    const double wave_mfma = (double)e.wm * e.wn * e.bk * (dt == TSG_F32 ? 1.0 / 32.0 : 1.0 / 512.0);
     const double wg_mfma = wave_mfma * wg_wps;
     // fewer waves per SIMD hide less of the barrier and LDS latency; small wave tiles
     // re-read LDS more often per MFMA; the finely pipelined forms pay a little for their order
     double ineff = (1.0 + 0.16 / (conc * wg_wps)) * (1.0 + 17.7 / (e.wm + e.wn));
-    if (e.sched == 2 || e.sched == 3) ineff *= 1.0275;
     if (e.sched >= 4) ineff *= 0.95;   // the LDS rings keep the barrier and the loads off the MFMA chain
     // k steps in flight ahead of the one being multiplied: register staging 1, the LDS rings 2 / 3
     const double depth = e.sched == 5 ? 3.0 : e.sched == 4 ? 2.0 : 1.0;
@@ -225,7 +224,7 @@ bool split_allowed(const KernelEntry& e, int split, int split_tail, int64_t batc
 
 // The default config of a shape: the model's minimum over instantiated tiles and splits.
 tsg_tile_config heuristic(tsg_dtype dt, int64_t batch, int64_t M, int64_t N, int64_t K, int64_t ws_bytes,
-                          bool direct_only = false) {
+                          int amode = tsg::A_ROW) {
     int n = 0;
     const KernelEntry* t = kernels(dt, &n);
     double best = 0;
@@ -233,8 +232,8 @@ tsg_tile_config heuristic(tsg_dtype dt, int64_t batch, int64_t M, int64_t N, int
     bool first = true;
     for (int i = 0; i < n; ++i)
         for (int tail = 0; tail < 2; ++tail)
-            for (int split = 1; split <= kMaxSplit; split *= 2) {
-                if (direct_only && t[i].sched < 4) break;
+            for (int split = 1; split <= kMaxSplit; ++split) {
+                if (!(t[i].modes >> amode & 1)) break;   // the tile does not exist for this operand layout
                 if (!split_allowed(t[i], split, tail, batch, M, N, K, ws_bytes)) {
                     if (split == 1) continue;   // tail = 1 starts at split 2
                     break;
@@ -284,6 +283,11 @@ TuneKey tune_key(const Problem& p) {
                    p.op == TSG_OP_CONV2D_NHWC ? p.Cin : 0};
 }
 
+int amode_of(const Problem& p) {
+    return p.op == TSG_OP_GEMM ? (p.trans_b ? tsg::A_ROW_BT : tsg::A_ROW)
+           : p.op == TSG_OP_GEMM_TRANSA ? (p.trans_b ? tsg::A_COL_BT : tsg::A_COL) : tsg::A_CONV;
+}
+
 struct Plan {
     const KernelEntry* entry;
     tsg_tile_config cfg;
@@ -298,7 +302,7 @@ tsg_status make_plan(const Problem& p, const tsg_tile_config& cfg, int alternati
     if (!e) return TSG_E_SILENCEABLE;
     if (!vec_legal(p, cfg.vec)) return TSG_E_SILENCEABLE;
     if (e->sched >= 4 && cfg.vec == 1) return TSG_E_SILENCEABLE;   // direct-to-LDS forms move 16-byte chunks
-    if (p.trans_b && e->sched < 4) return TSG_E_SILENCEABLE;       // a transposed B exists in those forms only
+    if (!(e->modes >> amode_of(p) & 1)) return TSG_E_SILENCEABLE;   // the tile does not exist for this operand layout
     if (cfg.raster != 0 && cfg.raster != 1) return TSG_E_SILENCEABLE;
     if (cfg.split_k < 1 || cfg.split_k > kMaxSplit) return TSG_E_SILENCEABLE;
     if ((cfg.split_tail != 0 && cfg.split_tail != 1) || (cfg.split_tail && cfg.split_k == 1)) return TSG_E_SILENCEABLE;
@@ -361,8 +365,7 @@ tsg_status make_plan(const Problem& p, const tsg_tile_config& cfg, int alternati
 }
 
 tsg_status enqueue(const Problem& p, const Plan& pl, hipStream_t s) {
-    const int amode = p.op == TSG_OP_GEMM ? (p.trans_b ? tsg::A_ROW_BT : tsg::A_ROW)
-                      : p.op == TSG_OP_GEMM_TRANSA ? (p.trans_b ? tsg::A_COL_BT : tsg::A_COL) : tsg::A_CONV;
+    const int amode = amode_of(p);
     int n = 0;
     const int tile = (int)(pl.entry - kernels(p.dtype, &n));
     const hipError_t e = pl.entry->launch(tile, amode, pl.variant, pl.args, (int)p.batch, s);
@@ -374,17 +377,17 @@ tsg_status enqueue(const Problem& p, const Plan& pl, hipStream_t s) {
 // The cost model's pick walks the whole table times the splits, which is worth remembering in
 // a loop that calls the same problem again and again: the last few problems of each thread.
 tsg_tile_config heuristic_cached(tsg_dtype dt, int64_t batch, int64_t M, int64_t N, int64_t K, int64_t ws_bytes,
-                                 bool trans_b) {
+                                 int amode) {
     struct Memo { int64_t key[7]; tsg_tile_config cfg; bool used; };
     thread_local Memo memo[8] = {};
     thread_local int next = 0;
-    const int64_t key[7] = {(int64_t)dt, batch, M, N, K, ws_bytes, (int64_t)trans_b};
+    const int64_t key[7] = {(int64_t)dt, batch, M, N, K, ws_bytes, (int64_t)amode};
     for (const Memo& m : memo)
         if (m.used && std::memcmp(m.key, key, sizeof key) == 0) return m.cfg;
     Memo& m = memo[next];
     next = (next + 1) % 8;
     std::memcpy(m.key, key, sizeof key);
-    m.cfg = heuristic(dt, batch, M, N, K, ws_bytes, trans_b);
+    m.cfg = heuristic(dt, batch, M, N, K, ws_bytes, amode);
     m.used = true;
     return m.cfg;
 }
@@ -411,7 +414,7 @@ tsg_status run(const Problem& p, hipStream_t s) {
         if (make_plan(p, pin, 0, &pl) == TSG_OK) return enqueue(p, pl, s);
         if (p.flags & TSG_STRICT) return TSG_E_SILENCEABLE;
     }
-    const tsg_tile_config heur = heuristic_cached(p.dtype, p.batch, p.M, p.N, p.K, ws_bytes, p.trans_b);
+    const tsg_tile_config heur = heuristic_cached(p.dtype, p.batch, p.M, p.N, p.K, ws_bytes, amode_of(p));
     if (make_plan(p, heur, 1, &pl) == TSG_OK) return enqueue(p, pl, s);
     if (p.flags & TSG_STRICT) return TSG_E_SILENCEABLE;
     // (a valid problem always passes the default's preconditions when B is stored transposed:
@@ -490,9 +493,11 @@ tsg_status conv_problem(int dtype, int64_t N, int64_t H, int64_t W, int64_t Cin,
 }
 
 // Enumerated search space: every instantiated tile x {wide access with either raster order,
-// scalar access, wide access with the k loop split 2, 4, 8 or 16 ways, or with only the tail
-// tiles split 2, 4 or 8 ways}.
-constexpr int kPointsPerTile = 10;
+// scalar access, wide access with the k loop split 2, 3, 4, 5, 6, 8, 10, 12 or 16 ways, or
+// with only the tail tiles split 2, 4 or 8 ways}.
+constexpr int kSplits[] = {2, 3, 4, 5, 6, 8, 10, 12, 16};
+constexpr int kNumSplits = (int)(sizeof(kSplits) / sizeof(kSplits[0]));
+constexpr int kPointsPerTile = 3 + kNumSplits + 3;
 int space_size(tsg_dtype dt) {
     int n = 0;
     kernels(dt, &n);
@@ -504,18 +509,16 @@ tsg_tile_config space_point(tsg_dtype dt, int idx) {
     const KernelEntry* t = kernels(dt, &n);
     const KernelEntry& e = t[idx / kPointsPerTile];
     const int k = idx % kPointsPerTile;
-    switch (k) {
-        case 0: return config_of(e, vec_max(dt), 1);
-        case 1: return config_of(e, vec_max(dt), 0);
-        case 2: return config_of(e, 1, 1);
-        case 3: case 4: case 5: case 6: return config_of(e, vec_max(dt), 0, 1 << (k - 2));
-        default: return config_of(e, vec_max(dt), 1, 1 << (k - 6), 1);   // tail only, split 2, 4, 8
-    }
+    if (k == 0) return config_of(e, vec_max(dt), 1);
+    if (k == 1) return config_of(e, vec_max(dt), 0);
+    if (k == 2) return config_of(e, 1, 1);
+    if (k < 3 + kNumSplits) return config_of(e, vec_max(dt), 0, kSplits[k - 3]);
+    return config_of(e, vec_max(dt), 1, 2 << (k - 3 - kNumSplits), 1);   // tail only, split 2, 4, 8
 }
 
 // Search state (Case Study 5): evaluation budget and visiting order of later tuner calls.
 int g_search_max_evals = 0;      // 0 = every legal point
-int g_search_model_order = 1;    // 1 = in the order of the cost model, 0 = in enumeration order
+int g_search_model_order = 1;    // 0 = enumeration order, 1 = cost-model order, 2 = cost model corrected by the timed points
 
 tsg_status autotune(Problem p, hipStream_t s, int iters, tsg_tile_config* best, float* best_ms,
                     tsg_tune_record* log, int32_t log_cap, int32_t* n_log) {
@@ -548,18 +551,48 @@ tsg_status autotune(Problem p, hipStream_t s, int iters, tsg_tile_config* best, 
     if (model_order)
         std::stable_sort(cand.begin(), cand.end(), [](const Cand& a, const Cand& b) { return a.pred < b.pred; });
 
+    // Adaptive order (model_order 2): the cost model is a prior that every timed point corrects.
+    // The ratio measured / predicted is kept per kernel (tile shape and form: its splits, raster
+    // orders and access widths share it) and overall, as sums of logarithms; a candidate's
+    // prediction is scaled by its kernel's mean ratio shrunk towards the overall one (a kernel
+    // without a timed point yet takes the overall ratio), and the next point timed is the
+    // candidate with the smallest corrected prediction.  A kernel family the prior flatters
+    // falls back after its first timed point instead of filling the head of the list.
+    struct Resid { double sum = 0.0; int n = 0; };
+    std::map<const KernelEntry*, Resid> resid;
+    Resid overall;
+    std::vector<char> done(n, 0);
+    auto corrected = [&](const Cand& cd) {
+        const auto it = resid.find(find_entry(p.dtype, cd.c));
+        const double g = overall.n ? overall.sum / overall.n : 0.0;
+        const double m = it == resid.end() ? g : (it->second.sum + g) / (it->second.n + 1);
+        return cd.pred * std::exp(m);
+    };
+
     float bms = -1.f;
     tsg_tile_config bcfg{};
     int written = 0, evals = 0;
     tsg_status st = TSG_OK;
-    for (int i = 0; i < n && st == TSG_OK; ++i) {
+    for (int visit = 0; visit < n && st == TSG_OK; ++visit) {
         if (max_evals > 0 && evals >= max_evals) break;
+        int i = visit;
+        if (model_order == 2) {
+            i = -1;
+            double best_pred = 0.0;
+            for (int j = 0; j < n; ++j) {
+                if (done[j]) continue;
+                const double cp = corrected(cand[j]);
+                if (i < 0 || cp < best_pred) { i = j; best_pred = cp; }
+            }
+        }
+        done[i] = 1;
         const tsg_tile_config c = cand[i].c;
         Plan pl;
-        float med = -1.f;
-        // splitting k only pays while the unsplit tiles cannot fill the chip twice over
+        // splitting k only pays while the unsplit tiles cannot fill the chip twice over: other
+        // split points are pruned, and logged as such (-2), apart from the illegal ones (-1)
         const bool worth = c.split_k == 1 || c.split_tail ||
                            p.batch * ((p.M + c.bm - 1) / c.bm) * ((p.N + c.bn - 1) / c.bn) < 2 * kCUs;
+        float med = worth ? -1.f : -2.f;
         if (worth && make_plan(p, c, 0, &pl) == TSG_OK) {
             st = enqueue(p, pl, s);   // warm-up
             // the first point also brings the clocks up from idle: untimed batches until 30 ms
@@ -591,6 +624,14 @@ tsg_status autotune(Problem p, hipStream_t s, int iters, tsg_tile_config* best, 
             ++evals;
             // a later point must win by more than timing noise: among ties the earlier point stays
             if (bms < 0 || med < bms * 0.995f) { bms = med; bcfg = c; }
+            // what this point teaches about its kernel and about the model as a whole (scalar
+            // access is priced by a flat factor, not by the model: it teaches nothing)
+            if (c.vec != 1 && cand[i].pred > 0) {
+                const double lr = std::log((double)med / cand[i].pred);
+                Resid& r = resid[find_entry(p.dtype, c)];
+                r.sum += lr; ++r.n;
+                overall.sum += lr; ++overall.n;
+            }
         }
         if (written < log_cap) {
             log[written].config = c;
@@ -763,9 +804,10 @@ tsg_status tsg_tile_config_check(tsg_op op, tsg_dtype dtype, int64_t M, int64_t 
         (cfg->split_tail != 0 && cfg->split_tail != 1))
         return TSG_E_INVALID;
     if (op == TSG_OP_CONV2D_NHWC && contig <= 0) return TSG_E_INVALID;
-    const tsg_tile_config c = fill_defaults(*cfg, heuristic(dtype, 1, M, N, K, 0));
+    const int amode = op == TSG_OP_GEMM ? tsg::A_ROW : op == TSG_OP_GEMM_TRANSA ? tsg::A_COL : tsg::A_CONV;
+    const tsg_tile_config c = fill_defaults(*cfg, heuristic(dtype, 1, M, N, K, 0, amode));
     const KernelEntry* e = find_entry(dtype, c);
-    if (!e) return TSG_E_SILENCEABLE;
+    if (!e || !(e->modes >> amode & 1)) return TSG_E_SILENCEABLE;
     if (c.raster != 0 && c.raster != 1) return TSG_E_SILENCEABLE;
     if (c.split_k < 1 || c.split_k > kMaxSplit || c.split_k > (K + e->bk - 1) / e->bk) return TSG_E_SILENCEABLE;
     if (c.split_tail && c.split_k == 1) return TSG_E_SILENCEABLE;
@@ -811,7 +853,8 @@ tsg_status tsg_tile_config_get(tsg_op op, tsg_dtype dtype, int64_t M, int64_t N,
             return TSG_OK;
         }
     }
-    *out = heuristic(dtype, 1, M, N, K, g_ws ? g_ws_bytes : 0);
+    *out = heuristic(dtype, 1, M, N, K, g_ws ? g_ws_bytes : 0,
+                     op == TSG_OP_GEMM ? tsg::A_ROW : op == TSG_OP_GEMM_TRANSA ? tsg::A_COL : tsg::A_CONV);
     return TSG_OK;
 }
 
@@ -843,7 +886,7 @@ int64_t tsg_workspace_bytes(tsg_dtype dtype, int64_t batch, int64_t M, int64_t N
 }
 
 tsg_status tsg_search_set(int32_t max_evals, int32_t model_order) {
-    if (max_evals < 0 || (model_order != 0 && model_order != 1)) return TSG_E_INVALID;
+    if (max_evals < 0 || model_order < 0 || model_order > 2) return TSG_E_INVALID;
     std::lock_guard<std::mutex> g(g_mu);
     g_search_max_evals = max_evals;
     g_search_model_order = model_order;

@@ -530,9 +530,32 @@ __device__ __forceinline__ void wait_loads_outstanding() {
 template <class T>
 struct LdsDirect {
     static constexpr int STAGES = T::SCHED == 5 ? 4 : 3;
-    static constexpr int A_ELEMS = T::BM * T::BK, B_ELEMS = T::BK * T::BN, STAGE = A_ELEMS + B_ELEMS;
+    // A tile is an array of chunks in thread order, a whole number of passes of the workgroup
+    // over it.  A k-contiguous tile whose rows do not fill the last pass (112 or 208 rows) keeps
+    // the pass whole: the chunks beyond the tile come from the block of zeros and are never read.
+    static constexpr int CHUNKS_PER_PASS = T::NT;
+    static constexpr int A_CHUNKS = (T::BM * T::BK / T::E::V + T::NT - 1) / T::NT * T::NT;
+    static constexpr int B_CHUNKS = (T::BK * T::BN / T::E::V + T::NT - 1) / T::NT * T::NT;
+    static constexpr int A_ELEMS = A_CHUNKS * T::E::V, B_ELEMS = B_CHUNKS * T::E::V, STAGE = A_ELEMS + B_ELEMS;
     static constexpr int BYTES = STAGES * STAGE * (int)sizeof(typename T::E::elem);
 };
+
+// Whether a tile shape exists for an address mode in the direct forms: an operand stored
+// [k][j] needs rows of whole chunks that divide the workgroup's passes, and a k-contiguous one
+// that does not fill its last pass is only handled for the left operand.
+template <class T, int MODE>
+constexpr bool direct_mode_ok() {
+    constexpr int AMODE = MODE == A_ROW_BT ? A_ROW : MODE == A_COL_BT ? A_COL : MODE;
+    constexpr bool B_KMAJ = MODE == A_ROW_BT || MODE == A_COL_BT, A_KMAJ = AMODE != A_COL;
+    constexpr int V = T::E::V, NT = T::NT;
+    constexpr int A_CPR = A_KMAJ ? T::BK / V : T::BM / V, A_ROWS = A_KMAJ ? T::BM : T::BK;
+    constexpr int B_CPR = B_KMAJ ? T::BK / V : T::BN / V, B_ROWS = B_KMAJ ? T::BN : T::BK;
+    if (NT % A_CPR || NT % B_CPR) return false;
+    if (B_ROWS % (NT / B_CPR)) return false;
+    if (A_ROWS % (NT / A_CPR) && !A_KMAJ) return false;
+    if ((!B_KMAJ && B_CPR < 8) || (!A_KMAJ && A_CPR < 8)) return false;
+    return true;
+}
 
 // EDGEV: 0 = every loop divides (no remainder code); 1 = remainder code with the masked register
 // path compiled into the ring (kept for operands narrower than one access); 2 = the remainder
@@ -564,15 +587,15 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_direct_kernel(const KArgs
     constexpr bool A_KMAJ = AMODE != A_COL;
     constexpr int A_CPR = A_KMAJ ? BK / V : BM / V;   // 16-byte chunks per stored row of A
     constexpr int A_ROWS = A_KMAJ ? BM : BK;
-    constexpr int A_RPP = NT / A_CPR, PA = A_ROWS / A_RPP;
+    constexpr int A_RPP = NT / A_CPR, PA = (A_ROWS + A_RPP - 1) / A_RPP;
+    constexpr bool A_RAGGED = A_ROWS % A_RPP != 0;    // the last pass runs past the tile's rows
     constexpr int B_CPR = B_KMAJ ? BK / V : BN / V;   // and of B
     constexpr int B_ROWS = B_KMAJ ? BN : BK;
     constexpr int B_RPP = NT / B_CPR, PB = B_ROWS / B_RPP;
     constexpr int LPT = PA + PB;                       // direct loads per thread and step
-    static_assert(NT % A_CPR == 0 && A_ROWS % A_RPP == 0 && PA >= 1, "A staging shape");
-    static_assert(NT % B_CPR == 0 && B_ROWS % B_RPP == 0 && PB >= 1, "B staging shape");
+    static_assert(direct_mode_ok<T, MODE>(), "tile shape and address mode");
+    static_assert(PA * NT * V == L::A_ELEMS && PB * NT * V == L::B_ELEMS, "LDS stage layout");
     static_assert((D - 1) * LPT <= 63, "outstanding-load counter range");
-    static_assert((B_KMAJ || B_CPR >= 8) && (A_KMAJ || A_CPR >= 8), "the [k][j] swizzle permutes chunks in groups of eight");
     constexpr int K_CPR = BK / V;   // chunks per row of a k-contiguous tile
     constexpr int SW_MOD = K_CPR < 16 ? K_CPR : 16, SW_DIV = 16 / SW_MOD;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -638,9 +661,11 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_direct_kernel(const KArgs
 #pragma unroll
     for (int q = 0; q < PA; ++q) {
         const int row = a_r + q * A_RPP;
+        // (rows of the last pass beyond the tile: nobody reads them, they come from the block of zeros)
+        const bool pad_row = A_RAGGED && q == PA - 1 && row >= A_ROWS;
         if constexpr (AMODE == A_ROW) {
             a_k[q] = (a_cp ^ swz_k(row)) * V;
-            a_in[q] = !CUT || m0 + row < p.M;
+            a_in[q] = (!CUT || m0 + row < p.M) && !pad_row;
             a_src[q] = A + (long long)(CLAMP ? min(m0 + row, p.M - 1) : m0 + row) * p.lda + a_k[q];
         } else if constexpr (AMODE == A_COL) {
             a_k[q] = row;   // the stored row is the k index
@@ -650,7 +675,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_direct_kernel(const KArgs
         } else {
             a_k[q] = (a_cp ^ swz_k(row)) * V;
             const int m = m0 + row;
-            a_in[q] = !CUT || m < p.M;
+            a_in[q] = (!CUT || m < p.M) && !pad_row;
             a_src[q] = A;
             const int mm = CLAMP ? min(m, p.M - 1) : a_in[q] ? m : 0;
             // (non-negative: unsigned divisions)
@@ -960,7 +985,9 @@ hipError_t launch_mode(int variant, const KArgs& a, int batch, hipStream_t s) {
     const dim3 grid(a.split_first + (a.tiles_m * a.tiles_n - a.split_first) * a.split_k, batch, 1), block(T::NT, 1, 1);
     void (*fn)(const KArgs) = nullptr;
     int bytes, one_tap = 0;
-    if constexpr (T::SCHED >= 4) {
+    if constexpr (T::SCHED >= 4 && !direct_mode_ok<T, AMODE>()) {
+        return hipErrorInvalidValue;   // this tile shape does not exist for this operand layout
+    } else if constexpr (T::SCHED >= 4) {
         // the direct-to-LDS forms move whole 16-byte chunks only
         if (variant == 2) return hipErrorInvalidValue;
         bytes = LdsDirect<T>::BYTES;
@@ -995,6 +1022,17 @@ hipError_t launch_mode(int variant, const KArgs& a, int batch, hipStream_t s) {
     return hipGetLastError();
 }
 
+// bit m set: the tile exists for address mode m
+template <class T>
+constexpr int mode_mask_of() {
+    if constexpr (T::SCHED >= 4)
+        return (direct_mode_ok<T, A_ROW>() << A_ROW) | (direct_mode_ok<T, A_COL>() << A_COL) |
+               (direct_mode_ok<T, A_CONV>() << A_CONV) | (direct_mode_ok<T, A_ROW_BT>() << A_ROW_BT) |
+               (direct_mode_ok<T, A_COL_BT>() << A_COL_BT);
+    else
+        return T::E::kHasGeneral ? (1 << A_ROW) | (1 << A_COL) | (1 << A_CONV) : 0;
+}
+
 template <class T>
 constexpr int lds_bytes_of() {
     if constexpr (T::SCHED >= 4) return LdsDirect<T>::BYTES;
@@ -1023,7 +1061,12 @@ constexpr int lds_bytes_of() {
     X(F32, 128, 128, 32, 64, 64, 2, 4)   \
     X(F32, 256, 128, 16, 64, 64, 2, 4)   \
     X(F32, 256, 128, 16, 64, 64, 2, 5)   \
-    X(F32, 256, 256, 16, 128, 64, 2, 4)
+    X(F32, 256, 256, 16, 128, 64, 2, 4)  \
+    X(F32, 64, 64, 32, 32, 32, 2, 5)     \
+    X(F32B16, 112, 64, 32, 112, 16, 2, 4) \
+    X(F32B16, 112, 64, 32, 112, 16, 2, 5) \
+    X(F32B16, 112, 64, 64, 112, 16, 1, 4) \
+    X(F32B16, 64, 64, 32, 64, 16, 2, 4)
 
 #define TSG_BF16_TILES(X)                  \
     X(BF16, 256, 256, 64, 128, 64, 2, 0)   \
@@ -1063,4 +1106,5 @@ constexpr int lds_bytes_of() {
 // The table of a type's tiles (one translation unit per type defines it).
 #define TSG_TABLE_ENTRY(el, bm, bn, bk, wm, wn, mw, sc)                                                      \
     KernelEntry{bm, bn, bk, wm, wn, sc, el::BLK == 16 ? 1 : 0, Tile<el, bm, bn, bk, wm, wn, mw, sc>::NT, el::V, \
-                lds_bytes_of<Tile<el, bm, bn, bk, wm, wn, mw, sc>>(), &launch_any},
+                lds_bytes_of<Tile<el, bm, bn, bk, wm, wn, mw, sc>>(),                                           \
+                mode_mask_of<Tile<el, bm, bn, bk, wm, wn, mw, sc>>(), &launch_any},

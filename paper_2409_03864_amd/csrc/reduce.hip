@@ -5,9 +5,11 @@
 // (up to floating-point rounding order), so the reduce can read the tensor as it lies in
 // memory.  This is that reduce: one pass over the bytes, bound by HBM bandwidth.
 //
-// Order of summation (fixed by the launch, so results are repeatable): thread t of workgroup
-// b adds the 16-byte chunks b*256 + t + j*(G*256), j = 0, 1, ..., into four 4-wide partial
-// sums (chunk j goes to sum j % 4); the 16 lanes of those are added in index order; waves
+// Order of summation (fixed by the launch, so results are repeatable): the view's 16-byte
+// chunks are numbered in row-major order over (row, chunk within the row), so a workgroup's
+// share spans rows and a view of many short rows fills the chip like a contiguous tensor.
+// Thread t of workgroup b adds chunks b*256 + t + j*(G*256), j = 0, 1, ..., into four 4-wide
+// partial sums (chunk j goes to sum j % 4); the 16 lanes of those are added in index order; waves
 // reduce by halving (lane l += lane l + 32, 16, ..., 1), the four wave sums are added in
 // order, and the last workgroup to arrive adds the G workgroup sums the same way.
 #include <hip/hip_runtime.h>
@@ -70,19 +72,41 @@ __global__ void __launch_bounds__(kThreads) reduce_sum_kernel(const void* __rest
         }
     };
 
-    // each row is a contiguous run of `cols` elements (a contiguous tensor is one row)
-    const long long chunks = (cols + V - 1) / V;
+    // The view is rows of `cpr` chunks (the last chunk of a row may be short); chunk number c in
+    // row-major order over (row, chunk in row) is what the order of summation above counts.  A
+    // contiguous tensor arrives as one row.  The (row, chunk) pair of a thread's next chunk is
+    // stepped, not divided out: the stride of G*256 chunks is split once into whole rows and a
+    // remainder.
+    const long long cpr = (cols + V - 1) / V;
+    const long long total = rows * cpr;
     const long long stride = (long long)G * kThreads;
-    for (long long r = 0; r < rows; ++r) {
-        const char* row = (const char*)x + r * ld * (BF16 ? 2 : 4);
-        long long c = (long long)blockIdx.x * kThreads + tid;
-        int j = 0;
-        // four chunks in flight per thread
-        for (; c + 3 * stride < chunks; c += 4 * stride) {
+    const long long es = BF16 ? 2 : 4;
+    long long c = (long long)blockIdx.x * kThreads + tid;
+    long long r = c / cpr, cc = c - r * cpr;
+    const long long dr = stride / cpr, dc = stride - dr * cpr;
+    auto chunk_ptr = [&](long long row, long long ch) { return (const char*)x + (row * ld + ch * V) * es; };
+    auto advance = [&]() {
+        c += stride;
+        r += dr;
+        cc += dc;
+        if (cc >= cpr) { cc -= cpr; ++r; }
+    };
+    // four chunks in flight per thread
+    while (c + 3 * stride < total) {
+        const void* ptr[4];
+        long long valid[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) add_chunk(acc[u], row + (c + u * stride) * 16, cols - (c + u * stride) * V);
+        for (int u = 0; u < 4; ++u) {
+            ptr[u] = chunk_ptr(r, cc);
+            valid[u] = cols - cc * V;
+            advance();
         }
-        for (; c < chunks; c += stride, ++j) add_chunk(acc[j & 3], row + c * 16, cols - c * V);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) add_chunk(acc[u], ptr[u], valid[u]);
+    }
+    for (int j = 0; c < total; ++j) {
+        add_chunk(acc[j & 3], chunk_ptr(r, cc), cols - cc * V);
+        advance();
     }
     float v = 0.f;
 #pragma unroll
@@ -125,7 +149,7 @@ extern "C" tsg_status tsg_reduce_sum(tsg_dtype dtype, int64_t rows, int64_t cols
     if (rows > (int64_t)1 << 40 || cols > (int64_t)1 << 40 || rows * cols > (int64_t)1 << 40) return TSG_E_INVALID;
     if (ld == cols) { cols *= rows; ld = cols; rows = 1; }   // a contiguous tensor is one long row
     const int v = dtype == TSG_F32 ? 4 : 8;
-    const int64_t chunks = (cols + v - 1) / v;
+    const int64_t chunks = rows * ((cols + v - 1) / v);
     // enough workgroups to keep every CU streaming, each with at least 16 chunks per thread
     int64_t groups = chunks / (tsg::kThreads * 16);
     groups = groups < 1 ? 1 : groups > tsg::kMaxGroups ? tsg::kMaxGroups : groups;

@@ -53,7 +53,8 @@ struct KernelEntry {
     int mfma;        // MFMA block: 0 = 32 x 32, 1 = 16 x 16
     int threads;
     int vec;         // elements per 16-byte access for this dtype
-    int lds_bytes;   // LDS per workgroup (both stages, k-contiguous A layout)
+    int lds_bytes;   // LDS per workgroup (all stages, k-contiguous A layout)
+    int modes;       // bit m set: the tile exists for address mode m (AMode)
     // variant: 0 = vec, no remainder path; 1 = vec with remainder path; 3 = vec with the remainder
     // path that clamps and peels (every operand at least one access wide); 2 = scalar
     // accesses with remainder path

@@ -154,6 +154,9 @@ CONFIGS = {
     9: dict(op="gemm_trans", dtype="f32", M=4096, N=4096, K=4096, dist="normal", seed=8, flags=()),
     10: dict(op="conv2d_nhwc", dtype="f32", N=8, H=56, W=56, Cin=64, Cout=64, KH=3, KW=3,
              stride=1, pad=1, seed=9, flags=("accumulate",), window_ring=2),
+    # the same reduce on a view: 2^20 rows of 192 elements inside rows of 256 (three quarters of a
+    # 1 GiB buffer are summed, a quarter is skipped)
+    11: dict(op="reduce_sum", dtype="f32", rows=1 << 20, cols=192, ld=256, dist="uniform", seed=10, flags=()),
 }
 
 PAPER_BATCH_MATMUL = dict(B=6, M=196, N=256, K=2305)
@@ -163,7 +166,9 @@ def config_inputs(k: int):
     """Host arrays for workload configuration k (1-based)."""
     c = CONFIGS[k]
     if c["op"] == "reduce_sum":
-        return c, uniform_pm1(c["seed"], 0, c["rows"] * c["cols"]).reshape(c["rows"], c["cols"]), None
+        # the whole buffer is generated, rows of `ld` elements; the view is its first `cols` columns
+        ld = c.get("ld", c["cols"])
+        return c, uniform_pm1(c["seed"], 0, c["rows"] * ld).reshape(c["rows"], ld), None
     if c["op"] == "gemm_batched":
         # one stream per tensor: the batch index is the slowest dimension of A and of B
         a, b = gemm_inputs(c["B"] * c["M"], c["N"], c["K"], seed=c["seed"], dist=c["dist"])

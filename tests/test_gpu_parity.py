@@ -887,6 +887,45 @@ def test_search_budget_and_model_order():
     assert np.array_equal(dC.cpu().numpy().astype(np.float64), oracle.gemm(A, B, with_s=False))
 
 
+def test_search_adaptive_order_and_pruned_points_are_told_apart(workspace):
+    """Model-based order (2): the first timed point is still the cost model's pick, every
+    visited point is visited once, the winner is a timed point and a tuned call is exact.  In
+    the log a point that was not timed says why: -1 illegal here, -2 pruned."""
+    M, N, K = 384, 320, 512
+    A, B = inputs(M, N, K, 13, "ints", False, tsg.F32)
+    dA, dB = dev(A), dev(B)
+    dC = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+    try:
+        tsg.search_set(0, 1)
+        best1, ms1, log1 = tsg.autotune_gemm(tsg.F32, False, M, N, K, dA, K, dB, N, dC, N, iters=3, log_cap=2048)
+        assert {round(r.ms) for r in log1 if r.ms < 0} <= {-1, -2}
+        # scalar access in a direct-to-LDS form is illegal; nothing is pruned while the tiles cannot fill the chip
+        assert any(r.ms == -1 and r.config.vec == 1 and r.config.sched >= 4 for r in log1)
+        tsg.search_set(12, 2)
+        best2, ms2, log2 = tsg.autotune_gemm(tsg.F32, False, M, N, K, dA, K, dB, N, dC, N, iters=3, log_cap=2048)
+        timed = [r for r in log2 if r.ms >= 0]
+        assert len(timed) == 12
+        first1 = next(r for r in log1 if r.ms >= 0).config.as_dict()
+        assert timed[0].config.as_dict() == first1
+        keys = [tuple(r.config.as_dict().values()) for r in log2]
+        assert len(keys) == len(set(keys))
+        assert best2.as_dict() in [r.config.as_dict() for r in timed]
+        assert ms2 <= timed[0].ms
+        # 4096^2 outputs in 64 x 64 tiles fill the chip sixteen times over: splits of k are pruned there
+        tsg.search_set(0, 1)
+        a3 = torch.zeros((4096, 64), dtype=torch.float32, device=DEV)
+        b3 = torch.zeros((64, 4096), dtype=torch.float32, device=DEV)
+        c3 = torch.zeros((4096, 4096), dtype=torch.float32, device=DEV)
+        _, _, log3 = tsg.autotune_gemm(tsg.F32, False, 4096, 4096, 64, a3, 64, b3, 4096, c3, 4096, iters=1, log_cap=2048)
+        pruned = [r for r in log3 if r.ms == -2]
+        assert pruned and all(r.config.split_k > 1 and not r.config.split_tail for r in pruned)
+    finally:
+        tsg.search_set(0, 1)
+    tsg.gemm(tsg.F32, M, N, K, dA, K, dB, N, dC, N)
+    torch.cuda.synchronize()
+    assert np.array_equal(dC.cpu().numpy().astype(np.float64), oracle.gemm(A, B, with_s=False))
+
+
 # ------------------------------------------------------------------ full additive reduce
 
 REDUCE_TOL = 1e-5   # of the sum of magnitudes: ~100 sequential fp32 adds per partial sum at most
@@ -942,6 +981,47 @@ def test_reduce_sum_random_tolerance_repeatable_and_transpose_invariant(workspac
     out = torch.zeros((1,), dtype=torch.float32, device=DEV)
     with pytest.raises(tsg.SilenceableError):
         tsg.reduce_sum(tsg.F32, 3000, 1111, dev(x), 1111, out, tsg.STRICT)
+
+
+def test_reduce_sum_view_of_many_short_rows(workspace):
+    """2^16 rows of 24 elements inside rows of 32: the workgroups' shares span rows, so the view
+    fills the chip (integers: exact; random: within the bound; both repeatable), and so does a
+    view whose rows end in a short chunk."""
+    rows, cols, ld = 1 << 16, 24, 32
+    for dtype in (tsg.F32, tsg.BF16_F32ACC):
+        xi = synth.small_ints(61, 0, rows * ld).reshape(rows, ld)
+        h = synth.f32_to_bf16_bits(xi) if dtype == tsg.BF16_F32ACC else xi
+        out = torch.zeros((1,), dtype=torch.float32, device=DEV)
+        tsg.reduce_sum(dtype, rows, cols, dev(h), ld, out, tsg.STRICT)
+        torch.cuda.synchronize()
+        assert float(out.item()) == oracle.reduce_sum(np.ascontiguousarray(h[:, :cols]))[0]
+    x = synth.uniform_pm1(62, 0, rows * ld).reshape(rows, ld)
+    d = dev(x)
+    out = torch.zeros((1,), dtype=torch.float32, device=DEV)
+    got = []
+    for cols in (24, 23, 5):
+        ref, mag = oracle.reduce_sum(np.ascontiguousarray(x[:, :cols]))
+        for _ in range(2):
+            tsg.reduce_sum(tsg.F32, rows, cols, d, ld, out, tsg.STRICT)
+            torch.cuda.synchronize()
+            got.append(float(out.item()))
+        assert abs(got[-1] - ref) <= REDUCE_TOL * mag, (cols, got[-1], ref)
+        assert got[-1] == got[-2]
+
+
+def test_workload11_reduce_of_a_view_full_size(workspace):
+    """The benchmark's strided-view reduce at full size, in its launch configuration."""
+    c, x, _ = synth.config_inputs(11)
+    ref, mag = oracle.reduce_sum(np.ascontiguousarray(x[:, :c["cols"]]))
+    out = torch.zeros((1,), dtype=torch.float32, device=DEV)
+    d = dev(x)
+    tsg.reduce_sum(tsg.F32, c["rows"], c["cols"], d, c["ld"], out)
+    torch.cuda.synchronize()
+    assert abs(float(out.item()) - ref) <= REDUCE_TOL * mag
+    d.fill_(1.0)
+    tsg.reduce_sum(tsg.F32, c["rows"], c["cols"], d, c["ld"], out)
+    torch.cuda.synchronize()
+    assert float(out.item()) == float(c["rows"] * c["cols"])
 
 
 def test_workload7_full_reduce_one_gib(workspace):

@@ -40,6 +40,21 @@ def test_split_matches_paper_and_oracle(golden_dir):
         tsg.split(8, -1)
 
 
+def _direct_tile_exists(c, op, v):
+    """A tile of the direct-to-LDS forms is an array of 16-byte chunks dealt over the workgroup's
+    threads in whole passes: a stored row must divide a pass, and the rows must fill whole passes
+    unless the operand is the k-contiguous left one (its last pass is then padded)."""
+    nt = 64 * (c.bm // c.wm) * (c.bn // c.wn)
+    a_kmaj = op != tsg.OP_GEMM_TRANSA
+    a_cpr, a_rows = (c.bk // v, c.bm) if a_kmaj else (c.bm // v, c.bk)
+    b_cpr, b_rows = c.bn // v, c.bk
+    if nt % a_cpr or nt % b_cpr or b_rows % (nt // b_cpr):
+        return False
+    if a_rows % (nt // a_cpr) and not a_kmaj:
+        return False
+    return b_cpr >= 8 and (a_kmaj or a_cpr >= 8)
+
+
 def test_search_space_enumeration():
     for op in (tsg.OP_GEMM, tsg.OP_GEMM_TRANSA, tsg.OP_CONV2D_NHWC):
         for dt, vmax in ((tsg.F32, 4), (tsg.BF16_F32ACC, 8)):
@@ -48,20 +63,24 @@ def test_search_space_enumeration():
             seen = set()
             for i in range(n):
                 c = tsg.tile_config_enum(op, dt, i)
-                assert c.bm % c.wm == 0 and c.bn % c.wn == 0 and c.wm % 32 == 0 and c.wn % 32 == 0
-                assert c.vec in (1, vmax) and c.raster in (0, 1) and c.sched in (0, 4, 5) and c.mfma in (0, 1)
-                assert c.split_k in (1, 2, 4, 8, 16)
+                blk = 16 if c.mfma else 32
+                assert c.mfma in (0, 1) and (dt == tsg.F32 or c.mfma == 0)
+                assert c.bm % c.wm == 0 and c.bn % c.wn == 0 and c.wm % blk == 0 and c.wn % blk == 0
+                assert c.vec in (1, vmax) and c.raster in (0, 1) and c.sched in (0, 4, 5)
+                assert 1 <= c.split_k <= 16
                 key = tuple(c.as_dict().values())
                 assert key not in seen
                 seen.add(key)
-                # the direct-to-LDS forms (sched 4, 5) have no scalar-access variant
-                # and a tail-only split needs a tile count that leaves a tail after rounds of 256
+                # the direct-to-LDS forms (sched >= 4) have no scalar-access variant, some of their
+                # tiles do not exist for every operand layout, and a tail-only split needs a tile
+                # count that leaves a tail after rounds of 256
                 assert c.split_tail in (0, 1) and (c.split_k > 1 or not c.split_tail)
                 for ext in (4096, 4000 + 96 * 3):
                     tiles = -(-ext // c.bm) * -(-ext // c.bn)
-                    bad = (c.vec == 1 and c.sched >= 4) or (c.split_tail and tiles % 256 == 0)
+                    bad = ((c.vec == 1 and c.sched >= 4) or (c.split_tail and tiles % 256 == 0) or
+                           (c.sched >= 4 and not _direct_tile_exists(c, op, vmax)) or (c.sched == 0 and c.mfma == 1))
                     want = tsg.E_SILENCEABLE if bad else tsg.OK
-                    assert tsg.tile_config_check(op, dt, ext, ext, 4096, c, contig=64) == want
+                    assert tsg.tile_config_check(op, dt, ext, ext, 4096, c, contig=64) == want, (c, op, ext)
             with pytest.raises(tsg.TsgError):
                 tsg.tile_config_enum(op, dt, n)
     assert tsg.tile_config_count(7, 0) == 0
@@ -322,10 +341,12 @@ def test_tune_cache_save_load_roundtrip(tmp_path):
 
 
 def test_search_set_validates():
-    for bad in ((-1, 1), (0, 2), (0, -1)):
+    for bad in ((-1, 1), (0, 3), (0, -1)):
         with pytest.raises(tsg.TsgError) as e:
             tsg._check(tsg._lib.tsg_search_set(*bad), "tsg_search_set")
         assert e.value.status == tsg.E_INVALID
+    for order in (0, 1, 2):
+        tsg.search_set(5, order)
     tsg.search_set(0, True)
 
 
@@ -333,6 +354,7 @@ def test_status_strings():
     assert "ok" in tsg.status_string(tsg.OK)
     assert "silenceable" in tsg.status_string(tsg.E_SILENCEABLE)
     assert "definite" in tsg.status_string(tsg.E_INVALID) and "definite" in tsg.status_string(tsg.E_RUNTIME)
+    assert "definite" in tsg.status_string(tsg.E_TOO_LARGE) and "tsg_gemm_trans" in tsg.status_string(tsg.E_TOO_LARGE)
 
 
 def test_bench_counts_and_traffic_lookup(monkeypatch):
