@@ -234,7 +234,7 @@ tsg_status tsg_conv2d_nhwc_window(tsg_dtype dtype, int64_t N, int64_t H, int64_t
  * Case Study 3: a full additive reduce may ignore a reshape or transpose of its operand, so
  * a tensor is passed as it lies in memory, whatever view the program had of it (ld >= cols;
  * ld == cols means one contiguous run).  x, out: DEVICE pointers.  One workgroup per 16 K
- * elements, up to 2048; more than one needs the workspace (tsg_workspace_set) for the
+ * elements, up to 768; more than one needs the workspace (tsg_workspace_set) for the
  * workgroup sums: without it the call runs as one workgroup, or fails silenceably under
  * TSG_STRICT. */
 tsg_status tsg_reduce_sum(tsg_dtype dtype, int64_t rows, int64_t cols, const void *x, int64_t ld,

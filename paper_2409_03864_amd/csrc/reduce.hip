@@ -27,7 +27,7 @@ typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
 typedef u16x8 u16x8_u __attribute__((aligned(2)));
 
 constexpr int kThreads = 256;
-constexpr int kMaxGroups = 2048;
+constexpr int kMaxGroups = 768;   // three workgroups per compute unit: more resident waves lower the rate (768: 6.8, 1024: 6.7, 2048: 5.7 TB/s)
 
 __device__ __forceinline__ float bf16_bits_to_f32(unsigned short h) { return __uint_as_float((unsigned)h << 16); }
 
@@ -54,15 +54,17 @@ __global__ void __launch_bounds__(kThreads) reduce_sum_kernel(const void* __rest
 #pragma unroll
     for (int a = 0; a < 4; ++a) acc[a] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+    // Every byte is read once and never again: the loads are marked non-temporal, so the stream
+    // does not displace what the caches hold (measured on 1 GiB: 6.8 against 6.2 TB/s).
     auto add_chunk = [&](f32x4& a, const void* p, long long valid) {
         // `valid` elements of the chunk exist (>= V for a whole chunk)
         if (valid >= V) {
             if constexpr (BF16) {
-                const u16x8 h = *(const u16x8_u*)p;
+                const u16x8 h = __builtin_nontemporal_load((const u16x8_u*)p);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) a[e & 3] += bf16_bits_to_f32(h[e]);
             } else {
-                a += *(const f32x4_u*)p;
+                a += __builtin_nontemporal_load((const f32x4_u*)p);
             }
         } else {
             for (int e = 0; e < valid; ++e) {
@@ -82,31 +84,49 @@ __global__ void __launch_bounds__(kThreads) reduce_sum_kernel(const void* __rest
     const long long stride = (long long)G * kThreads;
     const long long es = BF16 ? 2 : 4;
     long long c = (long long)blockIdx.x * kThreads + tid;
-    long long r = c / cpr, cc = c - r * cpr;
-    const long long dr = stride / cpr, dc = stride - dr * cpr;
-    auto chunk_ptr = [&](long long row, long long ch) { return (const char*)x + (row * ld + ch * V) * es; };
-    auto advance = [&]() {
-        c += stride;
-        r += dr;
-        cc += dc;
-        if (cc >= cpr) { cc -= cpr; ++r; }
-    };
-    // four chunks in flight per thread
-    while (c + 3 * stride < total) {
-        const void* ptr[4];
-        long long valid[4];
+    if (rows == 1 && cols % V == 0) {
+        // one contiguous run of whole chunks: nothing to step but the chunk number
+        const char* base = (const char*)x;
+        for (; c + 3 * stride < total; c += 4 * stride) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            ptr[u] = chunk_ptr(r, cc);
-            valid[u] = cols - cc * V;
+            for (int u = 0; u < 4; ++u) add_chunk(acc[u], base + (c + u * stride) * 16, V);
+        }
+        for (int j = 0; c < total; c += stride, ++j) add_chunk(acc[j & 3], base + c * 16, V);
+    } else {
+        long long r = c / cpr, cc = c - r * cpr;
+        const long long dr = stride / cpr, dc = stride - dr * cpr;
+        const char* ptr = (const char*)x + (r * ld + cc * V) * es;
+        const long long step_bytes = (dr * ld + dc * V) * es, wrap_bytes = (ld - cpr * V) * es;
+        auto advance = [&]() {
+            c += stride;
+            ptr += step_bytes;
+            cc += dc;
+            if (cc >= cpr) { cc -= cpr; ptr += wrap_bytes; }
+        };
+        // four chunks in flight per thread
+        while (c + 3 * stride < total) {
+            const void* p4[4];
+            long long valid[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                p4[u] = ptr;
+                valid[u] = cols - cc * V;
+                advance();
+            }
+            // (whole chunks, the usual case, are loaded together; a short chunk at the end of a
+            // row takes the element loop)
+            if (valid[0] >= V && valid[1] >= V && valid[2] >= V && valid[3] >= V) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) add_chunk(acc[u], p4[u], V);
+            } else {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) add_chunk(acc[u], p4[u], valid[u]);
+            }
+        }
+        for (int j = 0; c < total; ++j) {
+            add_chunk(acc[j & 3], ptr, cols - cc * V);
             advance();
         }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) add_chunk(acc[u], ptr[u], valid[u]);
-    }
-    for (int j = 0; c < total; ++j) {
-        add_chunk(acc[j & 3], chunk_ptr(r, cc), cols - cc * V);
-        advance();
     }
     float v = 0.f;
 #pragma unroll
