@@ -101,6 +101,124 @@ __device__ __forceinline__ void k_range(int nk_all, int split, int nsplit, int& 
     }
 }
 
+// Where a run of four accumulator rows starts in a window of a larger NHWC tensor: element
+// offset of its first pixel, and that pixel's (wo, ho).  A lane's runs lie a fixed number of rows
+// apart down its wave tile (8 with 32 x 32 blocks, 16 with 16 x 16), so only the first is decoded
+// with divisions (about forty four-cycle instructions each, which made the windowed epilogue a
+// microsecond longer than the plain one); the others step from it, wrapping wo and ho.
+struct RunStart { long long off; int wo, ho; };
+
+template <class T>
+struct WindowCursor {
+    RunStart cur;
+    bool started = false;
+    // the run that starts at row `row`; calls come in increasing row order, `step` rows apart
+    __device__ __forceinline__ void next(const KArgs& p, int row, RunStart& out) {
+        constexpr int STEP = T::E::BLK == 32 ? 8 : 16;
+        static_assert(T::E::BLK == 32 ? T::E::NACC == 16 : T::E::NACC == 4, "accumulator rows per block");
+        if (!started) {
+            // (non-negative: unsigned divisions)
+            const unsigned tq = (unsigned)row / (unsigned)p.Wo, nq = tq / (unsigned)p.Ho;
+            cur.wo = row - (int)tq * p.Wo;
+            cur.ho = (int)(tq - nq * (unsigned)p.Ho);
+            cur.off = (long long)nq * p.y_sn + (long long)cur.ho * p.y_sh + (long long)cur.wo * p.y_sw;
+            started = true;
+        } else {
+            const long long wrap_w = p.y_sh - (long long)p.Wo * p.y_sw, wrap_h = p.y_sn - (long long)p.Ho * p.y_sh;
+            cur.wo += STEP;
+            cur.off += STEP * p.y_sw;
+            while (cur.wo >= p.Wo) {
+                cur.wo -= p.Wo;
+                cur.off += wrap_w;
+                if (++cur.ho == p.Ho) { cur.ho = 0; cur.off += wrap_h; }
+            }
+        }
+        out = cur;
+    }
+    // the run starts of block row i of the wave tile (nothing to do for a plain matrix)
+    __device__ __forceinline__ void block(const KArgs& p, int m0, int wm0, int i, RunStart (&rs)[T::E::NACC / 4]) {
+        if (!p.y_window) return;
+        const int lane = threadIdx.x & 63;
+#pragma unroll
+        for (int rg = 0; rg < T::E::NACC / 4; ++rg) next(p, m0 + wm0 + i * T::E::BLK + T::E::acc_row(4 * rg, lane), rs[rg]);
+    }
+};
+
+// The outputs a lane holds for MFMA block (i, j) of its wave tile, in accumulator order:
+// f(r, address of the element, whether it lies inside C).  The rows of a run of four registers
+// are consecutive and runs lie 8 rows apart: in a plain matrix the row pointer steps, no
+// multiply per element; in a window of a larger NHWC tensor the first row of a run is decoded
+// to (n, ho, wo) and the others step from it.
+template <class T, bool CHECK, class F>
+__device__ __forceinline__ void visit_block(const KArgs& p, float* __restrict__ C, int m0, int n0, int wm0, int wn0,
+                                            int i, int j, const RunStart (&rs)[T::E::NACC / 4], F&& f) {
+    using E = typename T::E;
+    constexpr int BLK = E::BLK, NACC = E::NACC;
+    const int lane = threadIdx.x & 63;
+    const int col = n0 + wn0 + j * BLK + (lane & (BLK - 1));
+    const int row_b = m0 + wm0 + i * BLK;
+    if (p.y_window) {
+        const long long wrap_w = p.y_sh - (long long)p.Wo * p.y_sw, wrap_h = p.y_sn - (long long)p.Ho * p.y_sh;
+#pragma unroll
+        for (int rg = 0; rg < NACC / 4; ++rg) {
+            const int row0 = row_b + E::acc_row(4 * rg, lane);
+            int wo = rs[rg].wo, ho = rs[rg].ho;
+            float* ptr = C + rs[rg].off + col;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                f(4 * rg + e, ptr, !CHECK || (row0 + e < p.M && col < p.N));
+                ptr += p.y_sw;
+                if (++wo == p.Wo) {
+                    wo = 0;
+                    ptr += wrap_w;
+                    if (++ho == p.Ho) { ho = 0; ptr += wrap_h; }
+                }
+            }
+        }
+        return;
+    }
+    float* rp = C + (long long)(row_b + E::acc_row(0, lane)) * p.ldc + col;   // row of r = 0
+#pragma unroll
+    for (int r = 0; r < NACC; ++r) {
+        f(r, rp, !CHECK || (row_b + E::acc_row(r, lane) < p.M && col < p.N));
+        rp += (r & 3) == 3 ? 5 * p.ldc : p.ldc;
+    }
+}
+
+// The old values of C for `C += ...` (the form of Fig. 7), fetched BEFORE the k loop by tiles
+// small enough to spare the registers: the epilogue of a small tile is a large part of its run
+// time, and reading the old values there added a round trip to memory to it.  Nobody else
+// writes this tile of C during the launch, so the early read sees the same values.  Not used
+// when k is split: only the last arrival adds the old values, and it is not known in advance.
+template <class T>
+struct OldC {
+    static constexpr bool ON = T::MI * T::NI * T::E::NACC <= 32;
+    float v[ON ? T::MI : 1][ON ? T::NI : 1][ON ? T::E::NACC : 1];
+    bool loaded = false;
+
+    __device__ __forceinline__ void fetch(const KArgs& p, float* __restrict__ C, int m0, int n0, int wm0, int wn0,
+                                          bool interior, int nsplit) {
+        if constexpr (ON) {
+            if (!(p.flags & FLAG_ACCUMULATE) || nsplit > 1) return;
+            loaded = true;
+            WindowCursor<T> wc;
+#pragma unroll
+            for (int i = 0; i < T::MI; ++i) {
+                RunStart rs[T::E::NACC / 4];
+                wc.block(p, m0, wm0, i, rs);
+#pragma unroll
+                for (int j = 0; j < T::NI; ++j) {
+                    if (interior)
+                        visit_block<T, false>(p, C, m0, n0, wm0, wn0, i, j, rs, [&](int r, float* ptr, bool) { v[i][j][r] = *ptr; });
+                    else
+                        visit_block<T, true>(p, C, m0, n0, wm0, wn0, i, j, rs,
+                                             [&](int r, float* ptr, bool ok) { v[i][j][r] = ok ? *ptr : 0.f; });
+                }
+            }
+        }
+    }
+};
+
 // What follows the k loop.  Split k: park the partial tile, count the arrival, and let the
 // last arrival add the partials in split order.  Epilogue: sign, optional accumulate, masked
 // at the remainder, optionally addressed into a window of a larger NHWC tensor.
@@ -118,10 +236,10 @@ __device__ __forceinline__ void k_range(int nk_all, int split, int nsplit, int& 
 template <class T>
 __device__ __forceinline__ void finish_tile(const KArgs& p, typename T::E::acc_t (&acc)[T::MI][T::NI],
                                             float* __restrict__ C, int slot, int split, int nsplit, int m0, int n0,
-                                            int wm0, int wn0, bool interior) {
+                                            int wm0, int wn0, bool interior, const OldC<T>& oldc) {
     using E = typename T::E;
-    constexpr int BM = T::BM, BN = T::BN, NT = T::NT, MI = T::MI, NI = T::NI, BLK = E::BLK, NACC = E::NACC;
-    const int tid = threadIdx.x, lane = tid & 63, li = lane & (BLK - 1);
+    constexpr int BM = T::BM, BN = T::BN, NT = T::NT, MI = T::MI, NI = T::NI, NACC = E::NACC;
+    const int tid = threadIdx.x;
     if (nsplit > 1) {
         __shared__ int arrived;
         float* ws = p.ws + (long long)slot * nsplit * (BM * BN);
@@ -164,84 +282,41 @@ __device__ __forceinline__ void finish_tile(const KArgs& p, typename T::E::acc_t
 
     // With ACCUMULATE the old values of a block are all loaded before its first store: a load
     // behind a store to an address the compiler cannot tell apart would wait for it, one round
-    // trip to memory per element.
+    // trip to memory per element.  Small tiles bring them in before the k loop (OldC).
     const bool neg = p.flags & FLAG_NEGATE, accum = p.flags & FLAG_ACCUMULATE;
     // The bounds tests and the read of the old values are compiled into copies of their own,
     // chosen once per tile: with the tests beside every element an interior tile of the
     // remainder variant spent three times as long here.
     auto emit = [&](auto check_tag, auto accum_tag) {
         constexpr bool CHECK = decltype(check_tag)::value, ACCUM = decltype(accum_tag)::value;
-        // a lane holds its accumulators as runs of four consecutive rows
-        constexpr int RUNS = NACC / 4;
-        if (p.y_window) {
-            // output pixel row -> (n, ho, wo) -> its place in the larger tensor: the first row of a
-            // run is decoded, the others step from it
+        WindowCursor<T> wc;
 #pragma unroll
-            for (int i = 0; i < MI; ++i)
-#pragma unroll
-                for (int rg = 0; rg < RUNS; ++rg) {
-                    const int row0 = m0 + wm0 + i * BLK + E::acc_row(4 * rg, lane);
-                    // (non-negative: unsigned divisions)
-                    const unsigned tq = (unsigned)row0 / (unsigned)p.Wo, nq = tq / (unsigned)p.Ho;
-                    int wo = row0 - (int)tq * p.Wo, ho = (int)(tq - nq * (unsigned)p.Ho), n = (int)nq;
-                    float* dst[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        dst[e] = C + ((long long)n * p.y_sn + (long long)ho * p.y_sh + (long long)wo * p.y_sw) + n0 + wn0 + li;
-                        if (++wo == p.Wo) {
-                            wo = 0;
-                            if (++ho == p.Ho) { ho = 0; ++n; }
-                        }
-                    }
-                    float old[4][NI];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-#pragma unroll
-                        for (int j = 0; j < NI; ++j) {
-                            const bool ok = !CHECK || (row0 + e < p.M && n0 + wn0 + j * BLK + li < p.N);
-                            old[e][j] = (ACCUM && ok) ? dst[e][j * BLK] : 0.f;
-                        }
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-#pragma unroll
-                        for (int j = 0; j < NI; ++j) {
-                            const bool ok = !CHECK || (row0 + e < p.M && n0 + wn0 + j * BLK + li < p.N);
-                            const float v = acc[i][j][rg * 4 + e];
-                            const float sv = neg ? -v : v;
-                            if (ok) dst[e][j * BLK] = ACCUM ? sv + old[e][j] : sv;   // no add without the flag: -0 stays -0
-                        }
-                }
-            return;
-        }
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
+        for (int i = 0; i < MI; ++i) {
+            RunStart rs[NACC / 4];
+            wc.block(p, m0, wm0, i, rs);
 #pragma unroll
             for (int j = 0; j < NI; ++j) {
-                const int col = n0 + wn0 + j * BLK + li;
-                const int row_b = m0 + wm0 + i * BLK;
-                float* c0 = C + (long long)(row_b + E::acc_row(0, lane)) * p.ldc + col;   // row of r = 0
-                // the rows of a run are consecutive and runs lie 8 rows apart: the row pointer steps,
-                // no multiply per element
                 float old[NACC];
                 if constexpr (ACCUM) {
-                    float* rp = c0;
+                    bool have = false;
+                    if constexpr (OldC<T>::ON) {
+                        if (oldc.loaded) {
+                            have = true;
 #pragma unroll
-                    for (int r = 0; r < NACC; ++r) {
-                        const bool ok = !CHECK || (row_b + E::acc_row(r, lane) < p.M && col < p.N);
-                        old[r] = ok ? *rp : 0.f;
-                        rp += (r & 3) == 3 ? 5 * p.ldc : p.ldc;
+                            for (int r = 0; r < NACC; ++r) old[r] = oldc.v[i][j][r];
+                        }
                     }
+                    if (!have)
+                        visit_block<T, CHECK>(p, C, m0, n0, wm0, wn0, i, j, rs,
+                                              [&](int r, float* ptr, bool ok) { old[r] = ok ? *ptr : 0.f; });
                 }
-                float* rp = c0;
-#pragma unroll
-                for (int r = 0; r < NACC; ++r) {
-                    const bool ok = !CHECK || (row_b + E::acc_row(r, lane) < p.M && col < p.N);
+                visit_block<T, CHECK>(p, C, m0, n0, wm0, wn0, i, j, rs, [&](int r, float* ptr, bool ok) {
                     const float v = acc[i][j][r];
                     const float sv = neg ? -v : v;
-                    if (ok) *rp = ACCUM ? sv + old[r] : sv;   // no add without the flag: -0 stays -0
-                    rp += (r & 3) == 3 ? 5 * p.ldc : p.ldc;
-                }
+                    if (ok) *ptr = ACCUM ? sv + old[r] : sv;   // no add without the flag: -0 stays -0
+                });
             }
+        }
     };
     if (interior) {
         if (accum) emit(std::false_type{}, std::true_type{});
@@ -491,7 +566,8 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_staged_kernel(const KArgs
         __syncthreads();
     }
 
-    finish_tile<T>(p, acc, C, slot, split, nsplit, m0, n0, wm0, wn0, interior);
+    OldC<T> oldc;
+    finish_tile<T>(p, acc, C, slot, split, nsplit, m0, n0, wm0, wn0, interior, oldc);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -658,6 +734,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_direct_kernel(const KArgs
     bool a_in[PA];        // the chunk's row (A_ROW: m, A_COL: m range) lies inside the operand
     int cv_base[PA], cv_hi0[PA], cv_wi0[PA];
     long long cv_off[PA];   // element offset of tap (0, 0), channel a_k of the chunk's pixel (may lie outside the tensor)
+    int px_n = 0, px_ho = 0, px_wo = 0;
 #pragma unroll
     for (int q = 0; q < PA; ++q) {
         const int row = a_r + q * A_RPP;
@@ -677,13 +754,24 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_direct_kernel(const KArgs
             const int m = m0 + row;
             a_in[q] = (!CUT || m < p.M) && !pad_row;
             a_src[q] = A;
-            const int mm = CLAMP ? min(m, p.M - 1) : a_in[q] ? m : 0;
-            // (non-negative: unsigned divisions)
-            const unsigned tq = (unsigned)mm / (unsigned)p.Wo, nq = tq / (unsigned)p.Ho;
-            const int wo = mm - (int)tq * p.Wo, ho = (int)(tq - nq * (unsigned)p.Ho), n = (int)nq;
-            cv_base[q] = n * p.H;
-            cv_hi0[q] = ho * p.sh - p.ph;
-            cv_wi0[q] = wo * p.sw - p.pw;
+            // The thread's first pixel is decoded with divisions (about forty four-cycle
+            // instructions each); its other pixels lie A_RPP rows further on each and step from it.
+            // A row past the last pixel reads as padding for every tap.
+            if (q == 0) {
+                const unsigned tq = (unsigned)m / (unsigned)p.Wo, nq = tq / (unsigned)p.Ho;
+                px_wo = m - (int)tq * p.Wo;
+                px_ho = (int)(tq - nq * (unsigned)p.Ho);
+                px_n = (int)nq;
+            } else {
+                px_wo += A_RPP;
+                while (px_wo >= p.Wo) {
+                    px_wo -= p.Wo;
+                    if (++px_ho == p.Ho) { px_ho = 0; ++px_n; }
+                }
+            }
+            cv_base[q] = px_n * p.H;
+            cv_hi0[q] = m < p.M ? px_ho * p.sh - p.ph : -(1 << 28);
+            cv_wi0[q] = px_wo * p.sw - p.pw;
             cv_off[q] = ((long long)(cv_base[q] + cv_hi0[q]) * p.W + cv_wi0[q]) * p.Cin + a_k[q];
         }
     }
@@ -879,6 +967,10 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_direct_kernel(const KArgs
     // the barrier) and everybody has left step kt-1, so during that last group the loads of
     // tile kt+D go into the stage step kt-1 used and the first fragments of step kt+1 are
     // fetched.  No wave ever starts a step, or leaves a barrier, with its MFMA operands missing.
+    // (the old values of C, for small tiles: ordinary loads, older than every load of the ring, so
+    // the ring's counted waits only become stricter until they have landed)
+    OldC<T> oldc;
+    oldc.fetch(p, C, m0, n0, wm0, wn0, interior, nsplit);
     for (int t = 0; t < D; ++t)
         if (t < nkp) issue(t, t);
     if (D <= n_direct) wait_loads_outstanding<(D - 1) * LPT>();
@@ -976,7 +1068,7 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_direct_kernel(const KArgs
             }
         }
     }
-    finish_tile<T>(p, acc, C, slot, split, nsplit, m0, n0, wm0, wn0, interior);
+    finish_tile<T>(p, acc, C, slot, split, nsplit, m0, n0, wm0, wn0, interior, oldc);
 }
 
 template <class T, int AMODE>
