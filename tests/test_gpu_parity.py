@@ -743,6 +743,53 @@ def test_config4_conv_tail_only_split_full_size(workspace):
     assert np.array_equal(y2.view(np.uint32), y.view(np.uint32))
 
 
+def test_bench_launch_configurations_of_the_small_workloads_full_size(workspace):
+    """The tile configs the tuner settles on for the layer and for the paper's batched nest, pinned,
+    at full size: 112-row tiles of 16 x 16 MFMA blocks with a k step of 64 for the layer (plain, and
+    added into the interior of a larger tensor), 64 x 64 tiles with k split five ways for the batch.
+    Integer data bit for bit, then the workload's own data within tolerance."""
+    dt = tsg.F32
+    conv_cfg = tsg.TileConfig(bm=112, bn=64, bk=64, wm=112, wn=16, vec=4, raster=0, sched=4, split_k=1, split_tail=0, mfma=1)
+    assert tsg.tile_config_check(tsg.OP_CONV2D_NHWC, dt, 25088, 64, 576, conv_cfg, contig=64) == tsg.OK
+    tsg.tile_config_set(tsg.OP_CONV2D_NHWC, dt, conv_cfg)
+    xi, wi = synth.conv_inputs(8, 56, 56, 64, 64, 3, 3, seed=6, dist="ints")
+    Ri = oracle.conv2d_nhwc(xi, wi, pad=(1, 1), with_s=False)
+    yi = run_conv(dt, xi, wi, (1, 1), (1, 1), flags=tsg.STRICT)
+    li = tsg.last_launch()
+    assert li.alternative == 0 and li.config.mfma == 1 and li.tiles_m == 224 and li.edge == 0
+    assert np.array_equal(yi.astype(np.float64), Ri)
+    c, x, w = synth.config_inputs(4)
+    R, S = oracle.conv2d_nhwc(x, w, pad=(1, 1))
+    gate("config 4, tuned tile", run_conv(dt, x, w, (1, 1), (1, 1), flags=tsg.STRICT), R, S, 1e-4)
+    # the same tile adding into a window (workload 10): integers exact everywhere, ring untouched
+    ring, Ho, Co = 2, 56, 64
+    big0 = synth.small_ints(14, 3, 8 * (Ho + 2 * ring) ** 2 * Co).reshape(8, Ho + 2 * ring, Ho + 2 * ring, Co)
+    dbig = dev(big0)
+    sw_, sh_ = Co, (Ho + 2 * ring) * Co
+    sn_ = (Ho + 2 * ring) * sh_
+    tsg.conv2d_nhwc_window(dt, 8, 56, 56, 64, 64, 3, 3, 1, 1, 1, 1, dev(xi), dev(wi),
+                           dbig.data_ptr() + 4 * (ring * sh_ + ring * sw_), sn_, sh_, sw_, tsg.ACCUMULATE | tsg.STRICT)
+    torch.cuda.synchronize()
+    assert tsg.last_launch().config.as_dict() == conv_cfg.as_dict()
+    assert np.array_equal(dbig.cpu().numpy().astype(np.float64), oracle.add_of_zero_pad(big0, Ri, (0, ring, ring, 0)))
+    tsg.tile_config_set(tsg.OP_CONV2D_NHWC, dt, None)
+    # the paper's batched nest, k split five ways
+    P = synth.PAPER_BATCH_MATMUL
+    Bt, M, N, K = P["B"], P["M"], P["N"], P["K"]
+    gemm_cfg = tsg.TileConfig(bm=64, bn=64, bk=32, wm=32, wn=32, vec=4, raster=0, sched=4, split_k=5, split_tail=0)
+    tsg.tile_config_set(tsg.OP_GEMM, dt, gemm_cfg)
+    for dist, exact in (("ints", True), ("uniform", False)):
+        A = np.stack([synth.gemm_inputs(M, N, K, seed=70 + b, dist=dist)[0] for b in range(Bt)])
+        B = np.stack([synth.gemm_inputs(M, N, K, seed=70 + b, dist=dist)[1] for b in range(Bt)])
+        dC = torch.full((Bt, M, N), 9.0, dtype=torch.float32, device=DEV)
+        tsg.gemm_batched(dt, False, Bt, M, N, K, dev(A), K, M * K, dev(B), N, K * N, dC, N, M * N, tsg.STRICT)
+        torch.cuda.synchronize()
+        assert tsg.last_launch().config.split_k == 5
+        C = dC.cpu().numpy()
+        for b in range(Bt):
+            check(C[b], A[b], B[b], dt, exact=exact)
+
+
 def test_config5_bf16_gemm_8192_negated_full_oracle():
     """bf16 8192^3 with the negate fused: every element against the oracle on the workload's own
     data; integer-valued operands at full size, bit for bit (any indexing, swizzle or
