@@ -383,6 +383,12 @@ tsg_status tsg_tune_cache_load(const char *path, int32_t *loaded, int32_t *rejec
 tsg_status tsg_mfma_ceiling(tsg_dtype dtype, int32_t mfma, int32_t random_operands, int32_t waves_per_simd,
                             int32_t launches, float *sink, int64_t sink_bytes, float *tflops, void *stream);
 
+/* Measurement aid for the small shapes: the time per launch, in microseconds (HOST float), of
+ * `launches` (1..1000000) back-to-back launches of a kernel that does nothing, between two
+ * events on `stream`: the cost that every compute call of this library pays before its first
+ * instruction.  SYNCHRONISES. */
+tsg_status tsg_launch_floor(int32_t launches, float *us_per_launch, void *stream);
+
 const char *tsg_status_string(tsg_status s);
 int32_t tsg_version(void);
 

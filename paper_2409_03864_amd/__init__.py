@@ -71,6 +71,7 @@ def _load():
         "tsg_conv2d_nhwc_window": [i32] + [i64] * 11 + [vp, vp, vp, i64, i64, i64, u32, vp],
         "tsg_reduce_sum": [i32, i64, i64, vp, i64, vp, u32, vp],
         "tsg_mfma_ceiling": [i32, i32, i32, i32, i32, vp, i64, ctypes.POINTER(ctypes.c_float), vp],
+        "tsg_launch_floor": [i32, ctypes.POINTER(ctypes.c_float), vp],
         "tsg_split": [i64, i64, vp, vp, vp],
         "tsg_tile_config_enum": [i32, i32, i32, cfgp],
         "tsg_tile_config_check": [i32, i32, i64, i64, i64, i64, cfgp],
@@ -118,7 +119,7 @@ def _load():
 _lib = _load()
 
 EXPORTS = ("tsg_gemm", "tsg_gemm_transA", "tsg_gemm_batched", "tsg_gemm_trans", "tsg_gemm_trans_static", "tsg_autotune_gemm_trans", "tsg_conv2d_nhwc", "tsg_conv2d_nhwc_window",
-           "tsg_reduce_sum", "tsg_mfma_ceiling", "tsg_split",
+           "tsg_reduce_sum", "tsg_mfma_ceiling", "tsg_launch_floor", "tsg_split",
            "tsg_tile_config_count", "tsg_tile_config_enum", "tsg_tile_config_check",
            "tsg_tile_config_set", "tsg_tile_config_get", "tsg_last_launch", "tsg_workspace_set",
            "tsg_workspace_set_stream", "tsg_workspace_bytes", "tsg_search_set", "tsg_tune_cache_size", "tsg_tune_cache_clear",
@@ -217,6 +218,13 @@ def mfma_ceiling(dtype, mfma, random_operands, waves_per_simd, launches, sink, s
     _check(_lib.tsg_mfma_ceiling(dtype, mfma, int(bool(random_operands)), waves_per_simd, launches, _ptr(sink),
                                  sink.numel() * sink.element_size(), out, _stream(stream)), "tsg_mfma_ceiling")
     return float(out[0]), float(out[1])
+
+
+def launch_floor(launches=20000, stream=None):
+    """Microseconds per launch of an empty kernel, back to back on one stream."""
+    out = ctypes.c_float()
+    _check(_lib.tsg_launch_floor(launches, ctypes.byref(out), _stream(stream)), "tsg_launch_floor")
+    return float(out.value)
 
 
 # ---- schedule parameters (host only) -----------------------------------------------

@@ -79,8 +79,34 @@ __global__ void __launch_bounds__(256) mfma_loop(float* sink, int iters, int ran
     sink[t] = s;
 }
 
+// the fixed cost of a launch: a kernel whose one wave returns at once
+__global__ void empty_kernel() {}
+
 }  // namespace
 }  // namespace tsg
+
+extern "C" tsg_status tsg_launch_floor(int32_t launches, float* us_per_launch, void* stream) {
+    if (launches < 1 || launches > 1000000 || !us_per_launch) return TSG_E_INVALID;
+    hipStream_t s = (hipStream_t)stream;
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return TSG_E_RUNTIME;
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return TSG_E_RUNTIME; }
+    tsg_status st = TSG_OK;
+    float ms = 0.f;
+    // two passes: the first one also pays for loading the code object
+    for (int pass = 0; pass < 2 && st == TSG_OK; ++pass) {
+        if (hipEventRecord(e0, s) != hipSuccess) { st = TSG_E_RUNTIME; break; }
+        for (int l = 0; l < launches; ++l) hipLaunchKernelGGL(tsg::empty_kernel, dim3(1), dim3(64), 0, s);
+        if (hipGetLastError() != hipSuccess || hipEventRecord(e1, s) != hipSuccess ||
+            hipEventSynchronize(e1) != hipSuccess || hipEventElapsedTime(&ms, e0, e1) != hipSuccess)
+            st = TSG_E_RUNTIME;
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (st != TSG_OK) return st;
+    *us_per_launch = ms * 1000.f / launches;
+    return TSG_OK;
+}
 
 extern "C" tsg_status tsg_mfma_ceiling(tsg_dtype dtype, int32_t mfma, int32_t random_operands, int32_t waves_per_simd,
                                        int32_t launches, float* sink, int64_t sink_bytes, float* tflops,
