@@ -19,7 +19,9 @@
  *
  * Pins (tests marked "not gpu"): identity and all-ones closed forms, one-hot
  * locality probes, A^T.B = (B^T.A)^T, explicit zero padding, literal Python
- * brute force on tiny integer inputs, and numpy's fp64 matmul.
+ * brute force on tiny integer inputs, and numpy's fp64 matmul.  The bf16 branch of
+ * the convolution has pins of its own: bf16 bit patterns must give exactly what
+ * the same values give as fp32, and a brute-force geometry on bf16 inputs.
  */
 #include <math.h>
 #include <stdint.h>
