@@ -102,7 +102,12 @@ enum {
  *   sched      : kernel form: 0 = operand tiles staged through registers into two padded LDS
  *                stages, instruction order left to the compiler (serves every access width);
  *                4 / 5 = operand tiles loaded from global memory straight into a ring of
- *                3 / 4 LDS stages (two / three k steps in flight), wide accesses only.
+ *                3 / 4 LDS stages (two / three k steps in flight), wide accesses only;
+ *                1 = one MFMA block of C per workgroup (bm = bn = wm = wn = 16 or 32), the k
+ *                loop dealt over its four wavefronts and operands loaded straight into
+ *                registers: for products too small to give every compute unit a tile (the
+ *                inner fixed-size matmul of Fig. 8 taken as the whole tile); fp32 matrices
+ *                only, split_k must be 1.
  *                -1 = library default.  Only (tile, sched) pairs that are instantiated are
  *                legal.
  *   split_k    : number of workgroups that share one tile of C, each taking a contiguous
@@ -174,7 +179,7 @@ tsg_status tsg_gemm_batched(tsg_dtype dtype, int32_t trans_a, int64_t batch,
 /* The general form: either operand, or both, stored transposed and read in place (Case
  * Study 3: transposes folded into a matmul that takes transposed operands).  trans_a: A is
  * K x M (lda >= M); trans_b: B is N x K (ldb >= K).  Batched like tsg_gemm_batched.  A
- * transposed B is served by the direct-to-LDS kernel forms only (sched 4, 5): a pinned config
+ * transposed B is served by the direct-to-LDS kernel forms (sched 4, 5) and the block form (sched 1): a pinned config
  * of another form is a silenceable failure and the library's default for the shape is used. */
 tsg_status tsg_gemm_trans(tsg_dtype dtype, int32_t trans_a, int32_t trans_b, int64_t batch,
                           int64_t M, int64_t N, int64_t K,

@@ -173,6 +173,22 @@ constexpr double kModelLaunch = 7682.0;      // launch, first loads and epilogue
 double model_core(tsg_dtype dt, const KernelEntry& e, double ntiles, int split, int64_t K) {
     const double kLatency = 2324.0;     // cycles from issuing a tile's loads to LDS-ready
     const double kLds = 160.0 * 1024;
+    if (e.sched == 1) {
+        // One block per workgroup, one wave per SIMD: a wave takes every fourth k group, sixteen
+        // groups per workgroup in flight together.  A batch of sixteen groups costs one exposed
+        // latency (operands that small sit in L2: about 1000 cycles) when a CU holds a single
+        // workgroup; with several they overlap, and the CU is bound by its MFMA time or, sooner, by
+        // the operand bytes it draws from L2: nothing is shared between blocks, 32 KiB per batch
+        // at 14 (32 x 32 blocks) to 18.5 (16 x 16) bytes per cycle and CU.  Fitted on 128^3 .. 2048^3,
+        // 64 x 64 x 4096, 256 x 256 x 2048: within 15 % of the measured time on those.
+        const int64_t kg = e.bk / 4, groups = (K + kg - 1) / kg;
+        const double batches = (double)((groups + 15) / 16);
+        const double batch_mfma = 4.0 * 4.0 * (e.mfma ? 32.0 : 64.0);   // four groups of four MFMAs per wave
+        const double batch_bytes = 16.0 * kg * e.bm * 4.0 * 2.0;
+        const double per_cu = (double)(int64_t)((ntiles + kCUs - 1) / kCUs);
+        return batches * std::max(per_cu * std::max(batch_mfma * 1.2, batch_bytes / (e.mfma ? 18.5 : 14.0)),
+                                  1000.0 + batch_mfma);
+    }
     const int64_t nk_all = (K + e.bk - 1) / e.bk;
     const double tiles = ntiles * split;
     const double wg_wps = e.threads / 256.0;                        // waves per SIMD of one workgroup
@@ -216,6 +232,7 @@ double model_cycles(tsg_dtype dt, const KernelEntry& e, int split, int split_tai
 bool split_allowed(const KernelEntry& e, int split, int split_tail, int64_t batch, int64_t M, int64_t N, int64_t K,
                    int64_t ws_bytes) {
     if (split == 1) return !split_tail;
+    if (e.sched == 1) return false;   // the block form splits k inside the workgroup only
     const int64_t nk_all = (K + e.bk - 1) / e.bk;
     const int64_t n_split = split_tiles(((M + e.bm - 1) / e.bm) * ((N + e.bn - 1) / e.bn), split, split_tail);
     return n_split > 0 && split * 2 <= nk_all && ws_bytes_needed(e, batch, M, N, split, split_tail) <= ws_bytes &&
@@ -302,6 +319,7 @@ tsg_status make_plan(const Problem& p, const tsg_tile_config& cfg, int alternati
     if (!e) return TSG_E_SILENCEABLE;
     if (!vec_legal(p, cfg.vec)) return TSG_E_SILENCEABLE;
     if (e->sched >= 4 && cfg.vec == 1) return TSG_E_SILENCEABLE;   // direct-to-LDS forms move 16-byte chunks
+    if (e->sched == 1 && cfg.split_k > 1) return TSG_E_SILENCEABLE;   // the block form splits k inside the workgroup only
     if (!(e->modes >> amode_of(p) & 1)) return TSG_E_SILENCEABLE;   // the tile does not exist for this operand layout
     if (cfg.raster != 0 && cfg.raster != 1) return TSG_E_SILENCEABLE;
     if (cfg.split_k < 1 || cfg.split_k > kMaxSplit) return TSG_E_SILENCEABLE;
@@ -434,7 +452,7 @@ tsg_status run(const Problem& p, hipStream_t s) {
             const KernelEntry* t = kernels(p.dtype, &n);
             int pick = -1;
             for (int i = 0; i < n; ++i)
-                if (t[i].sched < 4 && (pick < 0 || t[i].bm * t[i].bn < t[pick].bm * t[pick].bn)) pick = i;
+                if (t[i].sched == 0 && (pick < 0 || t[i].bm * t[i].bn < t[pick].bm * t[pick].bn)) pick = i;
             if (pick < 0) return TSG_E_INVALID;
             scalar = config_of(t[pick], 1, heur.raster, 1);
         }
@@ -811,6 +829,7 @@ tsg_status tsg_tile_config_check(tsg_op op, tsg_dtype dtype, int64_t M, int64_t 
     if (c.raster != 0 && c.raster != 1) return TSG_E_SILENCEABLE;
     if (c.split_k < 1 || c.split_k > kMaxSplit || c.split_k > (K + e->bk - 1) / e->bk) return TSG_E_SILENCEABLE;
     if (c.split_tail && c.split_k == 1) return TSG_E_SILENCEABLE;
+    if (e->sched == 1 && c.split_k > 1) return TSG_E_SILENCEABLE;   // the block form splits k inside the workgroup only
     if (c.split_k > 1 && split_tiles(((M + e->bm - 1) / e->bm) * ((N + e->bn - 1) / e->bn), c.split_k, c.split_tail) == 0)
         return TSG_E_SILENCEABLE;   // no tail to split
     if (c.vec == 1) return e->sched >= 4 ? TSG_E_SILENCEABLE : TSG_OK;

@@ -21,7 +21,10 @@
 // counter; the workgroup that arrives last adds the S partials in split order (so the sum does
 // not depend on who was last), applies the epilogue and resets the counter.
 //
-// Two kernel forms (`sched`, a tunable like the tile sizes):
+// Three kernel forms (`sched`, a tunable like the tile sizes):
+//   1     one MFMA block of C per workgroup, k dealt over its four waves, operands straight
+//         from global memory into the MFMA's registers: for products too small to give the
+//         forms below a tile per compute unit.  fp32 GEMM only, no k split across workgroups.
 //   0     register staging: the tiles of step t+1 are fetched into registers while step t is
 //         multiplied from LDS (two padded stages, one barrier per step, instruction order left
 //         to the compiler).  Serves every access width, so it is also the last alternative.
@@ -45,10 +48,11 @@ struct Tile {
     using E = E_;
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, MINW = MINW_, SCHED = SCHED_;
     static constexpr int WAVES_M = BM / WM, WAVES_N = BN / WN;
-    static constexpr int NT = 64 * WAVES_M * WAVES_N;
+    static constexpr int NT = SCHED == 1 ? 256 : 64 * WAVES_M * WAVES_N;   // (sched 1: four waves share one block along k)
     static constexpr int MI = WM / E::BLK, NI = WN / E::BLK;
     static_assert(BM % WM == 0 && BN % WN == 0 && WM % E::BLK == 0 && WN % E::BLK == 0 && BK % E::KG == 0, "tile");
-    static_assert(SCHED == 0 || SCHED == 4 || SCHED == 5, "kernel form");
+    static_assert(SCHED == 0 || SCHED == 1 || SCHED == 4 || SCHED == 5, "kernel form");
+    static_assert(SCHED != 1 || (BM == E::BLK && BN == E::BLK && WM == BM && WN == BN && BK == 4 * E::KG), "block form");
 };
 
 __device__ __forceinline__ void tile_coords(const KArgs& p, int bid, int& tm, int& tn) {
@@ -325,6 +329,107 @@ __device__ __forceinline__ void finish_tile(const KArgs& p, typename T::E::acc_t
         if (accum) emit(std::true_type{}, std::true_type{});
         else emit(std::true_type{}, std::false_type{});
     }
+}
+
+// ---------------------------------------------------------------------------------------
+// sched 1: one MFMA block of C per workgroup, for products so small that the tiled forms leave
+// most of the chip idle (256^3 is 16 tiles of 64 x 64, but 256 blocks of 16 x 16).  The k loop
+// is dealt over the four waves of the workgroup, one per SIMD: k group g belongs to wave g % 4,
+// and a step of BK = 4 groups is one group per wave.  Operands go from global memory straight
+// into the MFMA's operand registers (lane (l, q) of a wave holds k = 4 q .. 4 q + 3 of row or
+// column l of its group: a 16-byte access where the operand is k-contiguous, four coalesced
+// scalars where it is not), four groups per wave in flight together: no LDS staging and no
+// barrier in the loop.  The waves' partial blocks meet in LDS and wave 0 adds them in wave
+// order, so the order of summation is fixed.  Remainder (VARIANT 1): rows and columns past the end
+// are clamped to the last valid one (their products only reach elements of C that are never
+// stored) and only the last, partial k group is masked, element by element; VARIANT 2 is the
+// same with scalar accesses throughout; VARIANT 0 has no remainder code.
+template <class T, int AMODE, int VARIANT>
+__global__ void __launch_bounds__(256) gemm_block_kernel(const KArgs p) {
+    using E = typename T::E;
+    using frag = typename E::frag;
+    using chunk_u = typename E::chunk_u;
+    static_assert(T::SCHED == 1 && T::MI == 1 && T::NI == 1 && sizeof(typename E::elem) == 4, "one fp32 block");
+    static_assert(AMODE != A_CONV, "no gathered operand in this form");
+    constexpr int BLK = E::BLK, KG = E::KG, NACC = E::NACC, WAVES = 4, U = 4;
+    constexpr bool EDGE = VARIANT != 0, WIDE = VARIANT != 2;
+    constexpr bool A_KMAJ = AMODE == A_ROW || AMODE == A_ROW_BT;
+    constexpr bool B_KMAJ = AMODE == A_ROW_BT || AMODE == A_COL_BT;
+    __shared__ float part[WAVES - 1][NACC][64];
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int li = lane & (BLK - 1), q = lane / BLK;
+    int tm, tn;
+    tile_coords(p, blockIdx.x, tm, tn);
+    const int m0 = tm * BLK, n0 = tn * BLK;
+    const float* __restrict__ A = (const float*)p.A + (long long)blockIdx.y * p.stride_a;
+    const float* __restrict__ B = (const float*)p.B + (long long)blockIdx.y * p.stride_b;
+    float* __restrict__ C = p.C + (long long)blockIdx.y * p.stride_c;
+
+    const int row = EDGE ? min(m0 + li, p.M - 1) : m0 + li;
+    const int col = EDGE ? min(n0 + li, p.N - 1) : n0 + li;
+    // the lane's row of op(A) and column of op(B) at k = 0
+    const float* a0 = A_KMAJ ? A + (long long)row * p.lda : A + row;
+    const float* b0 = B_KMAJ ? B + (long long)col * p.ldb : B + col;
+    const bool interior = !EDGE || (m0 + BLK <= p.M && n0 + BLK <= p.N);
+
+    typename E::acc_t acc[1][1];
+#pragma unroll
+    for (int r = 0; r < NACC; ++r) acc[0][0][r] = 0.f;
+    OldC<T> oldc;
+    if (wave == 0) oldc.fetch(p, C, m0, n0, 0, 0, interior, 1);
+
+    const int ngroups = (p.K + KG - 1) / KG;
+    for (int g0 = wave; g0 < ngroups; g0 += WAVES * U) {
+        frag a[U], b[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int g = g0 + WAVES * u;
+            const int k = g * KG + 4 * q;
+            a[u] = E::zero();
+            b[u] = E::zero();
+            if (g >= ngroups) continue;   // the same for the whole wave; zeros add nothing
+            if (!EDGE || (g + 1) * KG <= p.K) {   // a whole group (again the same for the whole wave)
+                if constexpr (A_KMAJ && WIDE) {
+                    a[u] = *(const chunk_u*)(a0 + k);
+                } else {
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) a[u][t] = A_KMAJ ? a0[k + t] : a0[(long long)(k + t) * p.lda];
+                }
+                if constexpr (B_KMAJ && WIDE) {
+                    b[u] = *(const chunk_u*)(b0 + k);
+                } else {
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) b[u][t] = B_KMAJ ? b0[k + t] : b0[(long long)(k + t) * p.ldb];
+                }
+            } else {
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const int kk = k + t;
+                    if (kk < p.K) {
+                        a[u][t] = A_KMAJ ? a0[kk] : a0[(long long)kk * p.lda];
+                        b[u][t] = B_KMAJ ? b0[kk] : b0[(long long)kk * p.ldb];
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) acc[0][0] = E::mfma(a[u], b[u], acc[0][0], t);
+    }
+
+    if (wave > 0) {
+#pragma unroll
+        for (int r = 0; r < NACC; ++r) part[wave - 1][r][lane] = acc[0][0][r];
+    }
+    __syncthreads();
+    if (wave != 0) return;
+#pragma unroll
+    for (int w = 0; w < WAVES - 1; ++w)
+#pragma unroll
+        for (int r = 0; r < NACC; ++r) acc[0][0][r] += part[w][r][lane];
+    finish_tile<T>(p, acc, C, 0, 0, 1, m0, n0, 0, 0, interior, oldc);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1076,8 +1181,19 @@ hipError_t launch_mode(int variant, const KArgs& a, int batch, hipStream_t s) {
     using E = typename T::E;
     const dim3 grid(a.split_first + (a.tiles_m * a.tiles_n - a.split_first) * a.split_k, batch, 1), block(T::NT, 1, 1);
     void (*fn)(const KArgs) = nullptr;
-    int bytes, one_tap = 0;
-    if constexpr (T::SCHED >= 4 && !direct_mode_ok<T, AMODE>()) {
+    int bytes = 0, one_tap = 0;
+    if constexpr (T::SCHED == 1) {
+        if constexpr (AMODE == A_CONV) {
+            return hipErrorInvalidValue;   // the block form takes matrices only
+        } else {
+            if (a.split_k != 1) return hipErrorInvalidValue;   // k is split inside the workgroup only
+            fn = variant == 0 ? gemm_block_kernel<T, AMODE, 0>
+                 : variant == 2 ? gemm_block_kernel<T, AMODE, 2> : gemm_block_kernel<T, AMODE, 1>;
+            hipLaunchKernelGGL(fn, grid, block, 0, s, a);
+            (void)one_tap;
+            return hipGetLastError();
+        }
+    } else if constexpr (T::SCHED >= 4 && !direct_mode_ok<T, AMODE>()) {
         return hipErrorInvalidValue;   // this tile shape does not exist for this operand layout
     } else if constexpr (T::SCHED >= 4) {
         // the direct-to-LDS forms move whole 16-byte chunks only
@@ -1117,7 +1233,9 @@ hipError_t launch_mode(int variant, const KArgs& a, int batch, hipStream_t s) {
 // bit m set: the tile exists for address mode m
 template <class T>
 constexpr int mode_mask_of() {
-    if constexpr (T::SCHED >= 4)
+    if constexpr (T::SCHED == 1)
+        return (1 << A_ROW) | (1 << A_COL) | (1 << A_ROW_BT) | (1 << A_COL_BT);
+    else if constexpr (T::SCHED >= 4)
         return (direct_mode_ok<T, A_ROW>() << A_ROW) | (direct_mode_ok<T, A_COL>() << A_COL) |
                (direct_mode_ok<T, A_CONV>() << A_CONV) | (direct_mode_ok<T, A_ROW_BT>() << A_ROW_BT) |
                (direct_mode_ok<T, A_COL_BT>() << A_COL_BT);
@@ -1127,7 +1245,8 @@ constexpr int mode_mask_of() {
 
 template <class T>
 constexpr int lds_bytes_of() {
-    if constexpr (T::SCHED >= 4) return LdsDirect<T>::BYTES;
+    if constexpr (T::SCHED == 1) return 3 * T::E::NACC * 64 * 4;
+    else if constexpr (T::SCHED >= 4) return LdsDirect<T>::BYTES;
     else return Lds<T, A_ROW>::BYTES;
 }
 
@@ -1158,7 +1277,9 @@ constexpr int lds_bytes_of() {
     X(F32B16, 112, 64, 32, 112, 16, 2, 4) \
     X(F32B16, 112, 64, 32, 112, 16, 2, 5) \
     X(F32B16, 112, 64, 64, 112, 16, 1, 4) \
-    X(F32B16, 64, 64, 32, 64, 16, 2, 4)
+    X(F32B16, 64, 64, 32, 64, 16, 2, 4) \
+    X(F32B16, 16, 16, 64, 16, 16, 1, 1)  \
+    X(F32, 32, 32, 32, 32, 32, 1, 1)
 
 #define TSG_BF16_TILES(X)                  \
     X(BF16, 256, 256, 64, 128, 64, 2, 0)   \

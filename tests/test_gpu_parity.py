@@ -240,10 +240,12 @@ def test_split_k_random_is_deterministic_and_within_tolerance(workspace):
     for r in runs[1:]:
         assert np.array_equal(r.view(np.uint32), runs[0].view(np.uint32))
     check(runs[0], A, B, dt)
-    # the library's own choice for this shape splits k once a workspace is there
+    # 16 tiles of 64 x 64 cannot fill the chip: the library's own choice for this shape either splits k
+    # (once a workspace is there) or takes the block form, 208 blocks of 16 x 16
     tsg.tile_config_set(op, dt, None)
     C = run_gemm(dt, A, B)
-    assert tsg.last_launch().config.split_k > 1
+    cfg = tsg.last_launch().config
+    assert cfg.split_k > 1 or cfg.sched == 1, cfg
     check(C, A, B, dt)
 
 
@@ -533,7 +535,7 @@ def test_conv_every_config_and_zero_pad_identity(workspace):
         c = tsg.tile_config_enum(op, dt, i)
         if tsg.tile_config_check(op, dt, N * H * W, Cout, 9 * Cin, c, contig=Cin) != tsg.OK:
             # illegal here: a split beyond the number of k steps, scalar access in a direct-to-LDS form
-            assert c.split_k > 1 or (c.vec == 1 and c.sched >= 4)
+            assert c.split_k > 1 or (c.vec == 1 and c.sched >= 4) or c.sched == 1   # (the block form takes matrices only)
             continue
         tsg.tile_config_set(op, dt, c)
         y = run_conv(dt, x, w, (1, 1), (1, 1), flags=tsg.STRICT)
@@ -624,7 +626,7 @@ def test_transposed_right_operand_bit_exact(dtype, trans_a, workspace):
             out = dC.cpu().numpy()
             assert np.array_equal(out[:, :N].astype(np.float64), C0 - R), (M, N, K, pad)
             assert np.all(out[:, N:] == np.float32(-9.0))
-            assert tsg.last_launch().config.sched >= 4
+            assert tsg.last_launch().config.sched != 0   # (the register-staged form has no transposed B)
     M, N, K = 196, 130, 461
     A, _ = inputs(M, N, K, 84, "ints", trans_a, dtype)
     Bt = inputs(N, 1, K, 85, "ints", False, dtype)[0]
@@ -633,7 +635,7 @@ def test_transposed_right_operand_bit_exact(dtype, trans_a, workspace):
     seen = 0
     for i in range(tsg.tile_config_count(op, dtype)):
         c = tsg.tile_config_enum(op, dtype, i)
-        if c.sched < 4 or c.vec == 1 or tsg.tile_config_check(op, dtype, M, N, K, c) != tsg.OK:
+        if c.sched == 0 or c.vec == 1 or tsg.tile_config_check(op, dtype, M, N, K, c) != tsg.OK:
             continue
         tsg.tile_config_set(op, dtype, c)
         dC = torch.zeros((M, N), dtype=torch.float32, device=DEV)
@@ -1088,6 +1090,84 @@ def test_workload7_full_reduce_one_gib(workspace):
 
 # ------------------------------------------------------------------ seeded sweep of shapes
 
+@pytest.mark.parametrize("blk,bk,mfma", [(16, 64, 1), (32, 32, 0)])
+@pytest.mark.parametrize("trans_a,trans_b", [(False, False), (True, False), (False, True), (True, True)])
+def test_block_form_every_layout_variant_and_flag(blk, bk, mfma, trans_a, trans_b):
+    """sched 1 (one MFMA block per workgroup, k dealt over its four waves): both variants
+    (divisible shape: wide unmasked loads; ragged shape and vec = 1: masked scalars), the four
+    operand layouts, padded leading dimensions, batches, sign and accumulate, bit-exact on
+    integers and within tolerance on uniform data."""
+    op = tsg.OP_GEMM_TRANSA if trans_a else tsg.OP_GEMM
+    dt = tsg.F32
+    for (nb, M, N, K, vec, pad) in [(1, 256, 256, 256, 4, 0), (3, 64, 96, 192, 4, 5), (2, 50, 70, 203, 4, 3),
+                                    (1, 33, 17, 7, 1, 1), (1, 16, 16, 1024, 4, 0), (2, 100, 36, 129, 1, 0)]:
+        cfg = tsg.TileConfig(bm=blk, bn=blk, bk=bk, wm=blk, wn=blk, vec=vec, raster=(M + N) % 2, sched=1, split_k=1, mfma=mfma)
+        tsg.tile_config_set(op, dt, cfg)
+        for dist, flags in (("ints", 0), ("ints", tsg.NEGATE | tsg.ACCUMULATE), ("uniform", tsg.ACCUMULATE)):
+            seed = 300 + M + N + K
+            n_a, n_b = nb * M * K, nb * K * N
+            gen = synth.small_ints if dist == "ints" else synth.uniform_pm1
+            A = gen(seed, 0, n_a).reshape((nb, K, M) if trans_a else (nb, M, K))
+            B = gen(seed, 1, n_b).reshape((nb, N, K) if trans_b else (nb, K, N))
+            C0 = synth.small_ints(seed, 2, nb * M * N).reshape(nb, M, N)
+            lda, ldb, ldc = A.shape[2] + pad, B.shape[2] + 2 * pad, N + pad
+            Ah = np.zeros((nb, A.shape[1], lda), np.float32); Ah[:, :, :A.shape[2]] = A
+            Bh = np.zeros((nb, B.shape[1], ldb), np.float32); Bh[:, :, :B.shape[2]] = B
+            Ch = np.full((nb, M, ldc), np.float32(-7.0)); Ch[:, :, :N] = C0
+            dC = dev(Ch)
+            tsg.gemm_trans(dt, trans_a, trans_b, nb, M, N, K, dev(Ah), lda, A.shape[1] * lda, dev(Bh), ldb,
+                           B.shape[1] * ldb, dC, ldc, M * ldc, flags | tsg.STRICT)
+            torch.cuda.synchronize()
+            li = tsg.last_launch()
+            assert li.alternative == 0 and li.config.sched == 1 and li.config.bm == blk
+            assert li.edge == int(bool(M % blk or N % blk or K % bk or vec == 1))
+            out = dC.cpu().numpy()
+            assert np.all(out[:, :, N:] == np.float32(-7.0))
+            for b in range(nb):
+                R, S = oracle.gemm(A[b], B[b], trans_a=trans_a, trans_b=trans_b)
+                sign = -1.0 if flags & tsg.NEGATE else 1.0
+                want = sign * R + (C0[b] if flags & tsg.ACCUMULATE else 0.0)
+                if dist == "ints":
+                    assert np.array_equal(out[b, :, :N].astype(np.float64), want), (nb, M, N, K, vec, flags)
+                else:
+                    err = np.abs(out[b, :, :N].astype(np.float64) - want)
+                    assert np.max(err / np.maximum(S, 1e-30)) <= 1e-4 and np.max(err) <= 1e-4 * np.max(np.abs(want))
+    # k split over workgroups does not exist in this form: silenceable under STRICT
+    ws = torch.empty(16 << 20, dtype=torch.uint8, device=DEV)
+    tsg.workspace_set(ws)
+    try:
+        cfg = tsg.TileConfig(bm=blk, bn=blk, bk=bk, wm=blk, wn=blk, vec=4, raster=0, sched=1, split_k=2, mfma=mfma)
+        assert tsg.tile_config_check(op, dt, 256, 256, 256, cfg) == tsg.E_SILENCEABLE
+        tsg.tile_config_set(op, dt, cfg)
+        A = synth.small_ints(1, 0, 256 * 256).reshape(256, 256)
+        dC = torch.zeros((256, 256), dtype=torch.float32, device=DEV)
+        with pytest.raises(tsg.SilenceableError):
+            tsg.gemm_trans(dt, trans_a, trans_b, 1, 256, 256, 256, dev(A), 256, 0, dev(A), 256, 0, dC, 256, 0, tsg.STRICT)
+        torch.cuda.synchronize()
+        assert not dC.any()
+    finally:
+        torch.cuda.synchronize()
+        tsg.workspace_set(None)
+
+
+def test_measurement_aids_return_plausible_figures_and_validate_arguments():
+    """tsg_launch_floor and tsg_mfma_ceiling are measurement aids, not part of the path: they must
+    reject bad arguments, run, and report figures below the published peaks."""
+    us = tsg.launch_floor(2000)
+    assert 0.2 < us < 100.0
+    with pytest.raises(tsg.TsgError):
+        tsg.launch_floor(0)
+    sink = torch.empty(4 << 20, dtype=torch.uint8, device=DEV)
+    for dt, peak in ((tsg.F32, 157.3), (tsg.BF16_F32ACC, 2500.0)):
+        for mfma in (0, 1):
+            best, sustained = tsg.mfma_ceiling(dt, mfma, 1, 1, 2, sink)
+            assert 0.2 * peak < sustained <= best * 1.001 and best < 1.02 * peak, (dt, mfma, best, sustained)
+    with pytest.raises(tsg.TsgError):
+        tsg.mfma_ceiling(tsg.F32, 2, 0, 1, 2, sink)
+    with pytest.raises(tsg.TsgError):
+        tsg.mfma_ceiling(tsg.F32, 0, 0, 1, 2, torch.empty(1024, dtype=torch.uint8, device=DEV))
+
+
 def test_seeded_sweep_of_ragged_shapes_all_entry_points(workspace):
     """Forty shapes drawn from a seeded generator (odd extents, odd leading dimensions, tiny
     and long k), each through a random entry point, dtype, flag set and, for half of them, a
@@ -1188,7 +1268,7 @@ def test_many_seeded_gemm_cases_random_configs(workspace):
             cnt = tsg.tile_config_count(op, dt)
             for _ in range(20):
                 c = tsg.tile_config_enum(op, dt, rng.randrange(cnt))
-                if tsg.tile_config_check(op, dt, M, N, K, c) == tsg.OK and not (tb and c.sched < 4):
+                if tsg.tile_config_check(op, dt, M, N, K, c) == tsg.OK and not (tb and c.sched == 0):
                     pin = c
                     break
         tsg.tile_config_set(op, dt, pin)

@@ -66,7 +66,9 @@ def test_search_space_enumeration():
                 blk = 16 if c.mfma else 32
                 assert c.mfma in (0, 1) and (dt == tsg.F32 or c.mfma == 0)
                 assert c.bm % c.wm == 0 and c.bn % c.wn == 0 and c.wm % blk == 0 and c.wn % blk == 0
-                assert c.vec in (1, vmax) and c.raster in (0, 1) and c.sched in (0, 4, 5)
+                # the block form: one MFMA block per workgroup, fp32 only
+                assert c.sched != 1 or (dt == tsg.F32 and c.bm == c.bn == c.wm == c.wn == blk)
+                assert c.vec in (1, vmax) and c.raster in (0, 1) and c.sched in (0, 1, 4, 5)
                 assert 1 <= c.split_k <= 16
                 key = tuple(c.as_dict().values())
                 assert key not in seen
@@ -78,7 +80,8 @@ def test_search_space_enumeration():
                 for ext in (4096, 4000 + 96 * 3):
                     tiles = -(-ext // c.bm) * -(-ext // c.bn)
                     bad = ((c.vec == 1 and c.sched >= 4) or (c.split_tail and tiles % 256 == 0) or
-                           (c.sched >= 4 and not _direct_tile_exists(c, op, vmax)) or (c.sched == 0 and c.mfma == 1))
+                           (c.sched >= 4 and not _direct_tile_exists(c, op, vmax)) or (c.sched == 0 and c.mfma == 1) or
+                           (c.sched == 1 and (c.split_k > 1 or op == tsg.OP_CONV2D_NHWC)))
                     want = tsg.E_SILENCEABLE if bad else tsg.OK
                     assert tsg.tile_config_check(op, dt, ext, ext, 4096, c, contig=64) == want, (c, op, ext)
             with pytest.raises(tsg.TsgError):

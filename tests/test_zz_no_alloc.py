@@ -46,10 +46,17 @@ def _both(batch, M, N, K, seed, dist, flags=0):
 
 
 def test_static_scratch_entry_point_matches_the_workspace_one_twice_in_a_row():
-    # first call: the paper's batched loop nest (Case Study 4); second: a smaller, ragged product
+    # first call: the paper's batched loop nest (Case Study 4), whose default config splits k;
+    # second: a smaller, ragged product, for which the library's own choice does not split, so
+    # a config that does is pinned (a pin applies to both entry points alike)
+    split3 = tsg.TileConfig(bm=64, bn=64, bk=32, wm=32, wn=32, vec=4, raster=0, sched=4, split_k=3)
     for step, (batch, M, N, K) in enumerate(((6, 196, 256, 2305), (2, 100, 72, 1031))):
         for dist in ("ints", "uniform"):
-            A, B, Cs, Cw, li_s, li_w = _both(batch, M, N, K, seed=50 + step, dist=dist)
+            tsg.tile_config_set(tsg.OP_GEMM, tsg.F32, split3 if step == 1 else None)
+            try:
+                A, B, Cs, Cw, li_s, li_w = _both(batch, M, N, K, seed=50 + step, dist=dist)
+            finally:
+                tsg.tile_config_set(tsg.OP_GEMM, tsg.F32, None)
             assert li_s.config.as_dict() == li_w.config.as_dict(), (li_s.config, li_w.config)
             assert li_s.config.split_k > 1, "the scratch is only exercised when the k loop is split"
             assert np.array_equal(Cs.view(np.uint32), Cw.view(np.uint32)), (step, dist)
