@@ -115,12 +115,16 @@ struct RunStart { long long off; int wo, ho; };
 template <class T>
 struct WindowCursor {
     RunStart cur;
-    bool started = false;
+    bool started = false, seeded = false;
+    // start from a first run that somebody decoded before (the early read of the old values)
+    __device__ __forceinline__ void seed(const RunStart& first) { cur = first; started = true; seeded = true; }
     // the run that starts at row `row`; calls come in increasing row order, `step` rows apart
     __device__ __forceinline__ void next(const KArgs& p, int row, RunStart& out) {
         constexpr int STEP = T::E::BLK == 32 ? 8 : 16;
         static_assert(T::E::BLK == 32 ? T::E::NACC == 16 : T::E::NACC == 4, "accumulator rows per block");
-        if (!started) {
+        if (seeded) {
+            seeded = false;   // the seed is this first run
+        } else if (!started) {
             // (non-negative: unsigned divisions)
             const unsigned tq = (unsigned)row / (unsigned)p.Wo, nq = tq / (unsigned)p.Ho;
             cur.wo = row - (int)tq * p.Wo;
@@ -162,6 +166,18 @@ __device__ __forceinline__ void visit_block(const KArgs& p, float* __restrict__ 
     const int col = n0 + wn0 + j * BLK + (lane & (BLK - 1));
     const int row_b = m0 + wm0 + i * BLK;
     if (p.y_window) {
+        if ((p.Wo & 3) == 0) {
+            // a run starts at a multiple of four rows, so with Wo a multiple of four it never
+            // crosses from one image row into the next: four pixels a fixed stride apart
+#pragma unroll
+            for (int rg = 0; rg < NACC / 4; ++rg) {
+                const int row0 = row_b + E::acc_row(4 * rg, lane);
+                float* ptr = C + rs[rg].off + col;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) f(4 * rg + e, ptr + e * p.y_sw, !CHECK || (row0 + e < p.M && col < p.N));
+            }
+            return;
+        }
         const long long wrap_w = p.y_sh - (long long)p.Wo * p.y_sw, wrap_h = p.y_sn - (long long)p.Ho * p.y_sh;
 #pragma unroll
         for (int rg = 0; rg < NACC / 4; ++rg) {
@@ -199,6 +215,7 @@ struct OldC {
     static constexpr bool ON = T::MI * T::NI * T::E::NACC <= 32;
     float v[ON ? T::MI : 1][ON ? T::NI : 1][ON ? T::E::NACC : 1];
     bool loaded = false;
+    RunStart first;   // the lane's first run in a window, decoded here once for the epilogue too
 
     __device__ __forceinline__ void fetch(const KArgs& p, float* __restrict__ C, int m0, int n0, int wm0, int wn0,
                                           bool interior, int nsplit) {
@@ -210,6 +227,7 @@ struct OldC {
             for (int i = 0; i < T::MI; ++i) {
                 RunStart rs[T::E::NACC / 4];
                 wc.block(p, m0, wm0, i, rs);
+                if (i == 0 && p.y_window) first = rs[0];
 #pragma unroll
                 for (int j = 0; j < T::NI; ++j) {
                     if (interior)
@@ -294,6 +312,9 @@ __device__ __forceinline__ void finish_tile(const KArgs& p, typename T::E::acc_t
     auto emit = [&](auto check_tag, auto accum_tag) {
         constexpr bool CHECK = decltype(check_tag)::value, ACCUM = decltype(accum_tag)::value;
         WindowCursor<T> wc;
+        if constexpr (OldC<T>::ON) {
+            if (oldc.loaded && p.y_window) wc.seed(oldc.first);
+        }
 #pragma unroll
         for (int i = 0; i < MI; ++i) {
             RunStart rs[NACC / 4];
@@ -1084,10 +1105,15 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_direct_kernel(const KArgs
 #pragma unroll
     for (int x = 0; x < NFRAG; ++x) frag_read(0, 0, 0, x);
     int cur = 0;
-    auto step = [&](auto parity_tag, int kt) {
+    auto step = [&](auto parity_tag, auto loads_tag, int kt) {
         // PAR: which fragment buffer group 0 of this step uses (only alternates per step when a
-        // step is a single group)
+        // step is a single group).  LOADS: 0 = every load of tile kt+D is guarded by a test that the
+        // tile exists; 1 = the caller knows it exists (no test); 2 = the caller knows it does not
+        // (no loads).  Small tiles run their steps as 1 then 2: a test beside each load cut the
+        // step's scheduling region at every one (1-2 % of the layer and of 1024^3); the large
+        // tiles keep the tests, where the split cost 13 %.
         constexpr int PAR = decltype(parity_tag)::value;
+        constexpr int LOADS = decltype(loads_tag)::value;
         const int nxt = cur + 1 == STAGES ? 0 : cur + 1;
         const int fill = cur == 0 ? STAGES - 1 : cur - 1;
 #pragma unroll
@@ -1122,12 +1148,12 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_direct_kernel(const KArgs
                         else frag_read(buf ^ 1, cur, g + 1, e);
                     }
                 }
-                if (last && m >= L0) {
+                if (LOADS != 2 && last && m >= L0) {
 #pragma unroll
                     for (int u = 0; u < LPER; ++u) {
                         const int e = (m - L0) * LPER + u;
                         if (e >= LPT) continue;
-                        if (kt + D < nkp) issue_part(kt + D, fill, e);
+                        if (LOADS == 1 || kt + D < nkp) issue_part(kt + D, fill, e);
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);
@@ -1135,15 +1161,41 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_direct_kernel(const KArgs
         }
         cur = nxt;
     };
-    if constexpr (GP == 0) {
-        for (int kt = 0; kt < nkp; ++kt) step(std::integral_constant<int, 0>{}, kt);
-    } else {
-        int kt = 0;
-        for (; kt + 1 < nkp; kt += 2) {
-            step(std::integral_constant<int, 0>{}, kt);
-            step(std::integral_constant<int, 1>{}, kt + 1);
+    {
+        using P0 = std::integral_constant<int, 0>;
+        using P1 = std::integral_constant<int, 1>;
+        using Guarded = std::integral_constant<int, 0>;
+        using Live = std::integral_constant<int, 1>;
+        using Dead = std::integral_constant<int, 2>;
+        constexpr bool SMALL = MI * NI * E::NACC <= 32;
+        if constexpr (!SMALL) {
+            if constexpr (GP == 0) {
+                for (int kt = 0; kt < nkp; ++kt) step(P0{}, Guarded{}, kt);
+            } else {
+                int kt = 0;
+                for (; kt + 1 < nkp; kt += 2) {
+                    step(P0{}, Guarded{}, kt);
+                    step(P1{}, Guarded{}, kt + 1);
+                }
+                if (kt < nkp) step(P0{}, Guarded{}, kt);
+            }
+        } else {
+            const int n_live = max(0, nkp - D);   // steps kt with a tile kt+D to bring in
+            int kt = 0;
+            if constexpr (GP == 0) {
+                for (; kt < n_live; ++kt) step(P0{}, Live{}, kt);
+                for (; kt < nkp; ++kt) step(P0{}, Dead{}, kt);
+            } else {
+                for (; kt < n_live; ++kt) {
+                    if (kt & 1) step(P1{}, Live{}, kt);
+                    else step(P0{}, Live{}, kt);
+                }
+                for (; kt < nkp; ++kt) {
+                    if (kt & 1) step(P1{}, Dead{}, kt);
+                    else step(P0{}, Dead{}, kt);
+                }
+            }
         }
-        if (kt < nkp) step(std::integral_constant<int, 0>{}, kt);
     }
 
     if constexpr (CLAMP) {
