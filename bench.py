@@ -409,18 +409,22 @@ def main() -> int:
     # A step of the small workloads takes tens of microseconds, and the first few milliseconds
     # after an idle period run at a lower clock: unless the caller fixes the count, time enough
     # steps for 0.2 s
+    for _ in range(20):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(20):
+        step()
+    torch.cuda.synchronize()
+    est = (time.perf_counter() - t0) / 20
     if args.steps is None:
-        for _ in range(20):
-            step()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(20):
-            step()
-        torch.cuda.synchronize()
-        est = (time.perf_counter() - t0) / 20
         args.steps = max(100, min(1000 if args.graph else 20000, int(0.2 / est)))
     if args.warmup is None:
         args.warmup = max(10, args.steps // 10)
+    # The tuner's report above left the GPU idle for a while.  Whatever W is, bring the clock back up
+    # first with 0.1 s of untimed steps, and go into the W warmup steps without a gap.
+    for _ in range(max(1, min(5000, int(0.1 / est)))):
+        step()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
