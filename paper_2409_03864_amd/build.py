@@ -10,15 +10,18 @@ from __future__ import annotations
 import os
 import subprocess
 import sys
+import time
 from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtsg.so")
-SOURCES = ["api.cpp", "gemm_f32_row.hip", "gemm_f32_col.hip", "gemm_f32_conv.hip",
-           "gemm_f32_row_bt.hip", "gemm_f32_col_bt.hip", "gemm_bf16_row_bt.hip", "gemm_bf16_col_bt.hip",
-           "gemm_bf16_row.hip", "gemm_bf16_col.hip", "gemm_bf16_conv.hip", "reduce.hip", "ceiling.hip"]
+# (the slowest units first: the build is as long as its longest chain of units)
+SOURCES = ["gemm_f32_conv.hip", "gemm_f32_conv_b.hip", "gemm_bf16_conv.hip", "gemm_bf16_conv_b.hip",
+           "gemm_bf16_row.hip", "gemm_bf16_col.hip", "gemm_f32_row.hip", "gemm_f32_col.hip",
+           "gemm_bf16_row_bt.hip", "gemm_bf16_col_bt.hip", "gemm_f32_row_bt.hip", "gemm_f32_col_bt.hip",
+           "api.cpp", "reduce.hip", "ceiling.hip"]
 PUBLIC_HEADER = os.path.join(HERE, "..", "include", "tsg.h")
 
 
@@ -27,7 +30,7 @@ def _deps(src: str):
     and the reduce see the public header."""
     deps = [os.path.join(CSRC, "tsg_internal.h")]
     if src.startswith("gemm_"):
-        deps += [os.path.join(CSRC, "gemm_kernel.h"), os.path.join(CSRC, "gemm_elem.h")]
+        deps += [os.path.join(CSRC, h) for h in ("gemm_kernel.h", "gemm_elem.h", "gemm_tiles.h")]
     else:
         deps.append(PUBLIC_HEADER)
     return deps
@@ -57,9 +60,12 @@ def _compile(src: str, force: bool) -> str:
     obj = os.path.join(OBJ, src + ".o")
     if force or _stale(obj, [path] + _deps(src)):
         cmd = [_hipcc()] + HIPCC_FLAGS + ["-x", "hip", "-c", path, "-o", obj]
+        t0 = time.time()
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError("hipcc failed for %s:\n%s\n%s" % (src, r.stdout, r.stderr))
+        if os.environ.get("TSG_BUILD_VERBOSE"):
+            print("  %-24s %6.1f s" % (src, time.time() - t0), file=sys.stderr, flush=True)
     return obj
 
 

@@ -1,5 +1,5 @@
 // bfloat16 kernels, op(A)(i,k) = A[i*lda + k], and the table of instantiated tiles.
-#include "gemm_kernel.h"
+#include "gemm_tiles.h"
 
 TSG_DEFINE_MODE(launch_bf16_row, TSG_BF16_TILES, A_ROW)
 

@@ -1,5 +1,5 @@
 // fp32 kernels, op(A)(i,k) = A[i*lda + k], and the table of instantiated tiles.
-#include "gemm_kernel.h"
+#include "gemm_tiles.h"
 
 TSG_DEFINE_MODE(launch_f32_row, TSG_F32_TILES, A_ROW)
 
