@@ -50,3 +50,16 @@ def test_reduce_record_is_priced_against_hbm():
     out = _record(7, with_search=False)
     assert out["roofline"]["bound"] == "hbm" and out["roofline"]["peak"] == 8000.0 and out["unit"] == "GB/s"
     assert "search" not in out
+
+
+def test_traffic_table_covers_every_workload_and_names_existing_summaries():
+    """Each workload has at least one measured-traffic entry, taken from a summary that is in
+    the tree; an entry is only reported while the kernel sources hash to what it was taken with."""
+    import os
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    assert sorted(bench.TRAFFIC) == list(range(1, 12))
+    for k, entries in bench.TRAFFIC.items():
+        assert entries
+        for e in entries:
+            assert e["bytes"] > 0 and len(e["kernel_hash"]) == 16
+            assert os.path.isfile(os.path.join(root, e["source"])), e["source"]
