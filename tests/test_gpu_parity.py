@@ -792,6 +792,47 @@ def test_bench_launch_configurations_of_the_small_workloads_full_size(workspace)
             check(C[b], A[b], B[b], dt, exact=exact)
 
 
+def test_bench_launch_configurations_of_configs_1_2_and_8_full_size():
+    """The other tile configs the tuner settles on, pinned, at the workloads' full sizes: the
+    16 x 16 block form for 256^3 (either raster), 64 x 64 tiles with a k step of 64 (three stages)
+    or 32 (four stages) for A^T B at 1024^3, and the 64 x 64 x 64 bf16 tile for the bf16 layer.
+    Integer data bit for bit, then the workload's own data within tolerance."""
+    dt = tsg.F32
+    for raster in (0, 1):
+        cfg = tsg.TileConfig(bm=16, bn=16, bk=64, wm=16, wn=16, vec=4, raster=raster, sched=1, split_k=1, split_tail=0, mfma=1)
+        tsg.tile_config_set(tsg.OP_GEMM, dt, cfg)
+        Ai, Bi = synth.gemm_inputs(256, 256, 256, seed=0, dist="ints")
+        Ci = run_gemm(dt, Ai, Bi, flags=tsg.STRICT)
+        assert tsg.last_launch().config.as_dict() == cfg.as_dict() and tsg.last_launch().edge == 0
+        check(Ci, Ai, Bi, dt, exact=True)
+        c, A, B = synth.config_inputs(1)
+        R, S = oracle.gemm(A, B)
+        gate("config 1, block form, raster %d" % raster, run_gemm(dt, A, B, flags=tsg.STRICT), R, S, TOL[dt])
+    tsg.tile_config_set(tsg.OP_GEMM, dt, None)
+    for bk, sched in ((64, 4), (32, 5)):
+        cfg = tsg.TileConfig(bm=64, bn=64, bk=bk, wm=32, wn=32, vec=4, raster=1, sched=sched, split_k=1, split_tail=0)
+        tsg.tile_config_set(tsg.OP_GEMM_TRANSA, dt, cfg)
+        Ai, Bi = synth.gemm_inputs(1024, 1024, 1024, seed=1, dist="ints", trans_a=True)
+        Ci = run_gemm(dt, Ai, Bi, trans_a=True, flags=tsg.STRICT)
+        assert tsg.last_launch().config.as_dict() == cfg.as_dict()
+        check(Ci, Ai, Bi, dt, trans_a=True, exact=True)
+        c, A, B = synth.config_inputs(2)
+        R, S = oracle.gemm(A, B, trans_a=True)
+        gate("config 2, 64 x 64 x %d" % bk, run_gemm(dt, A, B, trans_a=True, flags=tsg.STRICT), R, S, TOL[dt])
+    tsg.tile_config_set(tsg.OP_GEMM_TRANSA, dt, None)
+    bt = tsg.BF16_F32ACC
+    cfg = tsg.TileConfig(bm=64, bn=64, bk=64, wm=32, wn=32, vec=8, raster=0, sched=4, split_k=1, split_tail=0)
+    tsg.tile_config_set(tsg.OP_CONV2D_NHWC, bt, cfg)
+    xi, wi = synth.conv_inputs(8, 56, 56, 64, 64, 3, 3, seed=8, dist="ints")
+    xb, wb = synth.f32_to_bf16_bits(xi), synth.f32_to_bf16_bits(wi)
+    yi = run_conv(bt, xb, wb, (1, 1), (1, 1), flags=tsg.STRICT)
+    assert tsg.last_launch().config.as_dict() == cfg.as_dict()
+    assert np.array_equal(yi.astype(np.float64), oracle.conv2d_nhwc(xb, wb, pad=(1, 1), with_s=False))
+    c, x, w = synth.config_inputs(8)
+    R, S = oracle.conv2d_nhwc(x, w, pad=(1, 1))
+    gate("config 8, tuned tile", run_conv(bt, x, w, (1, 1), (1, 1), flags=tsg.STRICT), R, S, TOL[bt])
+
+
 def test_config5_bf16_gemm_8192_negated_full_oracle():
     """bf16 8192^3 with the negate fused: every element against the oracle on the workload's own
     data; integer-valued operands at full size, bit for bit (any indexing, swizzle or
