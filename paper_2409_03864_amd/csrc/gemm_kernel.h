@@ -1128,8 +1128,13 @@ __global__ void __launch_bounds__(T::NT, T::MINW) gemm_direct_kernel(const KArgs
             }
             // Behind the MFMAs of this group: first the fragments of the next one, all of them within
             // the first quarter of the group (a wave that is alone on its SIMD has nobody to hide an
-            // LDS wait behind), then, in a step's last group, the loads of tile kt+D.
-            constexpr int FQ = NM / 4 > 0 ? NM / 4 : 1;
+            // LDS wait behind), then, in a step's last group, the loads of tile kt+D.  Where the reads
+            // fall among the MFMAs moves a kernel by up to 13 %, and not monotonically: the quarter is
+            // the best of the spreads measured (all behind the first MFMA, an eighth, a quarter, a half,
+            // the whole group) for every fp32 tile; the four-stage bf16 tiles, whose group is 8 or 16
+            // long MFMAs, do 2 % better with the reads over the first half.
+            constexpr int FDIV = (E::TPG == 1 && T::SCHED == 5) ? 2 : 4;
+            constexpr int FQ = NM / FDIV > 0 ? NM / FDIV : 1;
             constexpr int FPER = (NFRAG + FQ - 1) / FQ;      // fragment reads behind one MFMA
             constexpr int FM = (NFRAG + FPER - 1) / FPER;    // MFMAs that carry them
             constexpr int LM = NM - FM > 0 ? NM - FM : 1;    // MFMAs that carry loads: the rest, or the last one
