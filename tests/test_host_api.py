@@ -25,6 +25,36 @@ def test_library_exports_every_declared_symbol():
     assert tsg.version() >= 1
 
 
+def test_public_header_is_plain_c_and_links_against_the_library(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 (and as C++), and a C program that
+    only uses host-side entry points must link against the built library and run without a GPU."""
+    import os, shutil, subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    inc, libdir = os.path.join(root, "include"), os.path.join(root, "paper_2409_03864_amd")
+    src = tmp_path / "use_tsg.c"
+    src.write_text(
+        '#include "tsg.h"\n#include <stdio.h>\n'
+        "int main(void) {\n"
+        "    int64_t main_part = 0, rest = 0, tiles = 0;\n"
+        "    if (tsg_split(2042, 8, &main_part, &rest, &tiles) != TSG_OK) return 1;\n"
+        '    printf("%lld %lld %lld %s\\n", (long long)main_part, (long long)rest, (long long)tiles, tsg_status_string(TSG_E_SILENCEABLE));\n'
+        "    return tsg_tile_config_count(TSG_OP_GEMM, TSG_F32) > 0 ? 0 : 2;\n}\n")
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    subprocess.check_call([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-I", inc, str(src)])
+    gxx = shutil.which("g++")
+    if gxx:
+        subprocess.check_call([gxx, "-std=c++11", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c++",
+                               "-I", inc, str(src)])
+    exe = tmp_path / "use_tsg"
+    subprocess.check_call([gcc, "-std=c99", "-I", inc, str(src), "-o", str(exe), "-L", libdir, "-ltsg",
+                           "-Wl,-rpath," + libdir])
+    out = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
+    assert out.returncode == 0, out.stderr
+    assert out.stdout.split()[:3] == ["2040", "2", "255"]     # Fig. 1: 2042 = 255 * 8 + 2
+
+
 def test_split_matches_paper_and_oracle(golden_dir):
     for line in open(os.path.join(golden_dir, "paper_split_examples.txt")):
         line = line.split("#")[0].split()
