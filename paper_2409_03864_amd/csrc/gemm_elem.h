@@ -139,5 +139,43 @@ struct BF16 {
     static __device__ __forceinline__ int acc_row(int r, int lane) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
 };
 
+// bfloat16 operands, v_mfma_f32_16x16x32_bf16: wave tiles in 16-row steps, as F32B16 for fp32.  Lane
+// slot q = lane / 16 feeds k = 8 q .. 8 q + 7 of the one MFMA of a 32-wide k group, so a k-contiguous
+// row is one 16-byte read per MFMA.  A [k][j] tile is fetched with the same transposing read as BF16:
+// a 16-lane group covers the 16 columns of the block and four rows of k per read, two reads per fragment.
+struct BF16B16 {
+    using elem = u16;
+    using chunk = u16x8;
+    using chunk_u = u16x8_u;
+    using frag = bf16x8;
+    using acc_t = f32x4;
+    static constexpr int V = 8;
+    static constexpr int BLK = 16;
+    static constexpr int LK = 4;
+    static constexpr int KG = 32;
+    static constexpr int TPG = 1;
+    static constexpr int NRJ = 2;
+    static constexpr int NACC = 4;
+    static constexpr int PAD_K = 8, PAD_J = 32;
+    static constexpr bool kHasGeneral = false;   // exists in the direct-to-LDS forms only
+    static __device__ __forceinline__ chunk zero() { return chunk{0, 0, 0, 0, 0, 0, 0, 0}; }
+    static __device__ __forceinline__ int swz_j(int krow) { return (krow & 3) << 1; }
+    // half h of a [k][j] fragment: k = k0 + 8 (lane / 16) + 4 h .. + 3, column col0 + lane % 16
+    static __device__ __forceinline__ void read_j(frag& f, int h, const elem* tile, int ld, int k0, int col0, int lane,
+                                                  bool swizzled) {
+        const int krow = k0 + 8 * (lane >> 4) + ((lane & 15) >> 2) + 4 * h;
+        const int c = col0 + 4 * (lane & 3);
+        const elem* p0 = tile + krow * ld + (swizzled ? ((((c >> 3) ^ swz_j(krow)) << 3) | (c & 7)) : c);
+        const bf16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr)(p0));
+        const bf16x4 lo = h == 0 ? v : __builtin_shufflevector(f, f, 0, 1, 2, 3);
+        const bf16x4 hi = h == 1 ? v : __builtin_shufflevector(f, f, 4, 5, 6, 7);
+        f = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    }
+    static __device__ __forceinline__ acc_t mfma(const frag& a, const frag& b, const acc_t& c, int) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ int acc_row(int r, int lane) { return 4 * (lane >> 4) + r; }
+};
+
 }  // namespace
 }  // namespace tsg

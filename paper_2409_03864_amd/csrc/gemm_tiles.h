@@ -46,7 +46,10 @@
     X(BF16, 256, 256, 32, 128, 64, 2, 4)   \
     X(BF16, 256, 256, 32, 128, 64, 2, 5)   \
     X(BF16, 256, 256, 32, 128, 128, 1, 4)  \
-    X(BF16, 256, 256, 32, 128, 128, 1, 5)
+    X(BF16, 256, 256, 32, 128, 128, 1, 5)  \
+    X(BF16B16, 112, 64, 64, 112, 16, 1, 4) \
+    X(BF16B16, 112, 64, 32, 112, 16, 2, 5) \
+    X(BF16B16, 64, 64, 64, 64, 16, 2, 4)
 #define TSG_BF16_TILES(X) TSG_BF16_TILES_A(X) TSG_BF16_TILES_B(X)
 #define TSG_COUNT_TILE(el, bm, bn, bk, wm, wn, mw, sc) +1
 

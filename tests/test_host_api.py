@@ -94,7 +94,7 @@ def test_search_space_enumeration():
             for i in range(n):
                 c = tsg.tile_config_enum(op, dt, i)
                 blk = 16 if c.mfma else 32
-                assert c.mfma in (0, 1) and (dt == tsg.F32 or c.mfma == 0)
+                assert c.mfma in (0, 1)
                 assert c.bm % c.wm == 0 and c.bn % c.wn == 0 and c.wm % blk == 0 and c.wn % blk == 0
                 # the block form: one MFMA block per workgroup, fp32 only
                 assert c.sched != 1 or (dt == tsg.F32 and c.bm == c.bn == c.wm == c.wn == blk)
