@@ -31,22 +31,22 @@ METRIC = "TFLOP/s and % of MI355X matrix peak, fp32 GEMM 4096^3 (1 GPU)"
 # An entry is reported only while the kernel sources still hash to the value it was taken
 # with and the launch uses the same tile config; otherwise `traffic` is null.
 TRAFFIC = {
-    1: [{"kernel_hash": "510f50857de72af8", "tile": {"bm": 16, "bn": 16, "bk": 64, "wm": 16, "wn": 16, "vec": 4, "sched": 1, "split_k": 1, "split_tail": 0, "mfma": 1}, "bytes": 2981480, "source": "profiles/gemm_f32_256.txt"}],
-    2: [{"kernel_hash": "510f50857de72af8", "tile": {"bm": 64, "bn": 64, "bk": 64, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0, "mfma": 0}, "bytes": 42108523, "source": "profiles/gemm_f32_transA_1024.txt"},
-        {"kernel_hash": "510f50857de72af8", "tile": {"bm": 64, "bn": 64, "bk": 64, "wm": 32, "wn": 32, "vec": 4, "raster": 1, "sched": 4, "split_k": 1, "split_tail": 0, "mfma": 0}, "bytes": 29527043, "source": "profiles/gemm_f32_transA_1024.txt"}],
-    3: [{"kernel_hash": "510f50857de72af8", "tile": {"bm": 256, "bn": 256, "bk": 16, "wm": 128, "wn": 64, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0, "mfma": 0}, "bytes": 719689088, "source": "profiles/gemm_f32_4096.txt"},
-        {"kernel_hash": "510f50857de72af8", "tile": {"bm": 256, "bn": 256, "bk": 16, "wm": 128, "wn": 64, "vec": 4, "raster": 1, "sched": 4, "split_k": 1, "split_tail": 0, "mfma": 0}, "bytes": 470066882, "source": "profiles/gemm_f32_4096.txt"}],
-    4: [{"kernel_hash": "510f50857de72af8", "tile": {"bm": 112, "bn": 64, "bk": 64, "wm": 112, "wn": 16, "vec": 4, "raster": 1, "sched": 4, "split_k": 1, "split_tail": 0, "mfma": 1}, "bytes": 14324806, "source": "profiles/conv2d_f32_8x56x56x64.txt"},
-        {"kernel_hash": "510f50857de72af8", "tile": {"bm": 112, "bn": 64, "bk": 64, "wm": 112, "wn": 16, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0, "mfma": 1}, "bytes": 20517200, "source": "profiles/conv2d_f32_8x56x56x64.txt"}],
-    5: [{"kernel_hash": "e77faea4fd82ad85", "tile": {"bm": 256, "bn": 256, "bk": 32, "wm": 128, "wn": 64, "vec": 8, "raster": 1, "sched": 5, "split_k": 1, "split_tail": 0, "mfma": 0}, "bytes": 1886853973, "source": "profiles/gemm_bf16_8192_negate.txt"},
-        {"kernel_hash": "e77faea4fd82ad85", "tile": {"bm": 256, "bn": 256, "bk": 32, "wm": 128, "wn": 64, "vec": 8, "raster": 0, "sched": 5, "split_k": 1, "split_tail": 0, "mfma": 0}, "bytes": 1883839785, "source": "profiles/gemm_bf16_8192_negate.txt"}],
-    6: [{"kernel_hash": "510f50857de72af8", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "sched": 4, "split_k": 5, "split_tail": 0, "mfma": 0}, "bytes": 91768623, "source": "profiles/gemm_f32_batched_196x256x2305.txt"}],
+    1: [{"kernel_hash": "3c08264ebc31e41c", "tile": {"bm": 16, "bn": 16, "bk": 64, "wm": 16, "wn": 16, "vec": 4, "sched": 1, "split_k": 1, "split_tail": 0, "mfma": 1}, "bytes": 2981485, "source": "profiles/gemm_f32_256.txt"}],
+    2: [{"kernel_hash": "3c08264ebc31e41c", "tile": {"bm": 64, "bn": 64, "bk": 64, "wm": 32, "wn": 32, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0, "mfma": 0}, "bytes": 42108508, "source": "profiles/gemm_f32_transA_1024.txt"},
+        {"kernel_hash": "3c08264ebc31e41c", "tile": {"bm": 64, "bn": 64, "bk": 64, "wm": 32, "wn": 32, "vec": 4, "raster": 1, "sched": 4, "split_k": 1, "split_tail": 0, "mfma": 0}, "bytes": 29527140, "source": "profiles/gemm_f32_transA_1024.txt"}],
+    3: [{"kernel_hash": "3c08264ebc31e41c", "tile": {"bm": 256, "bn": 256, "bk": 16, "wm": 128, "wn": 64, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0, "mfma": 0}, "bytes": 719853268, "source": "profiles/gemm_f32_4096.txt"},
+        {"kernel_hash": "3c08264ebc31e41c", "tile": {"bm": 256, "bn": 256, "bk": 16, "wm": 128, "wn": 64, "vec": 4, "raster": 1, "sched": 4, "split_k": 1, "split_tail": 0, "mfma": 0}, "bytes": 470069052, "source": "profiles/gemm_f32_4096.txt"}],
+    4: [{"kernel_hash": "3c08264ebc31e41c", "tile": {"bm": 112, "bn": 64, "bk": 64, "wm": 112, "wn": 16, "vec": 4, "raster": 1, "sched": 4, "split_k": 1, "split_tail": 0, "mfma": 1}, "bytes": 14324840, "source": "profiles/conv2d_f32_8x56x56x64.txt"},
+        {"kernel_hash": "3c08264ebc31e41c", "tile": {"bm": 112, "bn": 64, "bk": 64, "wm": 112, "wn": 16, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0, "mfma": 1}, "bytes": 20517259, "source": "profiles/conv2d_f32_8x56x56x64.txt"}],
+    5: [{"kernel_hash": "1dda433397d07fd1", "tile": {"bm": 256, "bn": 256, "bk": 32, "wm": 128, "wn": 64, "vec": 8, "raster": 1, "sched": 5, "split_k": 1, "split_tail": 0, "mfma": 0}, "bytes": 1887849981, "source": "profiles/gemm_bf16_8192_negate.txt"},
+        {"kernel_hash": "1dda433397d07fd1", "tile": {"bm": 256, "bn": 256, "bk": 32, "wm": 128, "wn": 64, "vec": 8, "raster": 0, "sched": 5, "split_k": 1, "split_tail": 0, "mfma": 0}, "bytes": 1880683579, "source": "profiles/gemm_bf16_8192_negate.txt"}],
+    6: [{"kernel_hash": "3c08264ebc31e41c", "tile": {"bm": 64, "bn": 64, "bk": 32, "wm": 32, "wn": 32, "vec": 4, "sched": 4, "split_k": 5, "split_tail": 0, "mfma": 0}, "bytes": 91766100, "source": "profiles/gemm_f32_batched_196x256x2305.txt"}],
     7: [{"kernel_hash": "ad97f1a93881e1ca", "tile": {}, "bytes": 1073704569, "source": "profiles/reduce_sum_f32_1gib.txt"}],
-    8: [{"kernel_hash": "e77faea4fd82ad85", "tile": {"bm": 64, "bn": 64, "bk": 64, "wm": 32, "wn": 32, "vec": 8, "sched": 4, "split_k": 1, "split_tail": 0, "mfma": 0}, "bytes": 15995805, "source": "profiles/conv2d_bf16_8x56x56x64.txt"}],
-    9: [{"kernel_hash": "510f50857de72af8", "tile": {"bm": 256, "bn": 256, "bk": 16, "wm": 128, "wn": 64, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0, "mfma": 0}, "bytes": 671357805, "source": "profiles/gemm_f32_both_transposed_4096.txt"},
-        {"kernel_hash": "510f50857de72af8", "tile": {"bm": 256, "bn": 256, "bk": 16, "wm": 128, "wn": 64, "vec": 4, "raster": 1, "sched": 4, "split_k": 1, "split_tail": 0, "mfma": 0}, "bytes": 470039469, "source": "profiles/gemm_f32_both_transposed_4096.txt"}],
-    10: [{"kernel_hash": "510f50857de72af8", "tile": {"bm": 112, "bn": 64, "bk": 64, "wm": 112, "wn": 16, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0, "mfma": 1}, "bytes": 27123293, "source": "profiles/conv2d_f32_window_accumulate.txt"},
-        {"kernel_hash": "510f50857de72af8", "tile": {"bm": 112, "bn": 64, "bk": 64, "wm": 112, "wn": 16, "vec": 4, "raster": 1, "sched": 4, "split_k": 1, "split_tail": 0, "mfma": 1}, "bytes": 20930886, "source": "profiles/conv2d_f32_window_accumulate.txt"}],
+    8: [{"kernel_hash": "1dda433397d07fd1", "tile": {"bm": 64, "bn": 64, "bk": 64, "wm": 32, "wn": 32, "vec": 8, "sched": 4, "split_k": 1, "split_tail": 0, "mfma": 0}, "bytes": 15995806, "source": "profiles/conv2d_bf16_8x56x56x64.txt"}],
+    9: [{"kernel_hash": "3c08264ebc31e41c", "tile": {"bm": 256, "bn": 256, "bk": 16, "wm": 128, "wn": 64, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0, "mfma": 0}, "bytes": 671356715, "source": "profiles/gemm_f32_both_transposed_4096.txt"},
+        {"kernel_hash": "3c08264ebc31e41c", "tile": {"bm": 256, "bn": 256, "bk": 16, "wm": 128, "wn": 64, "vec": 4, "raster": 1, "sched": 4, "split_k": 1, "split_tail": 0, "mfma": 0}, "bytes": 470040369, "source": "profiles/gemm_f32_both_transposed_4096.txt"}],
+    10: [{"kernel_hash": "3c08264ebc31e41c", "tile": {"bm": 112, "bn": 64, "bk": 64, "wm": 112, "wn": 16, "vec": 4, "raster": 0, "sched": 4, "split_k": 1, "split_tail": 0, "mfma": 1}, "bytes": 27123352, "source": "profiles/conv2d_f32_window_accumulate.txt"},
+        {"kernel_hash": "3c08264ebc31e41c", "tile": {"bm": 112, "bn": 64, "bk": 64, "wm": 112, "wn": 16, "vec": 4, "raster": 1, "sched": 4, "split_k": 1, "split_tail": 0, "mfma": 1}, "bytes": 20930914, "source": "profiles/conv2d_f32_window_accumulate.txt"}],
     11: [{"kernel_hash": "ad97f1a93881e1ca", "tile": {}, "bytes": 805369830, "source": "profiles/reduce_sum_f32_view_of_short_rows.txt"}],
 }
 
