@@ -121,6 +121,11 @@ enum {
  *                tile loop itself (Fig. 8 applied at the grid level), for tile counts just
  *                above a multiple of 256.  Needs split_k > 1 and a tile count (per batch
  *                entry) that is not a multiple of 256, else silenceable.
+ *   mfma       : the MFMA block the wavefront tiles are built from, i.e. the fixed-size inner
+ *                matmul of Fig. 8: 0 = 32 x 32 outputs per instruction (32x32x2 fp32,
+ *                32x32x16 bf16), 1 = 16 x 16 (16x16x4 fp32, 16x16x32 bf16), which lets wm and wn
+ *                move in steps of 16 for extents that a 32-row block would pad (112-row tiles
+ *                for 56-pixel image rows).  Part of a tile's identity, like sched.
  */
 typedef struct {
     int32_t bm, bn, bk;
