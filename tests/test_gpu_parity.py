@@ -1191,6 +1191,88 @@ def test_block_form_every_layout_variant_and_flag(blk, bk, mfma, trans_a, trans_
         tsg.workspace_set(None)
 
 
+def test_element_offsets_beyond_32_bits():
+    """Maximum sizes: leading dimensions and batch strides so large that element offsets pass 2^31
+    (and byte offsets 2^33) in every operand, for each kernel form; the operands live in sparse
+    views of large device buffers and the result is exact on integers."""
+    dt, op = tsg.F32, tsg.OP_GEMM
+    M, N, K = 300, 200, 96
+    lda, ldb, ldc = (1 << 23) + 1, (1 << 25) + 3, (1 << 23) + 5     # 299 * lda, 95 * ldb, 299 * ldc > 2^31
+    A, B = synth.gemm_inputs(M, N, K, seed=91, dist="ints")
+    R = oracle.gemm(A, B, with_s=False)
+    bufA = torch.zeros((M - 1) * lda + K, dtype=torch.float32, device=DEV)
+    bufB = torch.zeros((K - 1) * ldb + N, dtype=torch.float32, device=DEV)
+    bufA.as_strided((M, K), (lda, 1)).copy_(torch.from_numpy(A))
+    bufB.as_strided((K, N), (ldb, 1)).copy_(torch.from_numpy(B))
+    configs = [tsg.TileConfig(bm=16, bn=16, bk=64, wm=16, wn=16, vec=4, raster=0, sched=1, split_k=1, mfma=1),
+               tsg.TileConfig(bm=64, bn=64, bk=32, wm=32, wn=32, vec=4, raster=0, sched=4, split_k=1),
+               tsg.TileConfig(bm=64, bn=64, bk=32, wm=32, wn=32, vec=4, raster=1, sched=0, split_k=1),
+               tsg.TileConfig(bm=64, bn=64, bk=32, wm=32, wn=32, vec=1, raster=0, sched=0, split_k=1)]
+    for cfg in configs:
+        bufC = torch.full(((M - 1) * ldc + N,), -3.0, dtype=torch.float32, device=DEV)
+        tsg.tile_config_set(op, dt, cfg)
+        tsg.gemm(dt, M, N, K, bufA, lda, bufB, ldb, bufC, ldc, tsg.STRICT)
+        torch.cuda.synchronize()
+        assert tsg.last_launch().config.as_dict() == cfg.as_dict()
+        out = bufC.as_strided((M, N), (ldc, 1)).cpu().numpy()
+        assert np.array_equal(out.astype(np.float64), R), cfg
+        # nothing between the rows was touched (a sample of the gaps: the rows' neighbours)
+        gaps = bufC.as_strided((M - 1, 8), (ldc, 1), N).cpu().numpy()
+        assert np.all(gaps == np.float32(-3.0))
+        del bufC
+    del bufA, bufB
+    # batch strides beyond 2^31 elements, direct form with k split (the workspace is per batch entry)
+    tsg.tile_config_set(op, dt, None)
+    nb, M, N, K = 2, 70, 96, 260
+    stride = (1 << 31) + 16
+    A = synth.small_ints(92, 0, nb * M * K).reshape(nb, M, K)
+    B = synth.small_ints(92, 1, nb * K * N).reshape(nb, K, N)
+    bufA = torch.zeros(stride + M * K, dtype=torch.float32, device=DEV)
+    bufB = torch.zeros(stride + K * N, dtype=torch.float32, device=DEV)
+    bufC = torch.zeros(stride + M * N, dtype=torch.float32, device=DEV)
+    for b in range(nb):
+        bufA[b * stride:b * stride + M * K].copy_(torch.from_numpy(A[b]).reshape(-1))
+        bufB[b * stride:b * stride + K * N].copy_(torch.from_numpy(B[b]).reshape(-1))
+    ws = torch.empty(16 << 20, dtype=torch.uint8, device=DEV)
+    tsg.workspace_set(ws)
+    try:
+        for cfg in (tsg.TileConfig(bm=64, bn=64, bk=32, wm=32, wn=32, vec=4, raster=0, sched=4, split_k=3),
+                    tsg.TileConfig(bm=32, bn=32, bk=32, wm=32, wn=32, vec=4, raster=0, sched=1, split_k=1)):
+            bufC.zero_()
+            tsg.tile_config_set(op, dt, cfg)
+            tsg.gemm_batched(dt, False, nb, M, N, K, bufA, K, stride, bufB, N, stride, bufC, N, stride, tsg.STRICT)
+            torch.cuda.synchronize()
+            assert tsg.last_launch().config.as_dict() == cfg.as_dict()
+            for b in range(nb):
+                out = bufC[b * stride:b * stride + M * N].reshape(M, N).cpu().numpy()
+                assert np.array_equal(out.astype(np.float64), oracle.gemm(A[b], B[b], with_s=False)), (cfg, b)
+        del bufA, bufB, bufC
+        # the reduce over a view whose last row starts beyond 2^31 elements
+        rows, cols, ld = 300, 96, (1 << 23) + 1
+        x = synth.small_ints(93, 0, rows * cols).reshape(rows, cols)
+        bufX = torch.zeros((rows - 1) * ld + cols, dtype=torch.float32, device=DEV)
+        bufX.as_strided((rows, cols), (ld, 1)).copy_(torch.from_numpy(x))
+        out = torch.zeros(1, dtype=torch.float32, device=DEV)
+        tsg.reduce_sum(dt, rows, cols, bufX, ld, out)
+        torch.cuda.synchronize()
+        assert float(out.item()) == float(x.astype(np.float64).sum())
+        del bufX
+        # a convolution written into a window whose image stride is beyond 2^31 elements
+        Nb, H, W, Cin, Cout = 2, 6, 6, 8, 16
+        xi, wi = synth.conv_inputs(Nb, H, W, Cin, Cout, 3, 3, seed=94, dist="ints")
+        Ry = oracle.conv2d_nhwc(xi, wi, pad=(1, 1), with_s=False)
+        sw_, sh_, sn_ = Cout, 1 << 20, (1 << 31) + 64
+        bufY = torch.full(((Nb - 1) * sn_ + (H - 1) * sh_ + W * sw_ + 8,), 5.0, dtype=torch.float32, device=DEV)
+        tsg.conv2d_nhwc_window(dt, Nb, H, W, Cin, Cout, 3, 3, 1, 1, 1, 1, dev(xi), dev(wi), bufY, sn_, sh_, sw_, 0)
+        torch.cuda.synchronize()
+        got = bufY.as_strided((Nb, H, W, Cout), (sn_, sh_, sw_, 1)).cpu().numpy()
+        assert np.array_equal(got.astype(np.float64), Ry)
+        assert bool((bufY.as_strided((Nb, H, 8), (sn_, sh_, 1), W * sw_) == 5.0).all())
+    finally:
+        torch.cuda.synchronize()
+        tsg.workspace_set(None)
+
+
 def test_measurement_aids_return_plausible_figures_and_validate_arguments():
     """tsg_launch_floor and tsg_mfma_ceiling are measurement aids, not part of the path: they must
     reject bad arguments, run, and report figures below the published peaks."""
